@@ -1,0 +1,183 @@
+/*
+ * adsa.h -- C ABI of the MI355X (gfx950) ADSA decode library.
+ *
+ * One call processes ONE transformer layer for a batch of independent
+ * sequences: the per-step decode attention of Adaptive Dynamic Sparse Attention
+ * (paper Section 4.1) restricted to prefix + local window + globally ranked
+ * tokens, and the dynamic KV-cache update that evicts and compacts
+ * (Section 4.2).  Every entry point only ENQUEUES work on the caller's HIP
+ * stream: no host synchronisation, no allocation, no global state.  The
+ * library never touches host memory behind the pointers it is given except
+ * `adsa_params` (a host struct, read during the call).
+ *
+ * Pointers are DEVICE pointers owned by the caller unless marked [host].
+ * Return value: ADSA_OK or a negative adsa_status; argument errors are found
+ * on the host before anything is launched.  Conditions only the device can see
+ * (a full cache, a malformed state) set `adsa_seq.status` of that sequence,
+ * which the caller reads when it next synchronises; such a sequence is left
+ * unchanged and its output row is zero-filled.
+ *
+ * Cache layout.  Element (slot, head, d) of a sequence's K (same for V) lives
+ * at  k + slot*kv_slot_stride + head*kv_head_stride + d  (strides in
+ * elements).  [slot][head][D] (slot stride = n_heads*head_dim, head stride =
+ * head_dim) makes a gathered token one contiguous burst and is the fast path;
+ * [head][slot][D] is expressible too.  Base pointers must be 16-byte aligned
+ * and both strides multiples of 16 bytes.
+ *
+ * Decode-step convention.  `step` = s = number of image tokens in the context
+ * INCLUDING the query token; the query token is image token s-1, at grid cell
+ * (row, col) = ((s-1) / grid_w, (s-1) % grid_w) and absolute position
+ * grid_origin + s - 1.  s = 0 means the query is the last prefix token
+ * (nothing is appended).  0 <= s <= grid_h*grid_w.  A sequence with step < 0
+ * is inactive and skipped.
+ */
+#ifndef ADSA_H
+#define ADSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ADSA_VERSION 1
+#define ADSA_MAX_CAP 8192      /* largest `cap` (slots per sequence) the select/compact kernels accept */
+
+typedef enum {
+  ADSA_OK = 0,
+  ADSA_ERR_NULL = -1,          /* a required pointer is NULL */
+  ADSA_ERR_SHAPE = -2,         /* a size or window parameter is out of range */
+  ADSA_ERR_DTYPE = -3,         /* unknown dtype / score mode */
+  ADSA_ERR_ALIGN = -4,         /* pointer or stride not 16-byte aligned */
+  ADSA_ERR_CAPACITY = -5,      /* cap or sel_cap too small / above ADSA_MAX_CAP */
+  ADSA_ERR_WORKSPACE = -6,     /* workspace missing or smaller than adsa_workspace_bytes() */
+  ADSA_ERR_LAUNCH = -7,        /* the HIP runtime refused a launch */
+  ADSA_ERR_UNSUPPORTED = -8    /* valid request this build does not implement */
+} adsa_status;
+
+typedef enum { ADSA_F32 = 0, ADSA_BF16 = 1 } adsa_dtype;
+
+/* How the "previous" tokens are ranked for Eq. 4 (which K of them are kept). */
+typedef enum {
+  ADSA_SCORE_ATTN_MASS = 0,    /* accumulated softmax probability received so far; keep LARGEST */
+  ADSA_SCORE_VCOS = 1,         /* mean pairwise cosine of V (Eq. 2-3) over the candidates; keep SMALLEST */
+  ADSA_SCORE_EXT_LARGEST = 2,  /* caller-maintained score[]; keep largest */
+  ADSA_SCORE_EXT_SMALLEST = 3  /* caller-maintained score[]; keep smallest */
+} adsa_score_mode;
+
+/* Device-side per-sequence status bits (adsa_seq.status). */
+#define ADSA_SEQ_OK            0
+#define ADSA_SEQ_CACHE_FULL    1   /* append would exceed cap */
+#define ADSA_SEQ_BAD_STATE     2   /* n_res/step out of range, or an entry newer than the query */
+#define ADSA_SEQ_SEL_OVERFLOW  4   /* attended set larger than sel_cap */
+
+/* adsa_step / adsa_attend flags. */
+#define ADSA_FLAG_NO_COMPACT   1u  /* caller guarantees no sequence closes a grid row in this step */
+#define ADSA_FLAG_NO_ACCUMULATE 2u /* adsa_attend: do not add attention mass to score[] */
+
+/* [host] Launch-wide parameters (Section 4.1's n, m, K and the problem shape). */
+typedef struct adsa_params {
+  int32_t n_seq;               /* sequences in this launch (>= 1) */
+  int32_t n_heads;             /* query heads == key/value heads */
+  int32_t head_dim;            /* 64 or 128 */
+  int32_t grid_h, grid_w;      /* image-token grid H x W, raster order */
+  int32_t win_rows_back;       /* R: rows above the query's row that belong to the local window */
+  int32_t win_col_radius;      /* w: column radius in those rows; w >= grid_w-1 gives the paper's
+                                  1-D "most recent m tokens" window */
+  int32_t sel_groups;          /* 1: one attended set per sequence shared by all heads */
+  int32_t dtype;               /* adsa_dtype of q, K, V, out */
+  int32_t score_mode;          /* adsa_score_mode */
+  int32_t cap;                 /* slots allocated per sequence (<= ADSA_MAX_CAP) */
+  int32_t sel_cap;             /* entries per row of sel_idx */
+  int64_t kv_slot_stride;      /* elements */
+  int64_t kv_head_stride;      /* elements */
+  float   softmax_scale;       /* 0 => 1/sqrt(head_dim) */
+  int32_t reserved;
+} adsa_params;
+
+/* Device array of n_seq entries: the ragged per-sequence state.  The kernels read AND update
+   n_res, step, status, compacted, so one launch serves sequences at different positions. */
+typedef struct adsa_seq {
+  void*    k;                  /* this sequence's K cache (dtype elements) */
+  void*    v;                  /* this sequence's V cache */
+  int32_t* pos;                /* [cap] absolute position of each resident slot, strictly ascending */
+  float*   score;              /* [cap] ranking score of each resident slot */
+  int32_t  n_res;              /* resident slots */
+  int32_t  step;               /* s (see the decode-step convention above); < 0: inactive */
+  int32_t  grid_origin;        /* P: absolute position of image token 0 (= prefix length) */
+  int32_t  n_keep_prefix;      /* positions below this are pinned (never ranked, never evicted) */
+  int32_t  budget;             /* B: global tokens kept, when budget_den == 0 */
+  int32_t  budget_num;         /* else B = floor((P + s) * budget_num / budget_den) */
+  int32_t  budget_den;
+  int32_t  status;             /* ADSA_SEQ_* bits, set by the device, cleared by the caller */
+  int32_t  compacted;          /* 1 if the last adsa_step/adsa_compact evicted+compacted this sequence */
+  int32_t  reserved[3];
+} adsa_seq;
+
+/* Bytes of device scratch the attend/step entry points need for these parameters. */
+size_t adsa_workspace_bytes(const adsa_params* p);
+
+/*
+ * Eq. 1 + Eq. 4: partition every sequence's resident slots into prefix / local / candidate for
+ * the query of its current `step`, rank the candidates, and write the attended set
+ *   PREFIX u LOCAL u top-min(B, |candidates|)
+ * as an ascending slot list.  Ties go to the lower slot; -0 == +0; NaN scores are a
+ * precondition violation.  Reads seqs[].pos/score/n_res/step; VCOS mode first writes Eq. 3's
+ * S_i into score[] at the candidate slots (reads V).
+ *   sel_idx  int32 [n_seq][sel_cap]   out
+ *   sel_cnt  int32 [n_seq]            out
+ */
+int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Eq. 5 + attention: per sequence and head, softmax(q.K_sel^T * scale) V_sel over the slots
+ * listed in sel_idx (gathered in place, never materialised), fp32 accumulation.
+ *   q    dtype [n_seq][n_heads][head_dim]
+ *   out  dtype [n_seq][n_heads][head_dim]
+ *   lse  float [n_seq][n_heads]   natural-log sum-exp of the scaled logits
+ * Unless ADSA_FLAG_NO_ACCUMULATE is set and for ADSA_SCORE_ATTN_MASS only, score[slot] of every
+ * attended slot gains the probability it received summed over heads (ascending head order).
+ */
+int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const int32_t* sel_idx,
+                const int32_t* sel_cnt, void* out, float* lse, uint32_t flags,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Section 4.2 in per-row form.  For every sequence whose query token closes a grid row
+ * ((s-1) % grid_w == grid_w-1, s >= 1): keep the pinned prefix, the last R completed rows and
+ * the top min(B, |rest|) of the rest by the same ranking as adsa_select; write
+ *   keep_map int32 [n_seq][cap]: new slot of old slot i, or -1 (entries >= old n_res untouched)
+ * move K, V, pos, score rows to the front in place, order preserved, and set n_res, compacted.
+ * Other sequences are untouched (compacted = 0, keep_map row untouched).
+ */
+int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One whole decode step of one layer: append (k_new, v_new) of the query token at slot n_res
+ * (pos = P+s-1, score = 0; skipped when s == 0), select, attend, accumulate attention mass
+ * (ATTN_MASS), evict+compact the sequences that closed a row, then step += 1.
+ *   k_new, v_new  dtype [n_seq][n_heads][head_dim]
+ * Outputs as in the three calls above; keep_map may be NULL only with ADSA_FLAG_NO_COMPACT.
+ */
+int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
+              const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
+              int32_t* keep_map, uint32_t flags, void* workspace, size_t workspace_bytes,
+              void* stream);
+
+/* Timing hook for benchmarks: when enabled, adsa_attend/adsa_step bracket the attention kernel
+   with HIP events on the caller's stream.  adsa_profile_read synchronises those events and
+   returns, through its arguments, the number of bracketed launches and their summed duration
+   in milliseconds since the last adsa_profile_enable(1); [host] pointers. */
+int adsa_profile_enable(int on);
+int adsa_profile_read(int64_t* n_launches, double* total_ms);
+
+const char* adsa_strerror(int code);
+int adsa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

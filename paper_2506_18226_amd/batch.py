@@ -1,0 +1,112 @@
+"""Device-memory plumbing for one layer of an ADSA decode batch.
+
+`LayerBatch` owns the torch tensors the C ABI points into (K/V caches, pos, score, the
+`adsa_seq` device array, outputs, workspace) and converts host arrays to and from them.
+It performs no step of the method: every call below that computes anything goes through
+`binding.adsa_*`.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .workloads import bf16_bits
+
+
+def to_device(x: np.ndarray, dtype_code: int, device) -> torch.Tensor:
+    """float32 host values (already representable in the storage type) -> device tensor."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if dtype_code == B.F32:
+        return torch.from_numpy(x).to(device)
+    bits = torch.from_numpy(bf16_bits(x).view(np.int16)).to(device)
+    return bits.view(torch.bfloat16)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """Device tensor (f32 or bf16) -> float32 numpy array."""
+    return t.detach().float().cpu().numpy()
+
+
+class LayerBatch:
+    def __init__(self, params: B.AdsaParams, device: str = "cuda:0", with_outputs: bool = True):
+        self.params = params
+        self.device = torch.device(device)
+        p = params
+        self.tdtype = torch.float32 if p.dtype == B.F32 else torch.bfloat16
+        n, cap, h, D = p.n_seq, p.cap, p.n_heads, p.head_dim
+        if p.kv_slot_stride != h * D or p.kv_head_stride != D:
+            raise ValueError("LayerBatch allocates the [slot][head][D] layout only")
+        dev = self.device
+        self.K = torch.zeros((n, cap, h, D), dtype=self.tdtype, device=dev)
+        self.V = torch.zeros((n, cap, h, D), dtype=self.tdtype, device=dev)
+        self.pos = torch.zeros((n, cap), dtype=torch.int32, device=dev)
+        self.score = torch.zeros((n, cap), dtype=torch.float32, device=dev)
+        self.seqs_host = np.zeros(n, dtype=B.SEQ_DTYPE)
+        elem = self.K.element_size()
+        for b in range(n):
+            s = self.seqs_host[b]
+            s["k"] = self.K.data_ptr() + b * cap * h * D * elem
+            s["v"] = self.V.data_ptr() + b * cap * h * D * elem
+            s["pos"] = self.pos.data_ptr() + b * cap * 4
+            s["score"] = self.score.data_ptr() + b * cap * 4
+            s["step"] = -1
+        self.seqs = torch.zeros(n * B.SEQ_DTYPE.itemsize, dtype=torch.uint8, device=dev)
+        if with_outputs:
+            self.out = torch.zeros((n, h, D), dtype=self.tdtype, device=dev)
+            self.lse = torch.zeros((n, h), dtype=torch.float32, device=dev)
+            self.sel_idx = torch.full((n, p.sel_cap), -1, dtype=torch.int32, device=dev)
+            self.sel_cnt = torch.zeros(n, dtype=torch.int32, device=dev)
+            self.keep_map = torch.full((n, cap), -3, dtype=torch.int32, device=dev)
+        ws = B.adsa_workspace_bytes(p)
+        if ws == 0:
+            raise B.AdsaError(-2, "adsa_workspace_bytes (invalid parameters)")
+        self.workspace = torch.zeros(ws, dtype=torch.uint8, device=dev)
+
+    # ---- host -> device
+    def set_sequence(self, b: int, *, k: np.ndarray, v: np.ndarray, pos: np.ndarray,
+                     score: Optional[np.ndarray], step: int, grid_origin: int,
+                     n_keep_prefix: Optional[int] = None, budget: int = 0, budget_num: int = 0,
+                     budget_den: int = 0) -> None:
+        n = len(pos)
+        p = self.params
+        if n > p.cap:
+            raise ValueError("more resident slots than cap")
+        if n:
+            self.K[b, :n] = to_device(k[:n], p.dtype, self.device)
+            self.V[b, :n] = to_device(v[:n], p.dtype, self.device)
+            self.pos[b, :n] = torch.from_numpy(np.ascontiguousarray(pos[:n], dtype=np.int32)).to(self.device)
+            sc = np.zeros(n, np.float32) if score is None else np.ascontiguousarray(score[:n], dtype=np.float32)
+            self.score[b, :n] = torch.from_numpy(sc).to(self.device)
+        s = self.seqs_host[b]
+        s["n_res"], s["step"], s["grid_origin"] = n, step, grid_origin
+        s["n_keep_prefix"] = grid_origin if n_keep_prefix is None else n_keep_prefix
+        s["budget"], s["budget_num"], s["budget_den"] = budget, budget_num, budget_den
+        s["status"], s["compacted"] = 0, 0
+
+    def upload_seqs(self) -> None:
+        raw = torch.from_numpy(self.seqs_host.view(np.uint8).reshape(-1).copy())
+        self.seqs.copy_(raw.to(self.device))
+
+    # ---- device -> host
+    def read_seqs(self) -> np.ndarray:
+        raw = self.seqs.cpu().numpy()
+        self.seqs_host = raw.view(B.SEQ_DTYPE).copy()
+        return self.seqs_host
+
+    # ---- thin forwards to the C ABI
+    def select(self, stream=None):
+        B.adsa_select(self.params, self.seqs, self.sel_idx, self.sel_cnt, self.workspace, stream)
+
+    def attend(self, q: torch.Tensor, flags: int = 0, stream=None):
+        B.adsa_attend(self.params, self.seqs, q, self.sel_idx, self.sel_cnt, self.out, self.lse,
+                      self.workspace, flags, stream)
+
+    def compact(self, stream=None):
+        B.adsa_compact(self.params, self.seqs, self.keep_map, self.workspace, stream)
+
+    def step(self, q, k_new, v_new, flags: int = 0, stream=None):
+        B.adsa_step(self.params, self.seqs, q, k_new, v_new, self.out, self.lse, self.sel_idx, self.sel_cnt,
+                    self.keep_map, self.workspace, flags, stream)

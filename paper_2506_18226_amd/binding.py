@@ -1,0 +1,182 @@
+"""ctypes binding of the ADSA HIP library: same names as include/adsa.h, marshalling only.
+
+Every function takes torch tensors (device memory) or raw integers for pointers, packs the
+host parameter struct and calls the C entry point.  No step of the decode path runs here.
+The library must be built (paper_2506_18226_amd/build.py) -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+SCORE_ATTN_MASS, SCORE_VCOS, SCORE_EXT_LARGEST, SCORE_EXT_SMALLEST = 0, 1, 2, 3
+FLAG_NO_COMPACT, FLAG_NO_ACCUMULATE = 1, 2
+SEQ_CACHE_FULL, SEQ_BAD_STATE, SEQ_SEL_OVERFLOW = 1, 2, 4
+MAX_CAP = 8192
+
+ERRORS = {0: "ADSA_OK", -1: "ADSA_ERR_NULL", -2: "ADSA_ERR_SHAPE", -3: "ADSA_ERR_DTYPE", -4: "ADSA_ERR_ALIGN",
+          -5: "ADSA_ERR_CAPACITY", -6: "ADSA_ERR_WORKSPACE", -7: "ADSA_ERR_LAUNCH", -8: "ADSA_ERR_UNSUPPORTED"}
+
+EXPORTS = ["adsa_workspace_bytes", "adsa_select", "adsa_attend", "adsa_compact", "adsa_step",
+           "adsa_profile_enable", "adsa_profile_read", "adsa_strerror", "adsa_version"]
+
+
+class AdsaParams(C.Structure):
+    """Mirror of `adsa_params` (host struct)."""
+    _fields_ = [
+        ("n_seq", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("grid_h", C.c_int32), ("grid_w", C.c_int32),
+        ("win_rows_back", C.c_int32), ("win_col_radius", C.c_int32),
+        ("sel_groups", C.c_int32), ("dtype", C.c_int32), ("score_mode", C.c_int32),
+        ("cap", C.c_int32), ("sel_cap", C.c_int32),
+        ("kv_slot_stride", C.c_int64), ("kv_head_stride", C.c_int64),
+        ("softmax_scale", C.c_float), ("reserved", C.c_int32),
+    ]
+
+
+# Mirror of `adsa_seq` (device struct array), 80 bytes per entry.
+SEQ_DTYPE = np.dtype([
+    ("k", np.uint64), ("v", np.uint64), ("pos", np.uint64), ("score", np.uint64),
+    ("n_res", np.int32), ("step", np.int32), ("grid_origin", np.int32), ("n_keep_prefix", np.int32),
+    ("budget", np.int32), ("budget_num", np.int32), ("budget_den", np.int32), ("status", np.int32),
+    ("compacted", np.int32), ("reserved", np.int32, (3,)),
+])
+assert SEQ_DTYPE.itemsize == 80
+
+
+class AdsaError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {ERRORS.get(code, code)} ({strerror(code)})")
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB_PATH
+
+
+def load_library() -> C.CDLL:
+    """dlopen the built HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise FileNotFoundError(f"{path} is missing: run `python -m paper_2506_18226_amd.build` "
+                                    "(or __graft_entry__.build()) first; there is no fallback path")
+        lib = C.CDLL(path)
+        vp, i32p, f32p = C.c_void_p, C.c_void_p, C.c_void_p
+        pp = C.POINTER(AdsaParams)
+        lib.adsa_workspace_bytes.restype = C.c_size_t
+        lib.adsa_workspace_bytes.argtypes = [pp]
+        lib.adsa_select.restype = C.c_int
+        lib.adsa_select.argtypes = [pp, vp, i32p, i32p, vp, C.c_size_t, vp]
+        lib.adsa_attend.restype = C.c_int
+        lib.adsa_attend.argtypes = [pp, vp, vp, i32p, i32p, vp, f32p, C.c_uint32, vp, C.c_size_t, vp]
+        lib.adsa_compact.restype = C.c_int
+        lib.adsa_compact.argtypes = [pp, vp, i32p, vp, C.c_size_t, vp]
+        lib.adsa_step.restype = C.c_int
+        lib.adsa_step.argtypes = [pp, vp, vp, vp, vp, vp, f32p, i32p, i32p, i32p, C.c_uint32, vp, C.c_size_t, vp]
+        lib.adsa_profile_enable.restype = C.c_int
+        lib.adsa_profile_enable.argtypes = [C.c_int]
+        lib.adsa_profile_read.restype = C.c_int
+        lib.adsa_profile_read.argtypes = [C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+        lib.adsa_strerror.restype = C.c_char_p
+        lib.adsa_strerror.argtypes = [C.c_int]
+        lib.adsa_version.restype = C.c_int
+        lib.adsa_version.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def _ptr(x) -> Optional[int]:
+    """Device pointer of a torch tensor, or the integer itself, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _nbytes(x) -> int:
+    return 0 if x is None else x.numel() * x.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise AdsaError(rc, where)
+
+
+def make_params(*, n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, dtype,
+                score_mode, cap, sel_cap=None, sel_groups=1, kv_slot_stride=None, kv_head_stride=None,
+                softmax_scale=0.0) -> AdsaParams:
+    """Fill `adsa_params`; strides default to the [slot][head][D] layout."""
+    if kv_head_stride is None:
+        kv_head_stride = head_dim
+    if kv_slot_stride is None:
+        kv_slot_stride = n_heads * head_dim
+    return AdsaParams(n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, sel_groups,
+                      dtype, score_mode, cap, cap if sel_cap is None else sel_cap,
+                      kv_slot_stride, kv_head_stride, softmax_scale, 0)
+
+
+def strerror(code: int) -> str:
+    return load_library().adsa_strerror(code).decode()
+
+
+def adsa_version() -> int:
+    return load_library().adsa_version()
+
+
+def adsa_workspace_bytes(params: AdsaParams) -> int:
+    return int(load_library().adsa_workspace_bytes(C.byref(params)))
+
+
+def adsa_select(params, seqs, sel_idx, sel_cnt, workspace=None, stream=None) -> None:
+    _check(load_library().adsa_select(C.byref(params), _ptr(seqs), _ptr(sel_idx), _ptr(sel_cnt),
+                                      _ptr(workspace), _nbytes(workspace), _stream(stream)), "adsa_select")
+
+
+def adsa_attend(params, seqs, q, sel_idx, sel_cnt, out, lse, workspace, flags=0, stream=None) -> None:
+    _check(load_library().adsa_attend(C.byref(params), _ptr(seqs), _ptr(q), _ptr(sel_idx), _ptr(sel_cnt),
+                                      _ptr(out), _ptr(lse), flags, _ptr(workspace), _nbytes(workspace),
+                                      _stream(stream)), "adsa_attend")
+
+
+def adsa_compact(params, seqs, keep_map, workspace, stream=None) -> None:
+    _check(load_library().adsa_compact(C.byref(params), _ptr(seqs), _ptr(keep_map), _ptr(workspace),
+                                       _nbytes(workspace), _stream(stream)), "adsa_compact")
+
+
+def adsa_step(params, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, workspace,
+              flags=0, stream=None) -> None:
+    _check(load_library().adsa_step(C.byref(params), _ptr(seqs), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                    _ptr(lse), _ptr(sel_idx), _ptr(sel_cnt), _ptr(keep_map), flags,
+                                    _ptr(workspace), _nbytes(workspace), _stream(stream)), "adsa_step")
+
+
+def adsa_profile_enable(on: bool) -> None:
+    _check(load_library().adsa_profile_enable(1 if on else 0), "adsa_profile_enable")
+
+
+def adsa_profile_read():
+    """(number of bracketed attention launches, their summed duration in ms)."""
+    n, ms = C.c_int64(0), C.c_double(0.0)
+    _check(load_library().adsa_profile_read(C.byref(n), C.byref(ms)), "adsa_profile_read")
+    return n.value, ms.value

@@ -1,0 +1,59 @@
+// Internal declarations shared by the translation units of the ADSA HIP library:
+// launch plan (how the attended set is split over workgroups), workspace layout,
+// and the kernel launchers the C-ABI layer calls.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "adsa.h"
+
+namespace adsa {
+
+constexpr int kWave = 64;
+constexpr int kSelThreads = 256;       // select / compact-plan workgroup
+constexpr int kAttThreads = 256;       // attend workgroup: 4 waves share one token chunk
+constexpr int kAttWaves = kAttThreads / kWave;
+constexpr int kMoveThreads = 256;
+
+// Attend launch plan: a workgroup handles (sequence, head group, token chunk).
+struct AttendPlan {
+  int lanes_per_row;   // lanes that cover one (token, head) row with 16-byte loads
+  int heads_per_wave;  // heads one wave covers per load instruction
+  int n_head_groups;   // ceil(n_heads / heads_per_wave)
+  int n_chunks;        // token chunks per sequence (grid.x); every sequence splits its own count evenly
+  int chunk_max;       // upper bound of tokens in one chunk: ceil(sel_cap / n_chunks)
+};
+
+// Workspace layout (byte offsets from a 256-byte aligned base).
+struct Workspace {
+  size_t logits_off;    // float [n_seq][n_heads][sel_cap]   scaled logits in log2 units
+  size_t partial_off;   // float [n_seq][n_heads][n_chunks][head_dim + 2]   (m, l, acc[D]) per chunk
+  size_t plan_off;      // int32 [n_seq][4]   compaction: old n_res, first moved slot, did, new n_res
+  size_t vcos_off;      // float [n_seq][cap]   inverse V norms of the candidates (0 = not a candidate)
+  size_t vcos_u_off;    // float [n_seq][ceil(cap/64)][n_heads*head_dim]   per-tile partial sums of v^
+  size_t total;
+};
+
+AttendPlan make_attend_plan(const adsa_params& p);
+Workspace make_workspace(const adsa_params& p, const AttendPlan& plan);
+
+static inline int elem_bytes(const adsa_params& p) { return p.dtype == ADSA_F32 ? 4 : 2; }
+
+// Kernel launchers (each returns hipGetLastError() of its launch).
+hipError_t launch_select(const adsa_params& p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
+                         const void* k_new, const void* v_new, bool append, hipStream_t st);
+hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction, char* ws,
+                       const Workspace& w, hipStream_t st);
+int vcos_tiles(int cap);
+hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, const adsa_seq* seqs, const void* q,
+                         const int32_t* sel_idx, const int32_t* sel_cnt, char* ws, const Workspace& w,
+                         bool want_logits, hipStream_t st);
+hipError_t launch_combine(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs,
+                          const int32_t* sel_idx, const int32_t* sel_cnt, void* out, float* lse,
+                          char* ws, const Workspace& w, bool accumulate, bool advance_step, hipStream_t st);
+hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_map, char* ws,
+                          const Workspace& w, bool advance_step, hipStream_t st);
+
+}  // namespace adsa

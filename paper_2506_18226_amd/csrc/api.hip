@@ -1,0 +1,213 @@
+// C ABI of the ADSA HIP library: host-side argument validation and launch ordering.
+// Every entry point only enqueues kernels on the caller's stream.
+#include <vector>
+
+#include "adsa_internal.h"
+
+namespace adsa {
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate_params(const adsa_params* p) {
+  if (!p) return ADSA_ERR_NULL;
+  if (p->dtype != ADSA_F32 && p->dtype != ADSA_BF16) return ADSA_ERR_DTYPE;
+  if (p->score_mode < ADSA_SCORE_ATTN_MASS || p->score_mode > ADSA_SCORE_EXT_SMALLEST) return ADSA_ERR_DTYPE;
+  if (p->n_seq < 1 || p->n_seq > 65535) return ADSA_ERR_SHAPE;
+  if (p->n_heads < 1 || p->n_heads > 256) return ADSA_ERR_SHAPE;
+  if (p->head_dim != 64 && p->head_dim != 128) return ADSA_ERR_SHAPE;
+  if (p->grid_h < 1 || p->grid_w < 1 || (long long)p->grid_h * p->grid_w > (1 << 24)) return ADSA_ERR_SHAPE;
+  if (p->win_rows_back < 0 || p->win_col_radius < 0) return ADSA_ERR_SHAPE;
+  if (p->sel_groups != 1) return ADSA_ERR_UNSUPPORTED;
+  if (p->score_mode == ADSA_SCORE_VCOS && (long long)p->n_heads * p->head_dim > 8192) return ADSA_ERR_UNSUPPORTED;
+  if (p->cap < 1 || p->cap > ADSA_MAX_CAP) return ADSA_ERR_CAPACITY;
+  if (p->sel_cap < 1 || p->sel_cap > p->cap) return ADSA_ERR_CAPACITY;
+  const long long eb = p->dtype == ADSA_F32 ? 4 : 2;
+  if (p->kv_slot_stride < 1 || p->kv_head_stride < 1) return ADSA_ERR_SHAPE;
+  if ((p->kv_slot_stride * eb) % 16 != 0 || (p->kv_head_stride * eb) % 16 != 0) return ADSA_ERR_ALIGN;
+  // rows of different (slot, head) must not overlap: one of the two supported nestings
+  const bool slot_major = p->kv_head_stride >= p->head_dim &&
+                          p->kv_slot_stride >= (long long)p->n_heads * p->kv_head_stride;
+  const bool head_major = p->kv_slot_stride >= p->head_dim &&
+                          p->kv_head_stride >= (long long)p->cap * p->kv_slot_stride;
+  if (!slot_major && !head_major) return ADSA_ERR_SHAPE;
+  if (!(p->softmax_scale >= 0.0f)) return ADSA_ERR_SHAPE;
+  return ADSA_OK;
+}
+
+int check_workspace(const adsa_params* p, const void* ws, size_t bytes, AttendPlan* plan, Workspace* w) {
+  *plan = make_attend_plan(*p);
+  *w = make_workspace(*p, *plan);
+  if (!ws) return ADSA_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return ADSA_ERR_ALIGN;
+  if (bytes < w->total) return ADSA_ERR_WORKSPACE;
+  return ADSA_OK;
+}
+
+// ---- benchmark timing hook: HIP events around the attention kernel, on the caller's stream
+struct Profile {
+  bool on = false;
+  std::vector<hipEvent_t> ev;      // pairs (start, stop)
+  size_t used = 0;
+};
+Profile g_prof;
+
+hipEvent_t prof_event() {
+  if (g_prof.used == g_prof.ev.size()) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    g_prof.ev.push_back(e);
+  }
+  return g_prof.ev[g_prof.used++];
+}
+
+hipError_t timed_attend(const adsa_params& p, const AttendPlan& plan, const adsa_seq* seqs, const void* q,
+                        const int32_t* sel_idx, const int32_t* sel_cnt, char* ws, const Workspace& w,
+                        bool want_logits, hipStream_t st) {
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (g_prof.on) {
+    e0 = prof_event();
+    e1 = prof_event();
+    if (e0 && e1) (void)hipEventRecord(e0, st);
+  }
+  hipError_t e = launch_attend(p, plan, seqs, q, sel_idx, sel_cnt, ws, w, want_logits, st);
+  if (e0 && e1) (void)hipEventRecord(e1, st);
+  return e;
+}
+
+}  // namespace
+}  // namespace adsa
+
+using namespace adsa;
+
+extern "C" {
+
+int adsa_version(void) { return ADSA_VERSION; }
+
+const char* adsa_strerror(int code) {
+  switch (code) {
+    case ADSA_OK: return "ok";
+    case ADSA_ERR_NULL: return "required pointer is NULL";
+    case ADSA_ERR_SHAPE: return "size or window parameter out of range";
+    case ADSA_ERR_DTYPE: return "unknown dtype or score mode";
+    case ADSA_ERR_ALIGN: return "pointer or stride not 16-byte aligned";
+    case ADSA_ERR_CAPACITY: return "cap or sel_cap out of range";
+    case ADSA_ERR_WORKSPACE: return "workspace missing or too small";
+    case ADSA_ERR_LAUNCH: return "HIP launch failed";
+    case ADSA_ERR_UNSUPPORTED: return "not implemented in this build";
+    default: return "unknown error";
+  }
+}
+
+size_t adsa_workspace_bytes(const adsa_params* p) {
+  if (validate_params(p) != ADSA_OK) return 0;
+  AttendPlan plan = make_attend_plan(*p);
+  return make_workspace(*p, plan).total;
+}
+
+int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = validate_params(p);
+  if (rc) return rc;
+  if (!seqs || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (p->score_mode == ADSA_SCORE_VCOS) {
+    AttendPlan plan; Workspace w;
+    rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
+    if (rc) return rc;
+    if (launch_vcos(*p, seqs, false, (char*)workspace, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  }
+  if (launch_select(*p, seqs, sel_idx, sel_cnt, nullptr, nullptr, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  return ADSA_OK;
+}
+
+int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const int32_t* sel_idx,
+                const int32_t* sel_cnt, void* out, float* lse, uint32_t flags,
+                void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = validate_params(p);
+  if (rc) return rc;
+  if (!seqs || !q || !sel_idx || !sel_cnt || !out || !lse) return ADSA_ERR_NULL;
+  if (!aligned16(q) || !aligned16(out)) return ADSA_ERR_ALIGN;
+  AttendPlan plan; Workspace w;
+  rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
+  if (rc) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS && !(flags & ADSA_FLAG_NO_ACCUMULATE);
+  if (timed_attend(*p, plan, seqs, q, sel_idx, sel_cnt, (char*)workspace, w, accumulate, st) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
+  if (launch_combine(*p, plan, seqs, sel_idx, sel_cnt, out, lse, (char*)workspace, w, accumulate, false, st) !=
+      hipSuccess)
+    return ADSA_ERR_LAUNCH;
+  return ADSA_OK;
+}
+
+int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = validate_params(p);
+  if (rc) return rc;
+  if (!seqs || !keep_map) return ADSA_ERR_NULL;
+  AttendPlan plan; Workspace w;
+  rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
+  if (rc) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  if (p->score_mode == ADSA_SCORE_VCOS &&
+      launch_vcos(*p, seqs, true, (char*)workspace, w, st) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
+  if (launch_compact(*p, seqs, keep_map, (char*)workspace, w, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  return ADSA_OK;
+}
+
+int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
+              const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
+              int32_t* keep_map, uint32_t flags, void* workspace, size_t workspace_bytes,
+              void* stream) {
+  int rc = validate_params(p);
+  if (rc) return rc;
+  const bool compact = !(flags & ADSA_FLAG_NO_COMPACT);
+  if (!seqs || !q || !k_new || !v_new || !out || !lse || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
+  if (compact && !keep_map) return ADSA_ERR_NULL;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(k_new) || !aligned16(v_new)) return ADSA_ERR_ALIGN;
+  AttendPlan plan; Workspace w;
+  rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
+  if (rc) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* ws = (char*)workspace;
+  const bool vcos = p->score_mode == ADSA_SCORE_VCOS;
+  const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS;
+  if (vcos && launch_vcos(*p, seqs, false, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  if (launch_select(*p, seqs, sel_idx, sel_cnt, k_new, v_new, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  if (timed_attend(*p, plan, seqs, q, sel_idx, sel_cnt, ws, w, accumulate, st) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
+  if (launch_combine(*p, plan, seqs, sel_idx, sel_cnt, out, lse, ws, w, accumulate, !compact, st) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
+  if (compact) {
+    if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+    if (launch_compact(*p, seqs, keep_map, ws, w, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  }
+  return ADSA_OK;
+}
+
+int adsa_profile_enable(int on) {
+  g_prof.on = on != 0;
+  if (on) g_prof.used = 0;
+  return ADSA_OK;
+}
+
+int adsa_profile_read(int64_t* n_launches, double* total_ms) {
+  if (!n_launches || !total_ms) return ADSA_ERR_NULL;
+  double tot = 0.0;
+  int64_t n = 0;
+  for (size_t i = 0; i + 1 < g_prof.used; i += 2) {
+    if (hipEventSynchronize(g_prof.ev[i + 1]) != hipSuccess) return ADSA_ERR_LAUNCH;
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, g_prof.ev[i], g_prof.ev[i + 1]) != hipSuccess) return ADSA_ERR_LAUNCH;
+    tot += ms;
+    ++n;
+  }
+  *n_launches = n;
+  *total_ms = tot;
+  g_prof.used = 0;
+  return ADSA_OK;
+}
+
+}  // extern "C"

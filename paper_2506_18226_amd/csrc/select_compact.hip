@@ -1,0 +1,395 @@
+// Partition + ranking kernels of the ADSA decode path (gfx950).
+//
+//  k_select        : Eq. 1 partition of the resident slots, Eq. 4 ranking of the candidates by an
+//                    LDS-resident 4-pass MSB radix select with lowest-slot tie-break, and the
+//                    ascending attended-slot list.  Optionally appends the query token's K/V row
+//                    first (Section 4.2: new tokens go to the end of the cache).
+//  k_compact_plan  : Section 4.2 in per-row form: keep flags (prefix, last R rows, top-B of the
+//                    rest), ballot/prefix-sum keep map, in-place move of pos[] and score[].
+//  k_compact_move  : in-place, order-preserving move of the surviving K and V rows.
+//
+// One workgroup of 256 threads owns one sequence in the first two kernels; everything it ranks
+// lives in LDS (keys 4 B/slot), so the score array is read from HBM exactly once.
+#include "adsa_internal.h"
+#include "adsa_partition.h"
+
+namespace adsa {
+namespace {
+
+constexpr uint8_t kFixed = 0;      // prefix / local / protected row: always kept
+constexpr uint8_t kCand = 2;       // competes for the budget
+
+struct RankShared {
+  uint32_t key[ADSA_MAX_CAP];      // order-preserving key; later reused for the keep map
+  uint8_t  cls[ADSA_MAX_CAP];
+  uint32_t hist[256];
+  uint32_t wave_tot[kSelThreads / kWave];
+  uint32_t bcast[4];
+};
+
+// Larger key == kept first.  -0 is folded into +0 so that they tie (IEEE equality).
+__device__ __forceinline__ uint32_t order_key(float x, bool keep_largest) {
+  if (x == 0.0f) x = 0.0f;
+  uint32_t u = __float_as_uint(x);
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return keep_largest ? u : ~u;
+}
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    uint32_t o = __shfl_up(v, d, kWave);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+// Exclusive prefix sum of one value per thread over the 256-thread workgroup; *total gets the sum.
+__device__ __forceinline__ uint32_t block_excl_scan(RankShared& sh, uint32_t v, uint32_t* total) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  uint32_t incl = wave_incl_scan(v);
+  __syncthreads();                                   // wave_tot may still be read from a previous scan
+  if (lane == kWave - 1) sh.wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kSelThreads / kWave; ++w) {
+    uint32_t t = sh.wave_tot[w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  *total = tot;
+  return base + incl - v;
+}
+
+// Eq. 4 as a threshold: returns T and need_eq such that {key > T} plus the first need_eq slots
+// with key == T (ascending slot) are exactly the `want` best candidates.
+__device__ void radix_threshold(RankShared& sh, int n, uint32_t n_cand, uint32_t want,
+                                uint32_t* T_out, uint32_t* need_eq_out) {
+  if (want == 0) { *T_out = 0xFFFFFFFFu; *need_eq_out = 0; return; }
+  if (want >= n_cand) { *T_out = 0u; *need_eq_out = 0xFFFFFFFFu; return; }
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  uint32_t prefix = 0, mask = 0, remaining = want;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    sh.hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += kSelThreads) {
+      uint32_t k = sh.key[i];
+      if (sh.cls[i] == kCand && (k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      // lane l owns digits 255-4l .. 252-4l; scan from the largest digit down
+      uint32_t c[4];
+      uint32_t local = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { c[k] = sh.hist[255 - 4 * lane - k]; local += c[k]; }
+      uint32_t incl = wave_incl_scan(local);
+      unsigned long long hit = __ballot(incl >= remaining);
+      int first = __ffsll((long long)hit) - 1;        // exists: remaining <= candidates under prefix
+      if (lane == first) {
+        uint32_t run = incl - local;
+        int digit = 0;
+        uint32_t rem = remaining;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          if (run + c[k] >= remaining) { digit = 255 - 4 * lane - k; rem = remaining - run; break; }
+          run += c[k];
+        }
+        sh.bcast[0] = (uint32_t)digit;
+        sh.bcast[1] = rem;
+      }
+    }
+    __syncthreads();
+    prefix |= sh.bcast[0] << shift;
+    mask |= 0xFFu << shift;
+    remaining = sh.bcast[1];
+    __syncthreads();
+  }
+  *T_out = prefix;
+  *need_eq_out = remaining;
+}
+
+__device__ __forceinline__ int effective_budget(const adsa_seq& q, int s) {
+  long long b = q.budget;
+  if (q.budget_den > 0) b = ((long long)(q.grid_origin + s) * q.budget_num) / q.budget_den;
+  if (b < 0) b = 0;
+  if (b > ADSA_MAX_CAP) b = ADSA_MAX_CAP;
+  return (int)b;
+}
+
+// 16-byte copy of one [n_heads][head_dim] row into the cache at `slot`.
+__device__ __forceinline__ void append_row(void* cache, const void* row, int slot, int n_heads,
+                                           int vec_per_head, long long slot_stride_b,
+                                           long long head_stride_b) {
+  const int total = n_heads * vec_per_head;
+  for (int i = threadIdx.x; i < total; i += blockDim.x) {
+    int hh = i / vec_per_head, within = i - hh * vec_per_head;
+    const uint4 val = reinterpret_cast<const uint4*>(row)[i];
+    char* dst = reinterpret_cast<char*>(cache) + (long long)slot * slot_stride_b + (long long)hh * head_stride_b;
+    reinterpret_cast<uint4*>(dst)[within] = val;
+  }
+}
+
+struct LaunchShape {
+  int n_heads, head_dim, elem_bytes;
+  int grid_h, grid_w, R, w;
+  int cap, sel_cap, score_mode;
+  long long slot_stride_b, head_stride_b;    // bytes
+};
+
+__device__ __forceinline__ bool keep_largest_of(int mode) {
+  return mode == ADSA_SCORE_ATTN_MASS || mode == ADSA_SCORE_EXT_LARGEST;
+}
+
+__global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq* seqs, int32_t* sel_idx,
+                                                       int32_t* sel_cnt, const char* k_new,
+                                                       const char* v_new, int do_append) {
+  __shared__ RankShared sh;
+  __shared__ int s_bad;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  adsa_seq& sq = seqs[b];
+  const int s = sq.step;
+  int n = sq.n_res;
+  const int status_in = sq.status;
+  if (tid == 0) s_bad = 0;
+  __syncthreads();
+  if (s < 0 || status_in != 0) { if (tid == 0) sel_cnt[b] = 0; return; }
+  if (n < 0 || n > L.cap || s > L.grid_h * L.grid_w) {
+    if (tid == 0) { sq.status = status_in | ADSA_SEQ_BAD_STATE; sel_cnt[b] = 0; }
+    return;
+  }
+  const int P = sq.grid_origin;
+  if (do_append && s >= 1) {
+    if (n + 1 > L.cap) {
+      if (tid == 0) { sq.status = status_in | ADSA_SEQ_CACHE_FULL; sel_cnt[b] = 0; }
+      return;
+    }
+    const int vph = L.head_dim * L.elem_bytes / 16;
+    const size_t row_b = (size_t)L.n_heads * L.head_dim * L.elem_bytes;
+    append_row(sq.k, k_new + (size_t)b * row_b, n, L.n_heads, vph, L.slot_stride_b, L.head_stride_b);
+    append_row(sq.v, v_new + (size_t)b * row_b, n, L.n_heads, vph, L.slot_stride_b, L.head_stride_b);
+    if (tid == 0) { sq.pos[n] = P + s - 1; sq.score[n] = 0.0f; sq.n_res = n + 1; }
+    n += 1;
+    __syncthreads();                       // pos/score of the new slot visible to the whole workgroup
+  }
+
+  // ---- Eq. 1: partition, keys into LDS
+  const QueryCell cell = make_query_cell(sq, s, L.grid_w, L.R, L.w);
+  const bool largest = keep_largest_of(L.score_mode);
+  uint32_t my_cand = 0;
+  for (int i = tid; i < n; i += kSelThreads) {
+    const int c = select_class(cell, sq.pos[i]);
+    if (c < 0) s_bad = 1;
+    sh.cls[i] = c == 1 ? kCand : kFixed;
+    sh.key[i] = order_key(sq.score[i], largest);
+    my_cand += (c == 1);
+  }
+  uint32_t n_cand;
+  block_excl_scan(sh, my_cand, &n_cand);   // also orders the LDS writes above before the reads below
+  if (s_bad) {
+    if (tid == 0) { sq.status = status_in | ADSA_SEQ_BAD_STATE; sel_cnt[b] = 0; }
+    return;
+  }
+
+  // ---- Eq. 4: threshold of the top-B candidates
+  const uint32_t B = (uint32_t)effective_budget(sq, s);
+  uint32_t T, need_eq;
+  radix_threshold(sh, n, n_cand, B < n_cand ? B : n_cand, &T, &need_eq);
+
+  // ---- ascending slot list: contiguous run of slots per thread, packed (kept | equal<<16) scan
+  const int per = (n + kSelThreads - 1) / kSelThreads;
+  const int lo = tid * per, hi = min(n, lo + per);
+  uint32_t a = 0, e = 0;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t k = sh.key[i];
+    const bool cand = sh.cls[i] == kCand;
+    a += (!cand) || (k > T);
+    e += cand && (k == T);
+  }
+  uint32_t total;
+  uint32_t ex = block_excl_scan(sh, a | (e << 16), &total);
+  uint32_t a_run = ex & 0xFFFFu, e_run = ex >> 16;
+  int32_t* out = sel_idx + (size_t)b * L.sel_cap;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t k = sh.key[i];
+    const bool cand = sh.cls[i] == kCand;
+    bool take = (!cand) || (k > T);
+    const bool eq = cand && (k == T);
+    const uint32_t dest = a_run + min(e_run, need_eq);
+    if (eq) { take = e_run < need_eq; ++e_run; } else if (take) ++a_run;
+    if (take && dest < (uint32_t)L.sel_cap) out[dest] = i;
+  }
+  if (tid == 0) {
+    const uint32_t cnt = (total & 0xFFFFu) + min(total >> 16, need_eq);
+    if (cnt > (uint32_t)L.sel_cap) { sq.status = status_in | ADSA_SEQ_SEL_OVERFLOW; sel_cnt[b] = 0; }
+    else sel_cnt[b] = (int32_t)cnt;
+  }
+}
+
+// plan[b] = { old n_res, first slot that moves, did compact, new n_res }
+__global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, adsa_seq* seqs,
+                                                             int32_t* keep_map, int32_t* plan,
+                                                             int advance_step) {
+  __shared__ RankShared sh;
+  const int b = blockIdx.x, tid = threadIdx.x;
+  adsa_seq& sq = seqs[b];
+  const int s = sq.step, n = sq.n_res, W = L.grid_w;
+  const bool active = s >= 0 && sq.status == 0;
+  const bool row_end = active && is_row_end(s, L.grid_h, W) && n >= 0 && n <= L.cap;
+  if (!row_end) {
+    if (tid == 0) {
+      plan[4 * b + 0] = 0; plan[4 * b + 1] = 0; plan[4 * b + 2] = 0; plan[4 * b + 3] = n;
+      if (active) { sq.compacted = 0; if (advance_step) sq.step = s + 1; }
+    }
+    return;
+  }
+  const QueryCell cell = make_query_cell(sq, s, W, L.R, L.w);
+  const bool largest = keep_largest_of(L.score_mode);
+  uint32_t my_rest = 0;
+  for (int i = tid; i < n; i += kSelThreads) {
+    const int c = evict_class(cell, sq.pos[i]);
+    sh.cls[i] = c == 1 ? kCand : kFixed;
+    sh.key[i] = order_key(sq.score[i], largest);
+    my_rest += (c == 1);
+  }
+  uint32_t n_rest;
+  block_excl_scan(sh, my_rest, &n_rest);
+  const uint32_t B = (uint32_t)effective_budget(sq, s);
+  uint32_t T, need_eq;
+  radix_threshold(sh, n, n_rest, B < n_rest ? B : n_rest, &T, &need_eq);
+
+  const int per = (n + kSelThreads - 1) / kSelThreads;
+  const int lo = tid * per, hi = min(n, lo + per);
+  uint32_t a = 0, e = 0;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t k = sh.key[i];
+    const bool cand = sh.cls[i] == kCand;
+    a += (!cand) || (k > T);
+    e += cand && (k == T);
+  }
+  uint32_t total;
+  uint32_t ex = block_excl_scan(sh, a | (e << 16), &total);
+  uint32_t a_run = ex & 0xFFFFu, e_run = ex >> 16;
+  int32_t* map = keep_map + (size_t)b * L.cap;
+  int my_first = n;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t k = sh.key[i];
+    const bool cand = sh.cls[i] == kCand;
+    bool take = (!cand) || (k > T);
+    const bool eq = cand && (k == T);
+    const uint32_t dest = a_run + min(e_run, need_eq);
+    if (eq) { take = e_run < need_eq; ++e_run; } else if (take) ++a_run;
+    const int32_t m = take ? (int32_t)dest : -1;
+    map[i] = m;
+    sh.key[i] = (uint32_t)m;                 // own run only: no other thread reads key[i] any more
+    if (m != i && i < my_first) my_first = i;
+  }
+  // first slot whose content changes (evicted or moved): everything before it stays put
+  __syncthreads();
+  if (tid == 0) sh.bcast[2] = (uint32_t)n;
+  __syncthreads();
+  atomicMin(&sh.bcast[2], (uint32_t)my_first);
+  __syncthreads();
+  const int first = (int)sh.bcast[2];
+  const uint32_t n_new = (total & 0xFFFFu) + min(total >> 16, need_eq);
+
+  // in-place, order-preserving move of pos[] and score[]: ascending tiles, load -> barrier -> store.
+  // A tile's destinations are <= its sources and below the next tile's sources.
+  for (int base = (first / kSelThreads) * kSelThreads; base < n; base += kSelThreads) {
+    const int i = base + tid;
+    int m = -1, pv = 0;
+    float sv = 0.0f;
+    if (i < n) { m = (int)sh.key[i]; if (m >= 0 && m != i) { pv = sq.pos[i]; sv = sq.score[i]; } }
+    __syncthreads();
+    if (m >= 0 && m != i) { sq.pos[m] = pv; sq.score[m] = sv; }
+  }
+  if (tid == 0) {
+    plan[4 * b + 0] = n; plan[4 * b + 1] = first; plan[4 * b + 2] = 1; plan[4 * b + 3] = (int32_t)n_new;
+    sq.n_res = (int32_t)n_new;
+    sq.compacted = 1;
+    if (advance_step) sq.step = s + 1;
+  }
+}
+
+// grid = (row slices, 2 {K,V}, n_seq).  A workgroup owns a 16*lanes-byte column slice of every row
+// of one cache and walks the rows in ascending tiles: load survivors -> barrier -> store.
+template <int ROWS_PER_THREAD>
+__global__ __launch_bounds__(kMoveThreads) void k_compact_move(LaunchShape L, const adsa_seq* seqs,
+                                                              const int32_t* keep_map,
+                                                              const int32_t* plan, int lanes_per_slice,
+                                                              int slices_per_head) {
+  const int b = blockIdx.z;
+  if (plan[4 * b + 2] == 0) return;
+  const int n_old = plan[4 * b + 0], first = plan[4 * b + 1];
+  if (first >= n_old) return;
+  const adsa_seq& sq = seqs[b];
+  char* base = reinterpret_cast<char*>(blockIdx.y == 0 ? sq.k : sq.v);
+  const int slice = blockIdx.x;
+  const int head = slice / slices_per_head, part = slice - head * slices_per_head;
+  base += (long long)head * L.head_stride_b + (long long)part * lanes_per_slice * 16;
+  const int rows_per_pass = kMoveThreads / lanes_per_slice;
+  const int row_in_pass = threadIdx.x / lanes_per_slice, lane = threadIdx.x % lanes_per_slice;
+  const int32_t* map = keep_map + (size_t)b * L.cap;
+  const int tile = rows_per_pass * ROWS_PER_THREAD;
+  for (int t0 = (first / tile) * tile; t0 < n_old; t0 += tile) {
+    uint4 val[ROWS_PER_THREAD];
+    int dst[ROWS_PER_THREAD];
+#pragma unroll
+    for (int u = 0; u < ROWS_PER_THREAD; ++u) {
+      const int i = t0 + u * rows_per_pass + row_in_pass;
+      dst[u] = -1;
+      if (i < n_old) {
+        const int m = map[i];
+        if (m >= 0 && m != i) {
+          dst[u] = m;
+          val[u] = reinterpret_cast<const uint4*>(base + (long long)i * L.slot_stride_b)[lane];
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < ROWS_PER_THREAD; ++u)
+      if (dst[u] >= 0) reinterpret_cast<uint4*>(base + (long long)dst[u] * L.slot_stride_b)[lane] = val[u];
+  }
+}
+
+LaunchShape shape_of(const adsa_params& p) {
+  LaunchShape L;
+  L.n_heads = p.n_heads; L.head_dim = p.head_dim; L.elem_bytes = elem_bytes(p);
+  L.grid_h = p.grid_h; L.grid_w = p.grid_w; L.R = p.win_rows_back; L.w = p.win_col_radius;
+  L.cap = p.cap; L.sel_cap = p.sel_cap; L.score_mode = p.score_mode;
+  L.slot_stride_b = (long long)p.kv_slot_stride * L.elem_bytes;
+  L.head_stride_b = (long long)p.kv_head_stride * L.elem_bytes;
+  return L;
+}
+
+}  // namespace
+
+hipError_t launch_select(const adsa_params& p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
+                         const void* k_new, const void* v_new, bool append, hipStream_t st) {
+  hipLaunchKernelGGL(k_select, dim3(p.n_seq), dim3(kSelThreads), 0, st, shape_of(p), seqs, sel_idx, sel_cnt,
+                     (const char*)k_new, (const char*)v_new, append ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_map, char* ws,
+                          const Workspace& w, bool advance_step, hipStream_t st) {
+  int32_t* plan = reinterpret_cast<int32_t*>(ws + w.plan_off);
+  LaunchShape L = shape_of(p);
+  hipLaunchKernelGGL(k_compact_plan, dim3(p.n_seq), dim3(kSelThreads), 0, st, L, seqs, keep_map, plan,
+                     advance_step ? 1 : 0);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // one workgroup per 128-byte column slice of a head row (whole head row when it is narrower)
+  const int head_bytes = p.head_dim * L.elem_bytes;
+  const int slice_bytes = head_bytes < 128 ? head_bytes : 128;
+  const int lanes = slice_bytes / 16, slices_per_head = head_bytes / slice_bytes;
+  dim3 grid(p.n_heads * slices_per_head, 2, p.n_seq);
+  hipLaunchKernelGGL(k_compact_move<4>, grid, dim3(kMoveThreads), 0, st, L, (const adsa_seq*)seqs,
+                     (const int32_t*)keep_map, (const int32_t*)plan, lanes, slices_per_head);
+  return hipGetLastError();
+}
+
+}  // namespace adsa

@@ -1,0 +1,177 @@
+// TopK-V redundancy score of the ADSA decode path (gfx950): Eq. 2-3, the mean pairwise cosine
+// similarity of a candidate's V vector (all heads concatenated) to the other candidates.
+//
+// The N x N cosine matrix is never formed.  With v^_i = v_i / max(|v_i|, 1e-8) and
+// u = sum_j v^_j over the candidates,  S_i = (v^_i . u - v^_i . v^_i) / (N - 1): two streaming
+// passes over the candidates' V rows instead of O(N^2 D) work.
+//
+//  k_vcos_norm_usum : grid (slot tile, sequence).  A wave per slot computes the inverse norm; then
+//                     the workgroup's threads each own 4 columns and add the tile's normalised
+//                     rows into a per-tile partial of u (deterministic order, no atomics).
+//  k_vcos_score     : grid (slot tile, sequence).  Sums the tile partials of u into LDS, counts the
+//                     candidates, then a wave per slot takes the dot product and writes S_i into
+//                     score[slot] (non-candidate slots keep their score).
+#include "adsa_internal.h"
+#include "adsa_partition.h"
+
+namespace adsa {
+namespace {
+
+constexpr int kVcThreads = 256;
+constexpr int kVcWaves = kVcThreads / kWave;
+constexpr int kVcTile = 64;                 // slots per workgroup
+constexpr int kVcMaxDim = 8192;             // n_heads * head_dim limit of the LDS copy of u
+
+struct VcosArgs {
+  const adsa_seq* seqs_c;
+  adsa_seq* seqs;
+  float* inv_norm;      // [n_seq][cap]
+  float* u_part;        // [n_seq][n_tiles][dim]
+  int n_heads, head_dim, elem_bytes, cap, n_tiles;
+  int grid_h, grid_w, R, w, for_compaction;
+  long long slot_stride_b, head_stride_b;
+};
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, kWave);
+  return x;
+}
+
+// candidate test for slot i of sequence sq (false for inactive sequences / non row-end compaction)
+__device__ __forceinline__ bool vcos_candidate(const VcosArgs& A, const QueryCell& c, int pos) {
+  return A.for_compaction ? evict_class(c, pos) == 1 : select_class(c, pos) == 1;
+}
+
+__device__ __forceinline__ bool vcos_active(const VcosArgs& A, const adsa_seq& sq) {
+  if (sq.step < 0 || sq.status != 0 || sq.n_res < 0 || sq.n_res > A.cap) return false;
+  if (sq.step > A.grid_h * A.grid_w) return false;
+  return A.for_compaction ? is_row_end(sq.step, A.grid_h, A.grid_w) : true;
+}
+
+// load 4 consecutive elements (column group g of the concatenated row) of slot `slot`
+__device__ __forceinline__ float4 load4(const VcosArgs& A, const char* vbase, int slot, int g) {
+  const int col = g * 4, head = col / A.head_dim, d = col - head * A.head_dim;
+  const char* p = vbase + (long long)slot * A.slot_stride_b + (long long)head * A.head_stride_b;
+  if (A.elem_bytes == 4) return reinterpret_cast<const float4*>(p)[d / 4];
+  const uint2 r = reinterpret_cast<const uint2*>(p)[d / 4];
+  return make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u),
+                     __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u));
+}
+
+__global__ __launch_bounds__(kVcThreads) void k_vcos_norm_usum(VcosArgs A) {
+  __shared__ float s_inv[kVcTile];
+  const int tile = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  const adsa_seq& sq = A.seqs_c[b];
+  if (!vcos_active(A, sq)) return;
+  const int n = sq.n_res, s0 = tile * kVcTile;
+  if (s0 >= n) return;
+  const int s1 = min(n, s0 + kVcTile);
+  const QueryCell cell = make_query_cell(sq, sq.step, A.grid_w, A.R, A.w);
+  const char* vbase = reinterpret_cast<const char*>(sq.v);
+  const int groups = A.n_heads * A.head_dim / 4;
+  for (int i = s0 + wave; i < s1; i += kVcWaves) {
+    float inv = 0.0f;                                   // 0 marks "not a candidate"
+    if (vcos_candidate(A, cell, sq.pos[i])) {
+      float ss = 0.0f;
+      for (int g = lane; g < groups; g += kWave) {
+        const float4 x = load4(A, vbase, i, g);
+        ss = fmaf(x.x, x.x, ss); ss = fmaf(x.y, x.y, ss); ss = fmaf(x.z, x.z, ss); ss = fmaf(x.w, x.w, ss);
+      }
+      ss = wave_sum(ss);
+      inv = 1.0f / fmaxf(sqrtf(ss), 1e-8f);
+    }
+    if (lane == 0) { s_inv[i - s0] = inv; A.inv_norm[(size_t)b * A.cap + i] = inv; }
+  }
+  __syncthreads();
+  float* up = A.u_part + ((size_t)b * A.n_tiles + tile) * (size_t)(groups * 4);
+  for (int g = tid; g < groups; g += kVcThreads) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int i = s0; i < s1; ++i) {
+      const float inv = s_inv[i - s0];
+      if (inv == 0.0f) continue;
+      const float4 x = load4(A, vbase, i, g);
+      acc.x = fmaf(x.x, inv, acc.x); acc.y = fmaf(x.y, inv, acc.y);
+      acc.z = fmaf(x.z, inv, acc.z); acc.w = fmaf(x.w, inv, acc.w);
+    }
+    reinterpret_cast<float4*>(up)[g] = acc;
+  }
+}
+
+__global__ __launch_bounds__(kVcThreads) void k_vcos_score(VcosArgs A) {
+  extern __shared__ float s_u[];                       // [dim]
+  __shared__ int s_cnt[kVcWaves];
+  const int tile = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  adsa_seq& sq = A.seqs[b];
+  if (!vcos_active(A, sq)) return;
+  const int n = sq.n_res, s0 = tile * kVcTile;
+  if (s0 >= n) return;
+  const int s1 = min(n, s0 + kVcTile);
+  const int groups = A.n_heads * A.head_dim / 4;
+  const int tiles_used = (n + kVcTile - 1) / kVcTile;
+  const float* up = A.u_part + (size_t)b * A.n_tiles * (size_t)(groups * 4);
+  for (int g = tid; g < groups; g += kVcThreads) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int t = 0; t < tiles_used; ++t) {             // ascending tile order: deterministic
+      const float4 x = reinterpret_cast<const float4*>(up + (size_t)t * groups * 4)[g];
+      acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+    }
+    reinterpret_cast<float4*>(s_u)[g] = acc;
+  }
+  int my = 0;
+  const float* invs = A.inv_norm + (size_t)b * A.cap;
+  for (int i = tid; i < n; i += kVcThreads) my += invs[i] != 0.0f;
+  for (int d = 32; d >= 1; d >>= 1) my += __shfl_xor(my, d, kWave);
+  if (lane == 0) s_cnt[wave] = my;
+  __syncthreads();
+  int N = 0;
+  for (int w = 0; w < kVcWaves; ++w) N += s_cnt[w];
+  const char* vbase = reinterpret_cast<const char*>(sq.v);
+  for (int i = s0 + wave; i < s1; i += kVcWaves) {
+    const float inv = invs[i];
+    if (inv == 0.0f) continue;                          // wave-uniform
+    float dot = 0.0f, ss = 0.0f;
+    for (int g = lane; g < groups; g += kWave) {
+      const float4 x = load4(A, vbase, i, g);
+      const float4 uu = reinterpret_cast<const float4*>(s_u)[g];
+      dot = fmaf(x.x, uu.x, dot); dot = fmaf(x.y, uu.y, dot); dot = fmaf(x.z, uu.z, dot); dot = fmaf(x.w, uu.w, dot);
+      ss = fmaf(x.x, x.x, ss); ss = fmaf(x.y, x.y, ss); ss = fmaf(x.z, x.z, ss); ss = fmaf(x.w, x.w, ss);
+    }
+    dot = wave_sum(dot);
+    ss = wave_sum(ss);
+    // remove the i == j term (1 for a normal row, 0 for a zero row) and average over the others
+    const float self = ss * inv * inv;
+    const float S = N > 1 ? (dot * inv - self) / (float)(N - 1) : 0.0f;
+    if (lane == 0) sq.score[i] = S;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction, char* ws,
+                       const Workspace& w, hipStream_t st) {
+  const int dim = p.n_heads * p.head_dim;
+  if (dim > kVcMaxDim) return hipErrorInvalidValue;
+  VcosArgs A;
+  A.seqs_c = seqs; A.seqs = seqs;
+  A.inv_norm = reinterpret_cast<float*>(ws + w.vcos_off);
+  A.u_part = reinterpret_cast<float*>(ws + w.vcos_u_off);
+  A.n_heads = p.n_heads; A.head_dim = p.head_dim; A.elem_bytes = elem_bytes(p); A.cap = p.cap;
+  A.n_tiles = (p.cap + kVcTile - 1) / kVcTile;
+  A.grid_h = p.grid_h; A.grid_w = p.grid_w; A.R = p.win_rows_back; A.w = p.win_col_radius;
+  A.for_compaction = for_compaction ? 1 : 0;
+  A.slot_stride_b = (long long)p.kv_slot_stride * A.elem_bytes;
+  A.head_stride_b = (long long)p.kv_head_stride * A.elem_bytes;
+  dim3 grid(A.n_tiles, p.n_seq);
+  hipLaunchKernelGGL(k_vcos_norm_usum, grid, dim3(kVcThreads), 0, st, A);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_vcos_score, grid, dim3(kVcThreads), sizeof(float) * (size_t)dim, st, A);
+  return hipGetLastError();
+}
+
+int vcos_tiles(int cap) { return (cap + kVcTile - 1) / kVcTile; }
+
+}  // namespace adsa

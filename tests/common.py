@@ -1,0 +1,51 @@
+"""Shared helpers of the test-suite: build oracle configs / library params from a workload and
+replay oracle trajectories.  The oracle (CPU) and the HIP binding are only ever brought together
+here and in the tests themselves."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+from paper_2506_18226_amd import workloads as WL
+
+
+def oracle_cfg(wl, *, P=None, budget=None, score_mode=None, cap=0, n_keep_prefix=None):
+    P = wl.prefix_len if P is None else P
+    use_frac = wl.budget_den > 0 and budget is None
+    return oracle.make_cfg(
+        n_heads=wl.n_heads, head_dim=wl.head_dim, grid_h=wl.grid_h, grid_w=wl.grid_w,
+        win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius, grid_origin=P,
+        n_keep_prefix=n_keep_prefix,
+        budget=(wl.budget if budget is None else budget) if not use_frac else 0,
+        budget_num=wl.budget_num if use_frac else 0, budget_den=wl.budget_den if use_frac else 0,
+        score_mode=wl.score_mode if score_mode is None else score_mode, cap=cap)
+
+
+def replay(wl, cfg, layer, seq, stop_before, snapshots=()):
+    """Run the oracle free from s = 0 up to (not including) step `stop_before`.
+    Returns (q, k, v, state, {s: state copy taken BEFORE step s} for s in snapshots)."""
+    P = cfg.grid_origin
+    q, k, v = WL.gen_tokens(wl, layer, seq, prefix_len=P)
+    st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+    snaps = {}
+    for s in range(0, stop_before):
+        if s in snapshots:
+            snaps[s] = st.copy()
+        p = P + s - 1
+        oracle.step(cfg, st, s, q[p], k[p], v[p])
+    if stop_before in snapshots:
+        snaps[stop_before] = st.copy()
+    return q, k, v, st, snaps
+
+
+def near_tie_ok(sel_gpu, sel_ref, score_ref, rel=1e-5, abs_tol=1e-7):
+    """Two attended sets that differ only in candidates whose oracle scores tie within tolerance."""
+    a, b = set(sel_gpu.tolist()), set(sel_ref.tolist())
+    if a == b:
+        return True
+    only_a, only_b = sorted(a - b), sorted(b - a)
+    if len(only_a) != len(only_b):
+        return False
+    vals = np.concatenate([score_ref[only_a], score_ref[only_b]]).astype(np.float64)
+    spread = vals.max() - vals.min()
+    return bool(spread <= abs_tol + rel * np.abs(vals).max())

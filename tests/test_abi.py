@@ -1,0 +1,116 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2506_18226_amd import binding as B
+from paper_2506_18226_amd import build as BLD
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(BLD.LIB_PATH):
+        BLD.build_library()
+    return B.load_library()
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "adsa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(adsa_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = header_functions()
+    assert sorted(names) == sorted(B.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert B.adsa_version() == 1
+
+
+def test_struct_mirrors_match_the_header():
+    assert C.sizeof(B.AdsaParams) == 12 * 4 + 2 * 8 + 4 + 4
+    assert B.SEQ_DTYPE.itemsize == 80
+    assert B.SEQ_DTYPE.fields["n_res"][1] == 32 and B.SEQ_DTYPE.fields["status"][1] == 60
+
+
+def good(**kw):
+    base = dict(n_seq=2, n_heads=4, head_dim=64, grid_h=8, grid_w=8, win_rows_back=1, win_col_radius=2,
+                dtype=B.BF16, score_mode=B.SCORE_ATTN_MASS, cap=128, sel_cap=128)
+    base.update(kw)
+    return B.make_params(**base)
+
+
+def test_workspace_size_is_positive_and_monotone(lib):
+    a = B.adsa_workspace_bytes(good())
+    b = B.adsa_workspace_bytes(good(n_seq=8))
+    assert a > 0 and b > a and a % 256 == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dtype=7), -3), (dict(score_mode=9), -3), (dict(n_seq=0), -2), (dict(n_heads=0), -2),
+    (dict(n_heads=300), -2), (dict(head_dim=96), -2), (dict(grid_w=0), -2), (dict(win_rows_back=-1), -2),
+    (dict(cap=0), -5), (dict(cap=B.MAX_CAP + 1, sel_cap=16), -5), (dict(sel_cap=0), -5), (dict(sel_cap=129), -5),
+    (dict(sel_groups=4), -8), (dict(kv_slot_stride=4 * 64 + 4), -4), (dict(kv_head_stride=32), -2),
+    (dict(kv_slot_stride=64), -2), (dict(softmax_scale=-1.0), -2),
+    (dict(score_mode=B.SCORE_VCOS, n_heads=128, head_dim=128), -8),
+])
+def test_bad_parameters_are_rejected_before_any_launch(lib, kw, code):
+    p = good(**kw)
+    fake = 0x1000   # never dereferenced: validation fails first
+    rc = lib.adsa_select(C.byref(p), fake, fake, fake, fake, 1 << 30, None)
+    assert rc == code, B.strerror(rc)
+    assert B.adsa_workspace_bytes(p) == 0
+    rc = lib.adsa_step(C.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None)
+    assert rc == code
+    assert len(B.strerror(rc)) > 3
+
+
+def test_null_alignment_and_workspace_errors(lib):
+    p = good()
+    ok = 0x1000
+    need = B.adsa_workspace_bytes(p)
+    assert lib.adsa_select(C.byref(p), None, ok, ok, ok, need, None) == -1
+    assert lib.adsa_select(None, ok, ok, ok, ok, need, None) == -1
+    assert lib.adsa_attend(C.byref(p), ok, ok, ok, ok, None, ok, 0, ok, need, None) == -1
+    assert lib.adsa_attend(C.byref(p), ok, ok + 4, ok, ok, ok, ok, 0, ok, need, None) == -4
+    assert lib.adsa_attend(C.byref(p), ok, ok, ok, ok, ok, ok, 0, None, need, None) == -6
+    assert lib.adsa_attend(C.byref(p), ok, ok, ok, ok, ok, ok, 0, ok, need - 1, None) == -6
+    assert lib.adsa_attend(C.byref(p), ok, ok, ok, ok, ok, ok, 0, ok + 16, need, None) == -4
+    assert lib.adsa_compact(C.byref(p), ok, None, ok, need, None) == -1
+    assert lib.adsa_compact(C.byref(p), ok, ok, ok, 0, None) == -6
+    # keep_map may be NULL only when the caller rules compaction out
+    assert lib.adsa_step(C.byref(p), ok, ok, ok, ok, ok, ok, ok, ok, None, 0, ok, need, None) == -1
+    assert lib.adsa_step(C.byref(p), ok, ok, ok, ok + 8, ok, ok, ok, ok, ok, 0, ok, need, None) == -4
+    n, ms = C.c_int64(), C.c_double()
+    assert lib.adsa_profile_read(None, C.byref(ms)) == -1
+    assert lib.adsa_profile_read(C.byref(n), C.byref(ms)) == 0 and n.value == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(BLD, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(FileNotFoundError):
+        B.load_library()
+    with pytest.raises(FileNotFoundError):
+        B.adsa_version()
+
+
+def test_product_package_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2506_18226_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "adsa_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2506_18226_amd" not in text and "adsa.h" not in text, f
