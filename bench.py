@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the ADSA decode hot path on one MI355X.
+
+A "step" is one decode step of the whole workload: every layer's adsa_step (append, select,
+gather attention, score accumulation, and the row-end eviction + compaction when the step closes
+a grid row) for every sequence.  The default workload is the LlamaGen-XXL-shaped configuration
+(48 layers, 32 sequences, 24 heads x 64, bf16, 120 prefix + 32x32 grid, window prev-row +-4,
+budget 512) and the default run times its complete 1024-step trajectory, free-running from the
+prefix-only cache, with all inputs resident in HBM before the clock starts.
+
+Prints ONE JSON line: decode tokens/s (whole job), the HBM roofline of the attention kernel
+(algorithmic selected-KV bytes / its HIP-event-timed duration), KV bytes resident, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the whole trajectory)")
+    ap.add_argument("--warmup", type=int, default=32, help="untimed decode steps before the timed region")
+    ap.add_argument("--workload", default="xxl", choices=["tiny", "xl", "xxl", "long"])
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline-pass", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle sample")
+    return ap.parse_args()
+
+
+class Job:
+    """All device state of the benchmark: per-layer caches, step-major inputs, shared outputs."""
+
+    def __init__(self, wl, n_layers, device):
+        import torch
+        from paper_2506_18226_amd import binding as B
+        from paper_2506_18226_amd import workloads as WL
+        from paper_2506_18226_amd.batch import LayerBatch
+
+        self.torch, self.B, self.wl, self.n_layers, self.device = torch, B, wl, n_layers, device
+        P, n, h, D = wl.prefix_len, wl.n_seq, wl.n_heads, wl.head_dim
+        self.n_steps_total = wl.n_image_tokens          # s = 0 .. H*W-1
+        self.params = B.make_params(
+            n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w,
+            win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
+            dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=wl.score_mode,
+            cap=wl.cap(), sel_cap=wl.sel_cap())
+        self.layers = []
+        self.q, self.kn, self.vn = [], [], []
+        S = self.n_steps_total
+        for l in range(n_layers):
+            lb = LayerBatch(self.params, device, with_outputs=False)
+            qd, kd, vd = WL.gen_tokens_device(wl, l, device)        # [n][L][h][D]
+            lb.K[:, :P] = kd[:, :P]
+            lb.V[:, :P] = vd[:, :P]
+            lb.pos[:, :P] = torch.arange(P, dtype=torch.int32, device=device)[None, :]
+            # step s queries with the token at position P+s-1: step-major [S][n][h][D]
+            self.q.append(qd[:, P - 1:P - 1 + S].permute(1, 0, 2, 3).contiguous())
+            self.kn.append(kd[:, P - 1:P - 1 + S].permute(1, 0, 2, 3).contiguous())
+            self.vn.append(vd[:, P - 1:P - 1 + S].permute(1, 0, 2, 3).contiguous())
+            del qd, kd, vd
+            self.layers.append(lb)
+        p = self.params
+        tdt = self.layers[0].tdtype
+        self.out = torch.zeros((n, h, D), dtype=tdt, device=device)
+        self.lse = torch.zeros((n, h), dtype=torch.float32, device=device)
+        self.sel_idx = torch.zeros((n, p.sel_cap), dtype=torch.int32, device=device)
+        self.keep_map = torch.zeros((n, p.cap), dtype=torch.int32, device=device)
+        self.sel_cnt_log = torch.zeros((S, n_layers, n), dtype=torch.int32, device=device)
+        self.workspace = self.layers[0].workspace
+        self.row_bytes = n * h * D * self.out.element_size()
+        self.reset()
+
+    def reset(self):
+        wl, P = self.wl, self.wl.prefix_len
+        for lb in self.layers:
+            for b in range(wl.n_seq):
+                s = lb.seqs_host[b]
+                s["n_res"], s["step"], s["grid_origin"], s["n_keep_prefix"] = P, 0, P, P
+                s["budget"], s["budget_num"], s["budget_den"] = wl.budget, wl.budget_num, wl.budget_den
+                s["status"], s["compacted"] = 0, 0
+            lb.upload_seqs()
+            lb.score.zero_()
+        self.sel_cnt_log.zero_()
+        self.torch.cuda.synchronize()
+
+    def run(self, s_begin, s_end, on_row_end=None):
+        """Enqueue decode steps s_begin .. s_end-1 for every layer (no host sync inside)."""
+        B, wl = self.B, self.wl
+        W = wl.grid_w
+        stream = self.torch.cuda.current_stream().cuda_stream
+        ptr = lambda t: t.data_ptr()
+        seqs = [ptr(lb.seqs) for lb in self.layers]
+        qb, kb, vb = [ptr(t) for t in self.q], [ptr(t) for t in self.kn], [ptr(t) for t in self.vn]
+        out, lse, sel_idx, keep_map = ptr(self.out), ptr(self.lse), ptr(self.sel_idx), ptr(self.keep_map)
+        cnt0 = ptr(self.sel_cnt_log)
+        n, L = wl.n_seq, self.n_layers
+        for s in range(s_begin, s_end):
+            row_end = s >= 1 and (s - 1) % W == W - 1
+            flags = 0 if row_end else B.FLAG_NO_COMPACT
+            off = s * self.row_bytes
+            for l in range(L):
+                B.adsa_step(self.params, seqs[l], qb[l] + off, kb[l] + off, vb[l] + off, out, lse, sel_idx,
+                            cnt0 + ((s * L + l) * n) * 4, keep_map, self.workspace, flags, stream)
+            if row_end and on_row_end is not None:
+                on_row_end(s)
+
+
+def cpu_baseline(wl, n_layers, seconds):
+    """The oracle as it stands, one thread, on whole single-(layer, sequence) trajectories."""
+    import oracle
+    from paper_2506_18226_amd import workloads as WL
+
+    P = wl.prefix_len
+    cfg = oracle.make_cfg(n_heads=wl.n_heads, head_dim=wl.head_dim, grid_h=wl.grid_h, grid_w=wl.grid_w,
+                          win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius, grid_origin=P,
+                          budget=wl.budget if wl.budget_den == 0 else 0, budget_num=wl.budget_num,
+                          budget_den=wl.budget_den, score_mode=wl.score_mode, cap=wl.cap())
+    done, spent = 0, 0.0
+    seq = 0
+    while spent < seconds and seq < wl.n_seq:
+        q, k, v = WL.gen_tokens(wl, 0, seq)
+        st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+        t0 = time.perf_counter()
+        for s in range(wl.n_image_tokens):
+            p = P + s - 1
+            oracle.step(cfg, st, s, q[p], k[p], v[p])
+        spent += time.perf_counter() - t0
+        done += wl.n_image_tokens
+        seq += 1
+    seq_layer_steps_per_s = done / spent
+    return {
+        "value": seq_layer_steps_per_s / n_layers, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "sample": f"complete {wl.n_image_tokens}-step trajectories of {seq} of the {wl.n_seq * n_layers} "
+                  f"(sequence, layer) caches, {spent:.1f} s of CPU time, scaled by 1/{n_layers} layers",
+        "host_cpus": os.cpu_count(),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2506_18226_amd import binding as B
+    from paper_2506_18226_amd import workloads as WL
+
+    B.load_library()                                   # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    device = "cuda:0"
+    wl = WL.get_workload(args.workload)
+    n_layers = args.layers if args.layers > 0 else wl.n_layers
+    t_setup = time.perf_counter()
+    job = Job(wl, n_layers, device)
+    torch.cuda.synchronize()
+    t_setup = time.perf_counter() - t_setup
+    S = job.n_steps_total
+    K = S if args.steps <= 0 else min(args.steps, S)
+    Wm = max(0, args.warmup)
+
+    # warm-up: Wm steps, then (whole-trajectory runs) start again from the prefix-only cache;
+    # shorter runs time the LAST K steps of the trajectory, the deepest contexts.
+    job.run(0, min(Wm, S))
+    torch.cuda.synchronize()
+    job.reset()
+    s0 = S - K
+    if s0 > 0:
+        job.run(0, s0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    job.run(s0, S)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    seq_status = np.concatenate([lb.read_seqs()["status"] for lb in job.layers])
+    assert (seq_status == 0).all(), "a sequence reported a device-side error"
+    cnt_log = job.sel_cnt_log.cpu().numpy().astype(np.int64)           # [S][layers][n_seq]
+    tau = wl.token_bytes
+    tokens = wl.n_seq * K
+    result = {
+        "metric": "adsa_decode_tokens_per_s", "value": tokens / elapsed, "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": 1e3 * elapsed / K,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {
+            "workload": f"{wl.name}: {n_layers} layers x {wl.n_seq} sequences, {wl.n_heads} heads x {wl.head_dim}, "
+                        f"{wl.dtype}, prefix {wl.prefix_len} + {wl.grid_h}x{wl.grid_w} grid, window R={wl.win_rows_back} "
+                        f"w={wl.win_col_radius}, budget "
+                        + (f"{wl.budget}" if wl.budget_den == 0 else f"{wl.budget_num}/{wl.budget_den} of context")
+                        + ", ranking=accumulated attention mass, row-end eviction",
+            "decode_steps_timed": [s0, S], "global_batch": wl.n_seq, "layers": n_layers,
+            "setup_seconds": round(t_setup, 1),
+        },
+    }
+    timed_attended = int(cnt_log[s0:S].sum())
+    result["selected_kv_gb_per_step"] = timed_attended * tau / K / 1e9
+    result["selected_kv_gbs_whole_path"] = timed_attended * tau / elapsed / 1e9
+
+    # ---- roofline of the dominant kernel: same trajectory again with HIP events around k_attend
+    if not args.no_roofline_pass:
+        job.reset()
+        if s0 > 0:
+            job.run(0, s0)
+        torch.cuda.synchronize()
+        n_after = []
+        B.adsa_profile_enable(True)
+        job.run(s0, S, on_row_end=lambda s: n_after.append(
+            (s, [int(x) for lb in job.layers for x in lb.read_seqs()["n_res"]])))
+        torch.cuda.synchronize()
+        n_launch, att_ms = B.adsa_profile_read()
+        B.adsa_profile_enable(False)
+        cnt2 = job.sel_cnt_log.cpu().numpy().astype(np.int64)
+        att_bytes = int(cnt2[s0:S].sum()) * tau
+        achieved = att_bytes / (att_ms * 1e-3) / 1e9
+        result["roofline"] = {
+            "kernel": "k_attend", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "launches": int(n_launch), "avg_launch_us": 1e3 * att_ms / max(1, n_launch),
+            "algorithmic_bytes_per_launch": att_bytes / max(1, n_launch),
+        }
+        # KV bytes resident: between row ends n_res grows by one per step
+        if n_after:
+            W = wl.grid_w
+            peaks = [sum(v) + W * len(v) for _, v in n_after]      # a row of appends follows each compaction
+            dense = (wl.prefix_len + wl.n_image_tokens) * wl.n_seq * n_layers * tau
+            result["kv_bytes_resident"] = {
+                "max": max(peaks) * tau, "after_last_compaction": sum(n_after[-1][1]) * tau,
+                "dense_cache": dense, "ratio_max_to_dense": max(peaks) * tau / dense,
+            }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, n_layers, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

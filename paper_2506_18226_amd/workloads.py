@@ -237,3 +237,45 @@ def synthetic_state(wl: Workload, layer: int, seq: int, step: int, prefix_len: i
         "score": score, "q": q_all[qpos].copy(), "k_new": k_all[qpos].copy(),
         "v_new": v_all[qpos].copy(), "prefix_len": P, "budget": B, "step": step,
     }
+
+
+# --------------------------------------------------------------------------- on-device generation
+def gen_tokens_device(wl: Workload, layer: int, device, prefix_len: int | None = None):
+    """Same recipe as gen_tokens for ALL sequences of one layer, drawn on the GPU by torch.
+
+    Used only where host generation would dominate the run (the full-size benchmark
+    trajectory).  Seeded (per workload and layer) but a different random stream than the
+    numpy generator, so never used for parity.  Returns q, k, v as torch tensors
+    [n_seq][L][h][D] in the workload's storage type.
+    """
+    import torch
+
+    P = wl.prefix_len if prefix_len is None else prefix_len
+    L = P + wl.n_image_tokens
+    n, h, D = wl.n_seq, wl.n_heads, wl.head_dim
+    g = torch.Generator(device=device)
+    g.manual_seed((wl.seed << 16) | layer)
+    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+
+    def randn(*shape):
+        return torch.randn(*shape, generator=g, device=device, dtype=torch.float32)
+
+    kind = wl.value_kind
+    if kind == "lowrank8":
+        rank = 8
+        M = randn(n, h, D, rank)
+        U = randn(n, L, h, rank)
+        A = randn(n, L, h, rank)
+        k = torch.einsum("nlhr,nhdr->nlhd", U, M) / rank ** 0.5 + 0.1 * randn(n, L, h, D)
+        q = torch.einsum("nlhr,nhdr->nlhd", A, M) / rank ** 0.5 + 0.1 * randn(n, L, h, D)
+        v = randn(n, L, h, D)
+    else:
+        q = randn(n, L, h, D) * wl.value_scale
+        k = randn(n, L, h, D) * wl.value_scale
+        v = randn(n, L, h, D) * wl.value_scale
+        if kind == "tiny_sink":
+            k[:, :4] *= 4.0
+        elif kind == "outlier2pct":
+            mask = torch.rand(n, L, generator=g, device=device) < 0.02
+            k[mask] *= 3.0
+    return q.to(tdt), k.to(tdt), v.to(tdt)
