@@ -6,16 +6,18 @@
  * (paper Section 4.1) restricted to prefix + local window + globally ranked
  * tokens, and the dynamic KV-cache update that evicts and compacts
  * (Section 4.2).  Every entry point only ENQUEUES work on the caller's HIP
- * stream: no host synchronisation, no allocation, no global state.  The
- * library never touches host memory behind the pointers it is given except
- * `adsa_params` (a host struct, read during the call).
+ * stream: no host synchronisation, no allocation, no global state (the
+ * optional timing hook at the end of this file aside).  The library never
+ * touches host memory behind the pointers it is given except `adsa_params`
+ * (a host struct, read during the call).
  *
  * Pointers are DEVICE pointers owned by the caller unless marked [host].
  * Return value: ADSA_OK or a negative adsa_status; argument errors are found
  * on the host before anything is launched.  Conditions only the device can see
  * (a full cache, a malformed state) set `adsa_seq.status` of that sequence,
- * which the caller reads when it next synchronises; such a sequence is left
- * unchanged and its output row is zero-filled.
+ * which the caller reads when it next synchronises; such a sequence is
+ * skipped by every call until the caller clears the status, and its output
+ * row is zero-filled.
  *
  * Cache layout.  Element (slot, head, d) of a sequence's K (same for V) lives
  * at  k + slot*kv_slot_stride + head*kv_head_stride + d  (strides in
@@ -72,9 +74,15 @@ typedef enum {
 #define ADSA_SEQ_BAD_STATE     2   /* n_res/step out of range, or an entry newer than the query */
 #define ADSA_SEQ_SEL_OVERFLOW  4   /* attended set larger than sel_cap */
 
-/* adsa_step / adsa_attend flags. */
-#define ADSA_FLAG_NO_COMPACT   1u  /* caller guarantees no sequence closes a grid row in this step */
-#define ADSA_FLAG_NO_ACCUMULATE 2u /* adsa_attend: do not add attention mass to score[] */
+/* Flags of adsa_select / adsa_attend / adsa_compact / adsa_step. */
+#define ADSA_FLAG_NO_COMPACT    1u  /* caller guarantees no sequence closes a grid row in this step */
+#define ADSA_FLAG_NO_ACCUMULATE 2u  /* adsa_attend: do not add attention mass to score[] */
+#define ADSA_FLAG_PLAN_APPEND   4u  /* adsa_select: rank as if the query token already sat at slot n_res
+                                       (it is always local); adsa_attend with ADSA_FLAG_APPEND puts it there */
+#define ADSA_FLAG_APPEND        8u  /* adsa_attend: append (k_new, v_new) at slot n_res while attending */
+#define ADSA_FLAG_ADVANCE      16u  /* adsa_attend / adsa_compact: step += 1 for every active sequence when
+                                       the call is done; give it to the LAST call of a decode step only
+                                       (adsa_compact tests the row end on the step before the increment) */
 
 /* [host] Launch-wide parameters (Section 4.1's n, m, K and the problem shape). */
 typedef struct adsa_params {
@@ -115,8 +123,17 @@ typedef struct adsa_seq {
   int32_t  reserved[3];
 } adsa_seq;
 
-/* Bytes of device scratch the attend/step entry points need for these parameters. */
+/* Bytes of device scratch the entry points need for these parameters (0 if they are invalid). */
 size_t adsa_workspace_bytes(const adsa_params* p);
+
+/*
+ * Prepare a workspace (256-byte aligned, >= adsa_workspace_bytes(p)) for use with parameters p:
+ * zeroes the arrival counters at its head with a small fill kernel on `stream`.  Call it once
+ * after allocating the workspace and again before using the same memory with different
+ * parameters; every later call leaves the counters zero.  A workspace may be shared by calls
+ * that are ordered on one stream, not by concurrent ones.
+ */
+int adsa_workspace_init(const adsa_params* p, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Eq. 1 + Eq. 4: partition every sequence's resident slots into prefix / local / candidate for
@@ -124,12 +141,15 @@ size_t adsa_workspace_bytes(const adsa_params* p);
  *   PREFIX u LOCAL u top-min(B, |candidates|)
  * as an ascending slot list.  Ties go to the lower slot; -0 == +0; NaN scores are a
  * precondition violation.  Reads seqs[].pos/score/n_res/step; VCOS mode first writes Eq. 3's
- * S_i into score[] at the candidate slots (reads V).
+ * S_i into score[] at the candidate slots (reads V, needs the workspace; other modes accept a
+ * NULL workspace).  The ranking does not depend on the query token's q/k/v, so one call may
+ * cover the sequences of every layer of a model (n_seq = layers x batch) before the layers run.
+ * flags: ADSA_FLAG_PLAN_APPEND.
  *   sel_idx  int32 [n_seq][sel_cap]   out
  *   sel_cnt  int32 [n_seq]            out
  */
 int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
-                void* workspace, size_t workspace_bytes, void* stream);
+                uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Eq. 5 + attention: per sequence and head, softmax(q.K_sel^T * scale) V_sel over the slots
@@ -137,12 +157,17 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
  *   q    dtype [n_seq][n_heads][head_dim]
  *   out  dtype [n_seq][n_heads][head_dim]
  *   lse  float [n_seq][n_heads]   natural-log sum-exp of the scaled logits
- * Unless ADSA_FLAG_NO_ACCUMULATE is set and for ADSA_SCORE_ATTN_MASS only, score[slot] of every
- * attended slot gains the probability it received summed over heads (ascending head order).
+ *   k_new, v_new  dtype [n_seq][n_heads][head_dim], only read with ADSA_FLAG_APPEND (else may be NULL)
+ * For ADSA_SCORE_ATTN_MASS and unless ADSA_FLAG_NO_ACCUMULATE is set, score[slot] of every
+ * attended slot gains the probability it received summed over heads.
+ * ADSA_FLAG_APPEND (Section 4.2, "appended to the end of the cache"): for sequences with
+ * step >= 1 the row (k_new, v_new) is written to slot n_res, pos = P+s-1, score starts at 0,
+ * n_res += 1; sel_idx must come from adsa_select with ADSA_FLAG_PLAN_APPEND.
+ * flags: ADSA_FLAG_NO_ACCUMULATE, ADSA_FLAG_APPEND, ADSA_FLAG_ADVANCE.
  */
-int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const int32_t* sel_idx,
-                const int32_t* sel_cnt, void* out, float* lse, uint32_t flags,
-                void* workspace, size_t workspace_bytes, void* stream);
+int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
+                const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt, void* out,
+                float* lse, uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Section 4.2 in per-row form.  For every sequence whose query token closes a grid row
@@ -150,27 +175,29 @@ int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const int32
  * the top min(B, |rest|) of the rest by the same ranking as adsa_select; write
  *   keep_map int32 [n_seq][cap]: new slot of old slot i, or -1 (entries >= old n_res untouched)
  * move K, V, pos, score rows to the front in place, order preserved, and set n_res, compacted.
- * Other sequences are untouched (compacted = 0, keep_map row untouched).
+ * Other sequences are untouched (compacted = 0, keep_map row untouched).  Like adsa_select it
+ * may cover every layer's sequences in one call.  flags: ADSA_FLAG_ADVANCE.
  */
-int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map,
+int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map, uint32_t flags,
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * One whole decode step of one layer: append (k_new, v_new) of the query token at slot n_res
- * (pos = P+s-1, score = 0; skipped when s == 0), select, attend, accumulate attention mass
- * (ATTN_MASS), evict+compact the sequences that closed a row, then step += 1.
- *   k_new, v_new  dtype [n_seq][n_heads][head_dim]
- * Outputs as in the three calls above; keep_map may be NULL only with ADSA_FLAG_NO_COMPACT.
+ * One whole decode step of one layer, in one call: adsa_select(PLAN_APPEND), adsa_attend(APPEND)
+ * and, unless ADSA_FLAG_NO_COMPACT, adsa_compact in stream order, the last of them advancing: the query
+ * token is appended at slot n_res (skipped when s == 0), the attended set is chosen and attended,
+ * attention mass is accumulated (ATTN_MASS), sequences that closed a row are evicted+compacted,
+ * and step += 1.  keep_map may be NULL only with ADSA_FLAG_NO_COMPACT.
  */
 int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
               const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
               int32_t* keep_map, uint32_t flags, void* workspace, size_t workspace_bytes,
               void* stream);
 
-/* Timing hook for benchmarks: when enabled, adsa_attend/adsa_step bracket the attention kernel
-   with HIP events on the caller's stream.  adsa_profile_read synchronises those events and
-   returns, through its arguments, the number of bracketed launches and their summed duration
-   in milliseconds since the last adsa_profile_enable(1); [host] pointers. */
+/* Timing hook for benchmarks: when enabled, adsa_attend/adsa_step attach a start and a stop HIP
+   event to every attention-kernel dispatch on the caller's stream.  adsa_profile_read
+   synchronises those events and returns, through its arguments, the number of timed launches and
+   their summed duration in milliseconds since the last adsa_profile_enable(1); [host] pointers.
+   Process-wide state, not thread-safe. */
 int adsa_profile_enable(int on);
 int adsa_profile_read(int64_t* n_launches, double* total_ms);
 

@@ -63,7 +63,8 @@ class LayerBatch:
         ws = B.adsa_workspace_bytes(p)
         if ws == 0:
             raise B.AdsaError(-2, "adsa_workspace_bytes (invalid parameters)")
-        self.workspace = torch.zeros(ws, dtype=torch.uint8, device=dev)
+        self.workspace = torch.empty(ws, dtype=torch.uint8, device=dev)
+        B.adsa_workspace_init(p, self.workspace)
 
     # ---- host -> device
     def set_sequence(self, b: int, *, k: np.ndarray, v: np.ndarray, pos: np.ndarray,
@@ -97,16 +98,48 @@ class LayerBatch:
         return self.seqs_host
 
     # ---- thin forwards to the C ABI
-    def select(self, stream=None):
-        B.adsa_select(self.params, self.seqs, self.sel_idx, self.sel_cnt, self.workspace, stream)
+    def select(self, flags: int = 0, stream=None):
+        B.adsa_select(self.params, self.seqs, self.sel_idx, self.sel_cnt, self.workspace, flags, stream)
 
-    def attend(self, q: torch.Tensor, flags: int = 0, stream=None):
+    def attend(self, q: torch.Tensor, flags: int = 0, k_new=None, v_new=None, stream=None):
         B.adsa_attend(self.params, self.seqs, q, self.sel_idx, self.sel_cnt, self.out, self.lse,
-                      self.workspace, flags, stream)
+                      self.workspace, flags, k_new, v_new, stream)
 
-    def compact(self, stream=None):
-        B.adsa_compact(self.params, self.seqs, self.keep_map, self.workspace, stream)
+    def compact(self, flags: int = 0, stream=None):
+        B.adsa_compact(self.params, self.seqs, self.keep_map, self.workspace, flags, stream)
 
     def step(self, q, k_new, v_new, flags: int = 0, stream=None):
         B.adsa_step(self.params, self.seqs, q, k_new, v_new, self.out, self.lse, self.sel_idx, self.sel_cnt,
                     self.keep_map, self.workspace, flags, stream)
+
+
+class ModelBatch(LayerBatch):
+    """Caches of ALL layers of a model for one decode batch, laid out as n_layers * n_seq
+    independent sequences (layer-major), so that the q-independent phases of a decode step
+    (adsa_select, adsa_compact) run once for every layer while adsa_attend runs per layer on
+    its slice of the same arrays."""
+
+    def __init__(self, layer_params: B.AdsaParams, n_layers: int, device: str = "cuda:0"):
+        import copy
+        self.layer_params = layer_params
+        self.n_layers = n_layers
+        self.n_per_layer = layer_params.n_seq
+        total = copy.copy(layer_params)
+        total.n_seq = layer_params.n_seq * n_layers
+        super().__init__(total, device)
+        ws = B.adsa_workspace_bytes(layer_params)
+        self.layer_workspace = torch.empty(ws, dtype=torch.uint8, device=self.device)
+        B.adsa_workspace_init(layer_params, self.layer_workspace)
+
+    def select_all(self, flags: int = 0, stream=None):
+        B.adsa_select(self.params, self.seqs, self.sel_idx, self.sel_cnt, self.workspace, flags, stream)
+
+    def compact_all(self, flags: int = 0, stream=None):
+        B.adsa_compact(self.params, self.seqs, self.keep_map, self.workspace, flags, stream)
+
+    def attend_layer(self, layer: int, q, k_new=None, v_new=None, flags: int = 0, stream=None):
+        n, p = self.n_per_layer, self.layer_params
+        b0 = layer * n
+        B.adsa_attend(p, self.seqs.data_ptr() + b0 * B.SEQ_DTYPE.itemsize, q,
+                      self.sel_idx.data_ptr() + b0 * p.sel_cap * 4, self.sel_cnt.data_ptr() + b0 * 4,
+                      self.out[b0:b0 + n], self.lse[b0:b0 + n], self.layer_workspace, flags, k_new, v_new, stream)

@@ -16,14 +16,14 @@ from . import build as _build
 
 F32, BF16 = 0, 1
 SCORE_ATTN_MASS, SCORE_VCOS, SCORE_EXT_LARGEST, SCORE_EXT_SMALLEST = 0, 1, 2, 3
-FLAG_NO_COMPACT, FLAG_NO_ACCUMULATE = 1, 2
+FLAG_NO_COMPACT, FLAG_NO_ACCUMULATE, FLAG_PLAN_APPEND, FLAG_APPEND, FLAG_ADVANCE = 1, 2, 4, 8, 16
 SEQ_CACHE_FULL, SEQ_BAD_STATE, SEQ_SEL_OVERFLOW = 1, 2, 4
 MAX_CAP = 8192
 
 ERRORS = {0: "ADSA_OK", -1: "ADSA_ERR_NULL", -2: "ADSA_ERR_SHAPE", -3: "ADSA_ERR_DTYPE", -4: "ADSA_ERR_ALIGN",
           -5: "ADSA_ERR_CAPACITY", -6: "ADSA_ERR_WORKSPACE", -7: "ADSA_ERR_LAUNCH", -8: "ADSA_ERR_UNSUPPORTED"}
 
-EXPORTS = ["adsa_workspace_bytes", "adsa_select", "adsa_attend", "adsa_compact", "adsa_step",
+EXPORTS = ["adsa_workspace_bytes", "adsa_workspace_init", "adsa_select", "adsa_attend", "adsa_compact", "adsa_step",
            "adsa_profile_enable", "adsa_profile_read", "adsa_strerror", "adsa_version"]
 
 
@@ -76,12 +76,14 @@ def load_library() -> C.CDLL:
         pp = C.POINTER(AdsaParams)
         lib.adsa_workspace_bytes.restype = C.c_size_t
         lib.adsa_workspace_bytes.argtypes = [pp]
+        lib.adsa_workspace_init.restype = C.c_int
+        lib.adsa_workspace_init.argtypes = [pp, vp, C.c_size_t, vp]
         lib.adsa_select.restype = C.c_int
-        lib.adsa_select.argtypes = [pp, vp, i32p, i32p, vp, C.c_size_t, vp]
+        lib.adsa_select.argtypes = [pp, vp, i32p, i32p, C.c_uint32, vp, C.c_size_t, vp]
         lib.adsa_attend.restype = C.c_int
-        lib.adsa_attend.argtypes = [pp, vp, vp, i32p, i32p, vp, f32p, C.c_uint32, vp, C.c_size_t, vp]
+        lib.adsa_attend.argtypes = [pp, vp, vp, vp, vp, i32p, i32p, vp, f32p, C.c_uint32, vp, C.c_size_t, vp]
         lib.adsa_compact.restype = C.c_int
-        lib.adsa_compact.argtypes = [pp, vp, i32p, vp, C.c_size_t, vp]
+        lib.adsa_compact.argtypes = [pp, vp, i32p, C.c_uint32, vp, C.c_size_t, vp]
         lib.adsa_step.restype = C.c_int
         lib.adsa_step.argtypes = [pp, vp, vp, vp, vp, vp, f32p, i32p, i32p, i32p, C.c_uint32, vp, C.c_size_t, vp]
         lib.adsa_profile_enable.restype = C.c_int
@@ -148,19 +150,25 @@ def adsa_workspace_bytes(params: AdsaParams) -> int:
     return int(load_library().adsa_workspace_bytes(C.byref(params)))
 
 
-def adsa_select(params, seqs, sel_idx, sel_cnt, workspace=None, stream=None) -> None:
-    _check(load_library().adsa_select(C.byref(params), _ptr(seqs), _ptr(sel_idx), _ptr(sel_cnt),
+def adsa_workspace_init(params, workspace, stream=None) -> None:
+    _check(load_library().adsa_workspace_init(C.byref(params), _ptr(workspace), _nbytes(workspace),
+                                              _stream(stream)), "adsa_workspace_init")
+
+
+def adsa_select(params, seqs, sel_idx, sel_cnt, workspace=None, flags=0, stream=None) -> None:
+    _check(load_library().adsa_select(C.byref(params), _ptr(seqs), _ptr(sel_idx), _ptr(sel_cnt), flags,
                                       _ptr(workspace), _nbytes(workspace), _stream(stream)), "adsa_select")
 
 
-def adsa_attend(params, seqs, q, sel_idx, sel_cnt, out, lse, workspace, flags=0, stream=None) -> None:
-    _check(load_library().adsa_attend(C.byref(params), _ptr(seqs), _ptr(q), _ptr(sel_idx), _ptr(sel_cnt),
-                                      _ptr(out), _ptr(lse), flags, _ptr(workspace), _nbytes(workspace),
-                                      _stream(stream)), "adsa_attend")
+def adsa_attend(params, seqs, q, sel_idx, sel_cnt, out, lse, workspace, flags=0, k_new=None, v_new=None,
+                stream=None) -> None:
+    _check(load_library().adsa_attend(C.byref(params), _ptr(seqs), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                      _ptr(sel_idx), _ptr(sel_cnt), _ptr(out), _ptr(lse), flags,
+                                      _ptr(workspace), _nbytes(workspace), _stream(stream)), "adsa_attend")
 
 
-def adsa_compact(params, seqs, keep_map, workspace, stream=None) -> None:
-    _check(load_library().adsa_compact(C.byref(params), _ptr(seqs), _ptr(keep_map), _ptr(workspace),
+def adsa_compact(params, seqs, keep_map, workspace, flags=0, stream=None) -> None:
+    _check(load_library().adsa_compact(C.byref(params), _ptr(seqs), _ptr(keep_map), flags, _ptr(workspace),
                                        _nbytes(workspace), _stream(stream)), "adsa_compact")
 
 

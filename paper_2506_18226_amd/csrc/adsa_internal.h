@@ -28,12 +28,17 @@ struct AttendPlan {
 
 // Workspace layout (byte offsets from a 256-byte aligned base).
 struct Workspace {
-  size_t logits_off;    // float [n_seq][n_heads][sel_cap]   scaled logits in log2 units
-  size_t partial_off;   // float [n_seq][n_heads][n_chunks][head_dim + 2]   (m, l, acc[D]) per chunk
-  size_t plan_off;      // int32 [n_seq][4]   compaction: old n_res, first moved slot, did, new n_res
-  size_t vcos_off;      // float [n_seq][cap]   inverse V norms of the candidates (0 = not a candidate)
-  size_t vcos_u_off;    // float [n_seq][ceil(cap/64)][n_heads*head_dim]   per-tile partial sums of v^
+  size_t counters_off;     // int32 [n_seq][n_head_groups + 1]  arrival counters (zero between launches)
+  size_t persistent_bytes; // leading bytes that adsa_workspace_init zeroes and every launch leaves zero
+  size_t logits_off;       // float [n_seq][n_heads][lg_stride]  scaled logits in log2 units
+  size_t psum_off;         // float [n_seq][n_head_groups][lg_stride]  probability summed over a head group
+  size_t part_ml_off;      // float [n_seq][n_heads][n_chunks][2]   (m, l) per chunk
+  size_t part_acc_off;     // float [n_seq][n_heads][n_chunks][head_dim]
+  size_t plan_off;         // int32 [n_seq][4]   compaction: old n_res, first moved slot, did, new n_res
+  size_t vcos_off;         // float [n_seq][cap]   inverse V norms of the candidates (0 = not a candidate)
+  size_t vcos_u_off;       // float [n_seq][ceil(cap/64)][n_heads*head_dim]   per-tile partial sums of v^
   size_t total;
+  int lg_stride;           // sel_cap rounded up to a multiple of 4
 };
 
 AttendPlan make_attend_plan(const adsa_params& p);
@@ -42,17 +47,16 @@ Workspace make_workspace(const adsa_params& p, const AttendPlan& plan);
 static inline int elem_bytes(const adsa_params& p) { return p.dtype == ADSA_F32 ? 4 : 2; }
 
 // Kernel launchers (each returns hipGetLastError() of its launch).
+hipError_t launch_workspace_init(char* ws, const Workspace& w, hipStream_t st);
 hipError_t launch_select(const adsa_params& p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
-                         const void* k_new, const void* v_new, bool append, hipStream_t st);
+                         bool plan_append, hipStream_t st);
 hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction, char* ws,
                        const Workspace& w, hipStream_t st);
 int vcos_tiles(int cap);
-hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, const adsa_seq* seqs, const void* q,
-                         const int32_t* sel_idx, const int32_t* sel_cnt, char* ws, const Workspace& w,
-                         bool want_logits, hipStream_t st);
-hipError_t launch_combine(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs,
-                          const int32_t* sel_idx, const int32_t* sel_cnt, void* out, float* lse,
-                          char* ws, const Workspace& w, bool accumulate, bool advance_step, hipStream_t st);
+hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
+                         const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
+                         void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
+                         bool advance, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_map, char* ws,
                           const Workspace& w, bool advance_step, hipStream_t st);
 

@@ -61,18 +61,18 @@ hipEvent_t prof_event() {
   return g_prof.ev[g_prof.used++];
 }
 
-hipError_t timed_attend(const adsa_params& p, const AttendPlan& plan, const adsa_seq* seqs, const void* q,
-                        const int32_t* sel_idx, const int32_t* sel_cnt, char* ws, const Workspace& w,
-                        bool want_logits, hipStream_t st) {
+hipError_t timed_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
+                        const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
+                        void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
+                        bool advance, hipStream_t st) {
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (g_prof.on) {
     e0 = prof_event();
     e1 = prof_event();
-    if (e0 && e1) (void)hipEventRecord(e0, st);
+    if (!e0 || !e1) e0 = e1 = nullptr;
   }
-  hipError_t e = launch_attend(p, plan, seqs, q, sel_idx, sel_cnt, ws, w, want_logits, st);
-  if (e0 && e1) (void)hipEventRecord(e1, st);
-  return e;
+  return launch_attend(p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, ws, w, accumulate, append,
+                       advance, st, e0, e1);
 }
 
 }  // namespace
@@ -105,8 +105,19 @@ size_t adsa_workspace_bytes(const adsa_params* p) {
   return make_workspace(*p, plan).total;
 }
 
+int adsa_workspace_init(const adsa_params* p, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = validate_params(p);
+  if (rc) return rc;
+  AttendPlan plan; Workspace w;
+  rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
+  if (rc) return rc;
+  if (launch_workspace_init((char*)workspace, w, reinterpret_cast<hipStream_t>(stream)) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
+  return ADSA_OK;
+}
+
 int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
-                void* workspace, size_t workspace_bytes, void* stream) {
+                uint32_t flags, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = validate_params(p);
   if (rc) return rc;
   if (!seqs || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
@@ -117,31 +128,33 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
     if (rc) return rc;
     if (launch_vcos(*p, seqs, false, (char*)workspace, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
   }
-  if (launch_select(*p, seqs, sel_idx, sel_cnt, nullptr, nullptr, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  if (launch_select(*p, seqs, sel_idx, sel_cnt, (flags & ADSA_FLAG_PLAN_APPEND) != 0, st) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
   return ADSA_OK;
 }
 
-int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const int32_t* sel_idx,
-                const int32_t* sel_cnt, void* out, float* lse, uint32_t flags,
-                void* workspace, size_t workspace_bytes, void* stream) {
+int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
+                const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt, void* out,
+                float* lse, uint32_t flags, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = validate_params(p);
   if (rc) return rc;
   if (!seqs || !q || !sel_idx || !sel_cnt || !out || !lse) return ADSA_ERR_NULL;
+  const bool append = (flags & ADSA_FLAG_APPEND) != 0;
+  if (append && (!k_new || !v_new)) return ADSA_ERR_NULL;
   if (!aligned16(q) || !aligned16(out)) return ADSA_ERR_ALIGN;
+  if (append && (!aligned16(k_new) || !aligned16(v_new))) return ADSA_ERR_ALIGN;
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
   if (rc) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS && !(flags & ADSA_FLAG_NO_ACCUMULATE);
-  if (timed_attend(*p, plan, seqs, q, sel_idx, sel_cnt, (char*)workspace, w, accumulate, st) != hipSuccess)
-    return ADSA_ERR_LAUNCH;
-  if (launch_combine(*p, plan, seqs, sel_idx, sel_cnt, out, lse, (char*)workspace, w, accumulate, false, st) !=
-      hipSuccess)
+  if (timed_attend(*p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, (char*)workspace, w, accumulate,
+                   append, (flags & ADSA_FLAG_ADVANCE) != 0, st) != hipSuccess)
     return ADSA_ERR_LAUNCH;
   return ADSA_OK;
 }
 
-int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map,
+int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map, uint32_t flags,
                  void* workspace, size_t workspace_bytes, void* stream) {
   int rc = validate_params(p);
   if (rc) return rc;
@@ -153,7 +166,8 @@ int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map,
   if (p->score_mode == ADSA_SCORE_VCOS &&
       launch_vcos(*p, seqs, true, (char*)workspace, w, st) != hipSuccess)
     return ADSA_ERR_LAUNCH;
-  if (launch_compact(*p, seqs, keep_map, (char*)workspace, w, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  if (launch_compact(*p, seqs, keep_map, (char*)workspace, w, (flags & ADSA_FLAG_ADVANCE) != 0, st) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
   return ADSA_OK;
 }
 
@@ -175,10 +189,9 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
   const bool vcos = p->score_mode == ADSA_SCORE_VCOS;
   const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS;
   if (vcos && launch_vcos(*p, seqs, false, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
-  if (launch_select(*p, seqs, sel_idx, sel_cnt, k_new, v_new, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
-  if (timed_attend(*p, plan, seqs, q, sel_idx, sel_cnt, ws, w, accumulate, st) != hipSuccess)
-    return ADSA_ERR_LAUNCH;
-  if (launch_combine(*p, plan, seqs, sel_idx, sel_cnt, out, lse, ws, w, accumulate, !compact, st) != hipSuccess)
+  if (launch_select(*p, seqs, sel_idx, sel_cnt, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  if (timed_attend(*p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, ws, w, accumulate, true,
+                   !compact, st) != hipSuccess)
     return ADSA_ERR_LAUNCH;
   if (compact) {
     if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;

@@ -1,16 +1,23 @@
 // Gather flash-decode of the ADSA decode path (gfx950): Eq. 5's gather fused with softmax
-// attention over the selected slots, split over the index list.
+// attention over the selected slots, split over the index list, with the cache append
+// (Section 4.2), the split merge and the attention-mass update fused into the same launch.
 //
-//  k_attend  : grid (token chunk, head group, sequence).  Every sequence splits ITS OWN attended
-//              count evenly over the chunks.  A wave reads one token's rows for `heads_per_wave`
-//              heads with a single 16-byte-per-lane load (1 KiB contiguous in [slot][head][D]
-//              layout), reduces q.k over the lanes of a row with DPP, and keeps an online-softmax
-//              state (m, l, acc) in registers, fp32, log2 domain.  The four waves of a workgroup
-//              interleave the chunk's tokens and merge through LDS; one partial per
-//              (sequence, head, chunk) goes to the workspace together with the scaled logits.
-//  k_combine : merges the chunk partials into out / lse and (ATTN_MASS) adds the probability each
-//              attended slot received, summed over heads in ascending order, to score[].
+//  k_attend : grid (token chunk, head group, sequence).  Every sequence splits ITS OWN attended
+//             count evenly over the chunks.  A wave reads one token's rows for `heads_per_wave`
+//             heads with a single streaming 16-byte-per-lane load (1 KiB contiguous in
+//             [slot][head][D] layout), reduces q.k over the lanes of a row with DPP, and keeps an
+//             online-softmax state (m, l, acc) in registers, fp32, log2 domain.  The four waves of
+//             a workgroup interleave the chunk's tokens and merge through LDS; one partial per
+//             (sequence, head, chunk) and the scaled logits go to the workspace.
+//             The LAST workgroup to finish a (sequence, head group) merges its partials into
+//             out / lse and sums, per attended token, the probability over its heads; the LAST
+//             head group of a sequence adds those sums to score[] in head-group order, finishes the
+//             append (pos, n_res) and advances the step.  "Last" is decided by an arrival counter
+//             after a device-scope fence, so nothing ever waits on another workgroup.
+#include <hip/hip_ext.h>
+
 #include "adsa_internal.h"
+#include "adsa_partition.h"
 
 namespace adsa {
 namespace {
@@ -34,6 +41,13 @@ __device__ __forceinline__ float row_sum(float x) {
   if (LPR >= 16) x += dpp_f<0x140>(x);   // row_mirror: the other half of the 16-lane row
   if (LPR >= 32) x += __shfl_xor(x, 16, kWave);
   return x;
+}
+
+// 16-byte streaming load: K/V rows are read once per step, so keep them out of the caches' way
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const char* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
 }
 
 template <int EB> struct Elems;
@@ -60,15 +74,26 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// chunk c of a list of cnt tokens split evenly over nc chunks
+__device__ __forceinline__ int chunk_begin(int cnt, int c, int nc) { return (int)(((long long)cnt * c) / nc); }
+
 struct AttendArgs {
-  const adsa_seq* seqs;
+  adsa_seq* seqs;
   const char* q;
+  const char* k_new;
+  const char* v_new;
   const int32_t* sel_idx;
   const int32_t* sel_cnt;
-  float* logits;        // [n_seq][n_heads][sel_cap]
+  char* out;
+  float* lse;
+  float* logits;        // [n_seq][n_heads][lg_stride]   scaled logits, log2 units
   float* part_ml;       // [n_seq][n_heads][n_chunks][2]
   float* part_acc;      // [n_seq][n_heads][n_chunks][D]
-  int n_heads, sel_cap, chunk_max, want_logits, cap;
+  float* psum;          // [n_seq][n_hg][lg_stride]      per head group: sum over its heads of p
+  int32_t* counters;    // [n_seq][n_hg + 1]             arrival counters, zero between launches
+  int n_heads, n_hg, sel_cap, lg_stride, chunk_max, cap;
+  int grid_h, grid_w;
+  int accumulate, append, advance;     // advance: step += 1 at the end
   long long slot_stride_b, head_stride_b;
   float scale_log2;     // softmax scale * log2(e)
 };
@@ -81,31 +106,50 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   extern __shared__ float s_dyn[];                  // logits tile [HPW][chunk_max]
   __shared__ float s_m[kAttWaves][HPW], s_l[kAttWaves][HPW];
   __shared__ float s_acc[kAttWaves][kWave][EPL];
+  __shared__ float s_lse2[HPW];
+  __shared__ int s_ticket;
 
   const int chunk = blockIdx.x, hg = blockIdx.y, b = blockIdx.z, n_chunks = gridDim.x;
-  const int cnt = min(A.sel_cnt[b], A.sel_cap);
-  if (cnt <= 0) return;
-  const int t_begin = (int)(((long long)cnt * chunk) / n_chunks);
-  const int t_end = (int)(((long long)cnt * (chunk + 1)) / n_chunks);
-  if (t_begin >= t_end) return;                     // fewer tokens than chunks
-
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int cnt = min(A.sel_cnt[b], A.sel_cap);
+  if (cnt <= 0) {                                   // inactive or rejected sequence: zero-filled row
+    if (chunk == 0) {
+      for (int o = tid; o < HPW * D; o += kAttThreads) {
+        const int head = hg * HPW + o / D;
+        if (head < A.n_heads) {
+          const size_t oi = ((size_t)b * A.n_heads + head) * D + (o % D);
+          if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = 0.0f;
+          else reinterpret_cast<uint16_t*>(A.out)[oi] = 0;
+          if (o % D == 0) A.lse[(size_t)b * A.n_heads + head] = 0.0f;
+        }
+      }
+    }
+    return;
+  }
+  const int t_begin = chunk_begin(cnt, chunk, n_chunks), t_end = chunk_begin(cnt, chunk + 1, n_chunks);
+  if (t_begin >= t_end) return;                     // fewer tokens than chunks
+  const int n_nonempty = min(cnt, n_chunks);
+
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int sub = lane / LPR, dl = lane - sub * LPR;
   const int head = hg * HPW + sub;
   const bool head_ok = head < A.n_heads;
   const int head_c = head_ok ? head : A.n_heads - 1;
 
-  const adsa_seq& sq = A.seqs[b];
+  adsa_seq& sq = A.seqs[b];
+  const int step = sq.step, n_res = sq.n_res;
+  const int new_slot = (A.append && step >= 1) ? n_res : -1;   // n_res is bumped by the very last workgroup
   float qf[EPL];
+  const size_t row_off = ((size_t)b * A.n_heads + head_c) * D * EB + dl * 16;
   {
-    const uint4 qr = reinterpret_cast<const uint4*>(A.q + ((size_t)b * A.n_heads + head_c) * D * EB)[dl];
+    const uint4 qr = *reinterpret_cast<const uint4*>(A.q + row_off);
     Elems<EB>::unpack(qr, qf);
 #pragma unroll
     for (int e = 0; e < EPL; ++e) qf[e] *= A.scale_log2;
   }
-  const char* kb = reinterpret_cast<const char*>(sq.k) + (long long)head_c * A.head_stride_b + dl * 16;
-  const char* vb = reinterpret_cast<const char*>(sq.v) + (long long)head_c * A.head_stride_b + dl * 16;
+  const long long lane_off = (long long)head_c * A.head_stride_b + dl * 16;
+  char* kb = reinterpret_cast<char*>(sq.k) + lane_off;
+  char* vb = reinterpret_cast<char*>(sq.v) + lane_off;
   const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
 
   float m = -INFINITY, l = 0.0f, acc[EPL];
@@ -117,10 +161,19 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int tt = min(t + u, t_end - 1);         // wave-uniform: scalar index load
-      const int slot = min(max(idx[tt], 0), A.cap - 1);   // never read outside the cache
-      const long long off = (long long)slot * A.slot_stride_b;
-      kr[u] = *reinterpret_cast<const uint4*>(kb + off);
-      vr[u] = *reinterpret_cast<const uint4*>(vb + off);
+      const int slot = min(max(idx[tt], 0), A.cap - 1);   // never touch memory outside the cache
+      if (slot == new_slot) {                       // the query token itself: take it from k_new / v_new
+        kr[u] = *reinterpret_cast<const uint4*>(A.k_new + row_off);
+        vr[u] = *reinterpret_cast<const uint4*>(A.v_new + row_off);
+        if (head_ok && t + u < t_end) {             // ... and append it to the cache (Section 4.2)
+          *reinterpret_cast<uint4*>(kb + (long long)slot * A.slot_stride_b) = kr[u];
+          *reinterpret_cast<uint4*>(vb + (long long)slot * A.slot_stride_b) = vr[u];
+        }
+      } else {
+        const long long off = (long long)slot * A.slot_stride_b;
+        kr[u] = load_stream16(kb + off);
+        vr[u] = load_stream16(vb + off);
+      }
     }
     float z[U];
     float m_new = m;
@@ -135,7 +188,7 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
       z[u] = (t + u < t_end) ? d : -INFINITY;
       m_new = fmaxf(m_new, z[u]);
     }
-    if (A.want_logits && dl == 0) {
+    if (A.accumulate && dl == 0) {
 #pragma unroll
       for (int u = 0; u < U; ++u)
         if (t + u < t_end) s_dyn[sub * A.chunk_max + (t + u - t_begin)] = z[u];
@@ -156,7 +209,7 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
     m = m_new;
   }
 
-  // merge the four waves through LDS
+  // ---- merge the four waves through LDS, one partial per (head, chunk) to the workspace
   if (dl == 0) { s_m[wave][sub] = m; s_l[wave][sub] = l; }
 #pragma unroll
   for (int e = 0; e < EPL; ++e) s_acc[wave][lane][e] = acc[e];
@@ -182,87 +235,108 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
     for (int e = 0; e < EPL; e += 4)
       *reinterpret_cast<float4*>(pa + e) = make_float4(at[e], at[e + 1], at[e + 2], at[e + 3]);
   }
-  if (A.want_logits) {
+  if (A.accumulate) {
     const int len = t_end - t_begin;
     for (int i = tid; i < HPW * len; i += kAttThreads) {
       const int sb = i / len, j = i - sb * len;
       const int hd = hg * HPW + sb;
       if (hd < A.n_heads)
-        A.logits[((size_t)b * A.n_heads + hd) * A.sel_cap + t_begin + j] = s_dyn[sb * A.chunk_max + j];
+        A.logits[((size_t)b * A.n_heads + hd) * A.lg_stride + t_begin + j] = s_dyn[sb * A.chunk_max + j];
     }
   }
-}
 
-struct CombineArgs {
-  adsa_seq* seqs;
-  const int32_t* sel_idx;
-  const int32_t* sel_cnt;
-  const float* logits;
-  const float* part_ml;
-  const float* part_acc;
-  char* out;
-  float* lse;
-  int n_heads, head_dim, sel_cap, n_chunks, elem_bytes, accumulate, advance_step, cap;
-};
-
-constexpr int kCombineThreads = 256;
-constexpr int kMaxHeads = 256;
-
-__global__ __launch_bounds__(kCombineThreads) void k_combine(CombineArgs A) {
-  __shared__ float s_lse2[kMaxHeads];
-  const int b = blockIdx.x, tid = threadIdx.x;
-  const int cnt = min(A.sel_cnt[b], A.sel_cap);
-  const int h = A.n_heads, D = A.head_dim, nc = A.n_chunks;
-  adsa_seq& sq = A.seqs[b];
-  const bool active = sq.step >= 0 && sq.status == 0;
-  for (int o = tid; o < h * D; o += kCombineThreads) {
-    const int head = o / D, d = o - head * D;
-    float val = 0.0f, lse2 = 0.0f;
-    if (cnt > 0) {
-      const size_t pbase = ((size_t)b * h + head) * nc;
-      float M = -INFINITY;
-      for (int c = 0; c < nc; ++c) {
-        const bool nonempty = ((long long)cnt * c) / nc < ((long long)cnt * (c + 1)) / nc;
-        if (nonempty) M = fmaxf(M, A.part_ml[(pbase + c) * 2]);
-      }
-      float L = 0.0f, a = 0.0f;
-      for (int c = 0; c < nc; ++c) {
-        const bool nonempty = ((long long)cnt * c) / nc < ((long long)cnt * (c + 1)) / nc;
-        if (!nonempty) continue;
-        const float wgt = fast_exp2(A.part_ml[(pbase + c) * 2] - M);
-        L = fmaf(A.part_ml[(pbase + c) * 2 + 1], wgt, L);
-        a = fmaf(A.part_acc[(pbase + c) * D + d], wgt, a);
-      }
-      val = a / L;
-      lse2 = M + __log2f(L);
-    }
-    const size_t oi = ((size_t)b * h + head) * D + d;
-    if (A.elem_bytes == 4) reinterpret_cast<float*>(A.out)[oi] = val;
-    else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
-    if (d == 0) { A.lse[(size_t)b * h + head] = lse2 * kLn2; s_lse2[head] = lse2; }
-  }
+  // ---- arrival: the last workgroup of this (sequence, head group) merges the chunks
+  int32_t* ctr = A.counters + (size_t)b * (A.n_hg + 1);
+  __threadfence();
   __syncthreads();
-  if (A.accumulate && cnt > 0 && active) {
-    const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
-    const float* lg = A.logits + (size_t)b * h * A.sel_cap;
-    for (int j = tid; j < cnt; j += kCombineThreads) {
-      float t = 0.0f;
-      for (int head = 0; head < h; ++head) t += fast_exp2(lg[(size_t)head * A.sel_cap + j] - s_lse2[head]);
-      const int slot = idx[j];
-      if (slot >= 0 && slot < A.cap) sq.score[slot] += t;
+  if (tid == 0) s_ticket = atomicAdd(&ctr[hg], 1);
+  __syncthreads();
+  if (s_ticket != n_nonempty - 1) return;
+  __threadfence();                                  // acquire: see every chunk's partials and logits
+  if (tid == 0) ctr[hg] = 0;                        // ready for the next launch
+
+  for (int o = tid; o < HPW * D; o += kAttThreads) {
+    const int sb = o / D, d = o - sb * D;
+    const int hd = hg * HPW + sb;
+    if (hd >= A.n_heads) continue;
+    const size_t pbase = ((size_t)b * A.n_heads + hd) * n_chunks;
+    float M = -INFINITY;
+    for (int c = 0; c < n_chunks; ++c)
+      if (chunk_begin(cnt, c, n_chunks) < chunk_begin(cnt, c + 1, n_chunks)) M = fmaxf(M, A.part_ml[(pbase + c) * 2]);
+    float L = 0.0f, a = 0.0f;
+    for (int c = 0; c < n_chunks; ++c) {
+      if (chunk_begin(cnt, c, n_chunks) >= chunk_begin(cnt, c + 1, n_chunks)) continue;   // empty chunk
+      const float wgt = fast_exp2(A.part_ml[(pbase + c) * 2] - M);
+      L = fmaf(A.part_ml[(pbase + c) * 2 + 1], wgt, L);
+      a = fmaf(A.part_acc[(pbase + c) * D + d], wgt, a);
+    }
+    const float val = a / L;
+    const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
+    if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
+    else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
+    if (d == 0) {
+      const float lse2 = M + __log2f(L);
+      A.lse[(size_t)b * A.n_heads + hd] = lse2 * kLn2;
+      s_lse2[sb] = lse2;
     }
   }
-  if (A.advance_step && tid == 0 && active) sq.step = sq.step + 1;
+  if (!(A.accumulate || A.append || A.advance)) return;
+  __syncthreads();
+  if (A.accumulate) {
+    // per attended token: probability summed over this group's heads, ascending head order
+    const float* lg = A.logits + ((size_t)b * A.n_heads + hg * HPW) * A.lg_stride;
+    float* ps = A.psum + ((size_t)b * A.n_hg + hg) * A.lg_stride;
+    const int heads_here = min(HPW, A.n_heads - hg * HPW);
+    for (int j = tid; j < cnt; j += kAttThreads) {
+      float t = 0.0f;
+      for (int sb = 0; sb < heads_here; ++sb) t += fast_exp2(lg[(size_t)sb * A.lg_stride + j] - s_lse2[sb]);
+      ps[j] = t;
+    }
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) s_ticket = atomicAdd(&ctr[A.n_hg], 1);
+  __syncthreads();
+  if (s_ticket != A.n_hg - 1) return;
+  __threadfence();
+  if (tid == 0) ctr[A.n_hg] = 0;
+
+  // ---- the last head group of the sequence: score update, end of append, step counter
+  if (A.accumulate) {
+    const float* ps = A.psum + (size_t)b * A.n_hg * A.lg_stride;
+    for (int j = tid; j < cnt; j += kAttThreads) {
+      const int slot = idx[j];
+      if (slot < 0 || slot >= A.cap) continue;
+      float inc = 0.0f;
+      for (int g = 0; g < A.n_hg; ++g) inc += ps[(size_t)g * A.lg_stride + j];
+      const float base = slot == new_slot ? 0.0f : sq.score[slot];   // a new slot starts at 0
+      sq.score[slot] = base + inc;
+    }
+  } else if (new_slot >= 0 && tid == 0) {
+    sq.score[new_slot] = 0.0f;
+  }
+  if (tid == 0) {
+    if (new_slot >= 0) { sq.pos[new_slot] = sq.grid_origin + step - 1; sq.n_res = n_res + 1; }
+    if (A.advance) sq.step = step + 1;
+  }
 }
 
 template <int EB, int D>
-hipError_t launch_attend_t(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st) {
+hipError_t launch_attend_t(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
+                           hipEvent_t ev_start, hipEvent_t ev_stop) {
   constexpr int U = 4;
   constexpr int HPW = kWave / (D / Elems<EB>::N);
-  const size_t lds = A.want_logits ? (size_t)HPW * plan.chunk_max * sizeof(float) : 0;
+  const size_t lds = A.accumulate ? (size_t)HPW * plan.chunk_max * sizeof(float) : 0;
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
-  hipLaunchKernelGGL((k_attend<EB, D, U>), grid, dim3(kAttThreads), lds, st, A);
+  if (ev_start && ev_stop)
+    hipExtLaunchKernelGGL((k_attend<EB, D, U>), grid, dim3(kAttThreads), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
+  else
+    hipLaunchKernelGGL((k_attend<EB, D, U>), grid, dim3(kAttThreads), lds, st, A);
   return hipGetLastError();
+}
+
+__global__ void k_zero_words(uint32_t* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
 }  // namespace
@@ -292,10 +366,17 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 Workspace make_workspace(const adsa_params& p, const AttendPlan& plan) {
   Workspace w;
   size_t off = 0;
+  w.lg_stride = (int)align_up((size_t)p.sel_cap, 4);
+  w.counters_off = off;
+  off = align_up(off + sizeof(int32_t) * (size_t)p.n_seq * (plan.n_head_groups + 1), 256);
+  w.persistent_bytes = off;     // must stay zero between launches
   w.logits_off = off;
-  off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * p.sel_cap, 256);
-  w.partial_off = off;   // ml then acc
+  off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * w.lg_stride, 256);
+  w.psum_off = off;
+  off = align_up(off + sizeof(float) * (size_t)p.n_seq * plan.n_head_groups * w.lg_stride, 256);
+  w.part_ml_off = off;
   off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * 2, 256);
+  w.part_acc_off = off;
   off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * p.head_dim, 256);
   w.plan_off = off;
   off = align_up(off + sizeof(int32_t) * (size_t)p.n_seq * 4, 256);
@@ -310,48 +391,38 @@ Workspace make_workspace(const adsa_params& p, const AttendPlan& plan) {
   return w;
 }
 
-static float* part_ml_ptr(char* ws, const Workspace& w) { return reinterpret_cast<float*>(ws + w.partial_off); }
-static float* part_acc_ptr(char* ws, const Workspace& w, const adsa_params& p, const AttendPlan& plan) {
-  return reinterpret_cast<float*>(
-      ws + align_up(w.partial_off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * 2, 256));
+hipError_t launch_workspace_init(char* ws, const Workspace& w, hipStream_t st) {
+  const size_t words = w.persistent_bytes / 4;
+  hipLaunchKernelGGL(k_zero_words, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
+                     reinterpret_cast<uint32_t*>(ws + w.counters_off), words);
+  return hipGetLastError();
 }
 
-hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, const adsa_seq* seqs, const void* q,
-                         const int32_t* sel_idx, const int32_t* sel_cnt, char* ws, const Workspace& w,
-                         bool want_logits, hipStream_t st) {
+hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
+                         const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
+                         void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
+                         bool advance, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   AttendArgs A;
-  A.seqs = seqs; A.q = (const char*)q; A.sel_idx = sel_idx; A.sel_cnt = sel_cnt;
+  A.seqs = seqs; A.q = (const char*)q; A.k_new = (const char*)k_new; A.v_new = (const char*)v_new;
+  A.sel_idx = sel_idx; A.sel_cnt = sel_cnt; A.out = (char*)out; A.lse = lse;
   A.logits = reinterpret_cast<float*>(ws + w.logits_off);
-  A.part_ml = part_ml_ptr(ws, w);
-  A.part_acc = part_acc_ptr(ws, w, p, plan);
-  A.n_heads = p.n_heads; A.sel_cap = p.sel_cap; A.chunk_max = plan.chunk_max; A.cap = p.cap;
-  A.want_logits = want_logits ? 1 : 0;
+  A.part_ml = reinterpret_cast<float*>(ws + w.part_ml_off);
+  A.part_acc = reinterpret_cast<float*>(ws + w.part_acc_off);
+  A.psum = reinterpret_cast<float*>(ws + w.psum_off);
+  A.counters = reinterpret_cast<int32_t*>(ws + w.counters_off);
+  A.n_heads = p.n_heads; A.n_hg = plan.n_head_groups; A.sel_cap = p.sel_cap; A.lg_stride = w.lg_stride;
+  A.chunk_max = plan.chunk_max; A.cap = p.cap; A.grid_h = p.grid_h; A.grid_w = p.grid_w;
+  A.accumulate = accumulate ? 1 : 0; A.append = append ? 1 : 0; A.advance = advance ? 1 : 0;
   const int eb = elem_bytes(p);
   A.slot_stride_b = (long long)p.kv_slot_stride * eb;
   A.head_stride_b = (long long)p.kv_head_stride * eb;
   const float scale = p.softmax_scale != 0.0f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
   A.scale_log2 = scale * kLog2e;
-  if (eb == 2 && p.head_dim == 64) return launch_attend_t<2, 64>(A, plan, p.n_seq, st);
-  if (eb == 2 && p.head_dim == 128) return launch_attend_t<2, 128>(A, plan, p.n_seq, st);
-  if (eb == 4 && p.head_dim == 64) return launch_attend_t<4, 64>(A, plan, p.n_seq, st);
-  if (eb == 4 && p.head_dim == 128) return launch_attend_t<4, 128>(A, plan, p.n_seq, st);
+  if (eb == 2 && p.head_dim == 64) return launch_attend_t<2, 64>(A, plan, p.n_seq, st, ev_start, ev_stop);
+  if (eb == 2 && p.head_dim == 128) return launch_attend_t<2, 128>(A, plan, p.n_seq, st, ev_start, ev_stop);
+  if (eb == 4 && p.head_dim == 64) return launch_attend_t<4, 64>(A, plan, p.n_seq, st, ev_start, ev_stop);
+  if (eb == 4 && p.head_dim == 128) return launch_attend_t<4, 128>(A, plan, p.n_seq, st, ev_start, ev_stop);
   return hipErrorInvalidValue;
-}
-
-hipError_t launch_combine(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs,
-                          const int32_t* sel_idx, const int32_t* sel_cnt, void* out, float* lse,
-                          char* ws, const Workspace& w, bool accumulate, bool advance_step, hipStream_t st) {
-  CombineArgs A;
-  A.seqs = seqs; A.sel_idx = sel_idx; A.sel_cnt = sel_cnt;
-  A.logits = reinterpret_cast<const float*>(ws + w.logits_off);
-  A.part_ml = part_ml_ptr(ws, w);
-  A.part_acc = part_acc_ptr(ws, w, p, plan);
-  A.out = (char*)out; A.lse = lse;
-  A.n_heads = p.n_heads; A.head_dim = p.head_dim; A.sel_cap = p.sel_cap; A.n_chunks = plan.n_chunks;
-  A.cap = p.cap;
-  A.elem_bytes = elem_bytes(p); A.accumulate = accumulate ? 1 : 0; A.advance_step = advance_step ? 1 : 0;
-  hipLaunchKernelGGL(k_combine, dim3(p.n_seq), dim3(kCombineThreads), 0, st, A);
-  return hipGetLastError();
 }
 
 }  // namespace adsa

@@ -2,8 +2,9 @@
 //
 //  k_select        : Eq. 1 partition of the resident slots, Eq. 4 ranking of the candidates by an
 //                    LDS-resident 4-pass MSB radix select with lowest-slot tie-break, and the
-//                    ascending attended-slot list.  Optionally appends the query token's K/V row
-//                    first (Section 4.2: new tokens go to the end of the cache).
+//                    ascending attended-slot list.  It can plan for the query token's append
+//                    (Section 4.2: new tokens go to the end of the cache) that the attention
+//                    launch performs, so the ranking never waits for the token's K/V.
 //  k_compact_plan  : Section 4.2 in per-row form: keep flags (prefix, last R rows, top-B of the
 //                    rest), ballot/prefix-sum keep map, in-place move of pos[] and score[].
 //  k_compact_move  : in-place, order-preserving move of the surviving K and V rows.
@@ -119,19 +120,6 @@ __device__ __forceinline__ int effective_budget(const adsa_seq& q, int s) {
   return (int)b;
 }
 
-// 16-byte copy of one [n_heads][head_dim] row into the cache at `slot`.
-__device__ __forceinline__ void append_row(void* cache, const void* row, int slot, int n_heads,
-                                           int vec_per_head, long long slot_stride_b,
-                                           long long head_stride_b) {
-  const int total = n_heads * vec_per_head;
-  for (int i = threadIdx.x; i < total; i += blockDim.x) {
-    int hh = i / vec_per_head, within = i - hh * vec_per_head;
-    const uint4 val = reinterpret_cast<const uint4*>(row)[i];
-    char* dst = reinterpret_cast<char*>(cache) + (long long)slot * slot_stride_b + (long long)hh * head_stride_b;
-    reinterpret_cast<uint4*>(dst)[within] = val;
-  }
-}
-
 struct LaunchShape {
   int n_heads, head_dim, elem_bytes;
   int grid_h, grid_w, R, w;
@@ -144,8 +132,7 @@ __device__ __forceinline__ bool keep_largest_of(int mode) {
 }
 
 __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq* seqs, int32_t* sel_idx,
-                                                       int32_t* sel_cnt, const char* k_new,
-                                                       const char* v_new, int do_append) {
+                                                       int32_t* sel_cnt, int plan_append) {
   __shared__ RankShared sh;
   __shared__ int s_bad;
   const int b = blockIdx.x, tid = threadIdx.x;
@@ -160,19 +147,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
     if (tid == 0) { sq.status = status_in | ADSA_SEQ_BAD_STATE; sel_cnt[b] = 0; }
     return;
   }
-  const int P = sq.grid_origin;
-  if (do_append && s >= 1) {
+  // Section 4.2: the query token goes to the end of the cache.  When the append itself happens
+  // later in this step (inside the attention launch), plan for it: slot n, always local, score 0.
+  int n_real = n;
+  if (plan_append && s >= 1) {
     if (n + 1 > L.cap) {
       if (tid == 0) { sq.status = status_in | ADSA_SEQ_CACHE_FULL; sel_cnt[b] = 0; }
       return;
     }
-    const int vph = L.head_dim * L.elem_bytes / 16;
-    const size_t row_b = (size_t)L.n_heads * L.head_dim * L.elem_bytes;
-    append_row(sq.k, k_new + (size_t)b * row_b, n, L.n_heads, vph, L.slot_stride_b, L.head_stride_b);
-    append_row(sq.v, v_new + (size_t)b * row_b, n, L.n_heads, vph, L.slot_stride_b, L.head_stride_b);
-    if (tid == 0) { sq.pos[n] = P + s - 1; sq.score[n] = 0.0f; sq.n_res = n + 1; }
     n += 1;
-    __syncthreads();                       // pos/score of the new slot visible to the whole workgroup
   }
 
   // ---- Eq. 1: partition, keys into LDS
@@ -180,10 +163,11 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   const bool largest = keep_largest_of(L.score_mode);
   uint32_t my_cand = 0;
   for (int i = tid; i < n; i += kSelThreads) {
-    const int c = select_class(cell, sq.pos[i]);
+    const bool planned = i >= n_real;               // the slot the query token will occupy
+    const int c = planned ? 0 : select_class(cell, sq.pos[i]);
     if (c < 0) s_bad = 1;
     sh.cls[i] = c == 1 ? kCand : kFixed;
-    sh.key[i] = order_key(sq.score[i], largest);
+    sh.key[i] = order_key(planned ? 0.0f : sq.score[i], largest);
     my_cand += (c == 1);
   }
   uint32_t n_cand;
@@ -368,9 +352,9 @@ LaunchShape shape_of(const adsa_params& p) {
 }  // namespace
 
 hipError_t launch_select(const adsa_params& p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
-                         const void* k_new, const void* v_new, bool append, hipStream_t st) {
+                         bool plan_append, hipStream_t st) {
   hipLaunchKernelGGL(k_select, dim3(p.n_seq), dim3(kSelThreads), 0, st, shape_of(p), seqs, sel_idx, sel_cnt,
-                     (const char*)k_new, (const char*)v_new, append ? 1 : 0);
+                     plan_append ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -64,7 +64,7 @@ def test_workspace_size_is_positive_and_monotone(lib):
 def test_bad_parameters_are_rejected_before_any_launch(lib, kw, code):
     p = good(**kw)
     fake = 0x1000   # never dereferenced: validation fails first
-    rc = lib.adsa_select(C.byref(p), fake, fake, fake, fake, 1 << 30, None)
+    rc = lib.adsa_select(C.byref(p), fake, fake, fake, 0, fake, 1 << 30, None)
     assert rc == code, B.strerror(rc)
     assert B.adsa_workspace_bytes(p) == 0
     rc = lib.adsa_step(C.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None)
@@ -76,15 +76,21 @@ def test_null_alignment_and_workspace_errors(lib):
     p = good()
     ok = 0x1000
     need = B.adsa_workspace_bytes(p)
-    assert lib.adsa_select(C.byref(p), None, ok, ok, ok, need, None) == -1
-    assert lib.adsa_select(None, ok, ok, ok, ok, need, None) == -1
-    assert lib.adsa_attend(C.byref(p), ok, ok, ok, ok, None, ok, 0, ok, need, None) == -1
-    assert lib.adsa_attend(C.byref(p), ok, ok + 4, ok, ok, ok, ok, 0, ok, need, None) == -4
-    assert lib.adsa_attend(C.byref(p), ok, ok, ok, ok, ok, ok, 0, None, need, None) == -6
-    assert lib.adsa_attend(C.byref(p), ok, ok, ok, ok, ok, ok, 0, ok, need - 1, None) == -6
-    assert lib.adsa_attend(C.byref(p), ok, ok, ok, ok, ok, ok, 0, ok + 16, need, None) == -4
-    assert lib.adsa_compact(C.byref(p), ok, None, ok, need, None) == -1
-    assert lib.adsa_compact(C.byref(p), ok, ok, ok, 0, None) == -6
+    assert lib.adsa_select(C.byref(p), None, ok, ok, 0, ok, need, None) == -1
+    assert lib.adsa_select(None, ok, ok, ok, 0, ok, need, None) == -1
+    assert lib.adsa_attend(C.byref(p), ok, ok, None, None, ok, ok, None, ok, 0, ok, need, None) == -1
+    assert lib.adsa_attend(C.byref(p), ok, ok + 4, None, None, ok, ok, ok, ok, 0, ok, need, None) == -4
+    assert lib.adsa_attend(C.byref(p), ok, ok, None, None, ok, ok, ok, ok, 0, None, need, None) == -6
+    assert lib.adsa_attend(C.byref(p), ok, ok, None, None, ok, ok, ok, ok, 0, ok, need - 1, None) == -6
+    assert lib.adsa_attend(C.byref(p), ok, ok, None, None, ok, ok, ok, ok, 0, ok + 16, need, None) == -4
+    # appending needs the new rows
+    assert lib.adsa_attend(C.byref(p), ok, ok, None, ok, ok, ok, ok, ok, B.FLAG_APPEND, ok, need, None) == -1
+    assert lib.adsa_attend(C.byref(p), ok, ok, ok + 2, ok, ok, ok, ok, ok, B.FLAG_APPEND, ok, need, None) == -4
+    assert lib.adsa_compact(C.byref(p), ok, None, 0, ok, need, None) == -1
+    assert lib.adsa_compact(C.byref(p), ok, ok, 0, ok, 0, None) == -6
+    assert lib.adsa_workspace_init(C.byref(p), None, need, None) == -6
+    assert lib.adsa_workspace_init(C.byref(p), ok, need - 1, None) == -6
+    assert lib.adsa_workspace_init(C.byref(p), ok + 8, need, None) == -4
     # keep_map may be NULL only when the caller rules compaction out
     assert lib.adsa_step(C.byref(p), ok, ok, ok, ok, ok, ok, ok, ok, None, 0, ok, need, None) == -1
     assert lib.adsa_step(C.byref(p), ok, ok, ok, ok + 8, ok, ok, ok, ok, ok, 0, ok, need, None) == -4

@@ -15,7 +15,7 @@ import torch
 import oracle
 from paper_2506_18226_amd import binding as B
 from paper_2506_18226_amd import workloads as WL
-from paper_2506_18226_amd.batch import LayerBatch, to_device, to_host
+from paper_2506_18226_amd.batch import LayerBatch, ModelBatch, to_device, to_host
 
 from common import oracle_cfg, replay, near_tie_ok
 
@@ -344,7 +344,7 @@ def test_device_side_status_and_inactive_sequences():
     torch.cuda.synchronize()
     seqs = batch.read_seqs()
     assert seqs["status"].tolist() == [B.SEQ_CACHE_FULL, 0, B.SEQ_SEL_OVERFLOW, 0]
-    assert seqs["n_res"].tolist() == [8, 3, 8, 4]
+    assert seqs["n_res"].tolist() == [8, 3, 7, 4]      # rejected sequences are left untouched
     assert seqs["step"].tolist() == [6, -1, 5, 2]
     out = to_host(batch.out)
     assert (out[0] == 0).all() and (out[1] == 0).all() and (out[2] == 0).all()
@@ -352,3 +352,52 @@ def test_device_side_status_and_inactive_sequences():
     st = oracle.CacheState.from_prefix(cfg, k[:3], v[:3])
     ref = oracle.step(cfg, st, 1, q[3], k[3], v[3])
     check_out(wl, out[3], ref["out"])
+
+
+# ----------------------------------------------------------------------------- split-phase, all layers
+def test_split_phase_steps_over_several_layers():
+    """The q-independent phases batched over layers: adsa_select(PLAN_APPEND) for every layer's
+    sequences at once, adsa_attend(APPEND | ADVANCE) per layer, adsa_compact(ADVANCE) for all
+    layers at row ends -- free-running for 3 rows against one oracle per (layer, sequence)."""
+    n_layers, n_seq = 3, 2
+    wl = WL.get_workload("xl", n_seq=n_seq, n_heads=20, grid_h=5, grid_w=8, prefix_len=9, budget_num=1, budget_den=2)
+    cfg = oracle_cfg(wl)
+    P = cfg.grid_origin
+    lp = params_for(wl, n_seq, cfg.cap)
+    mb = ModelBatch(lp, n_layers, DEV)
+    toks, states = {}, {}
+    for l in range(n_layers):
+        for b in range(n_seq):
+            q, k, v = WL.gen_tokens(wl, l, b)
+            toks[l, b] = (q, k, v)
+            st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+            states[l, b] = st
+            load_state(mb, l * n_seq + b, st, cfg, 0)
+    mb.upload_seqs()
+    for s in range(0, 3 * wl.grid_w + 2):
+        row_end = s >= 1 and (s - 1) % wl.grid_w == wl.grid_w - 1
+        p = P + s - 1
+        mb.select_all(flags=B.FLAG_PLAN_APPEND)
+        for l in range(n_layers):
+            qd, kd, vd = (to_device(np.stack([toks[l, b][i][p] for b in range(n_seq)]), lp.dtype, DEV) for i in range(3))
+            mb.attend_layer(l, qd, kd, vd, flags=B.FLAG_APPEND | (0 if row_end else B.FLAG_ADVANCE))
+        if row_end:
+            mb.compact_all(flags=B.FLAG_ADVANCE)
+        torch.cuda.synchronize()
+        seqs = mb.read_seqs()
+        out, sel_idx, sel_cnt = to_host(mb.out), mb.sel_idx.cpu().numpy(), mb.sel_cnt.cpu().numpy()
+        posd = mb.pos.cpu().numpy()
+        for l in range(n_layers):
+            for b in range(n_seq):
+                i = l * n_seq + b
+                q, k, v = toks[l, b]
+                st = states[l, b]
+                before = st.score.copy()
+                ref = oracle.step(cfg, st, s, q[p], k[p], v[p])
+                tag = f"s={s} layer={l} seq={b}"
+                assert seqs["status"][i] == 0 and seqs["step"][i] == s + 1, tag
+                sel = sel_idx[i, :sel_cnt[i]]
+                assert np.array_equal(sel, ref["sel_idx"]) or near_tie_ok(sel, ref["sel_idx"], before), tag
+                check_out(wl, out[i], ref["out"], tag)
+                assert seqs["n_res"][i] == st.n_res, tag
+                assert np.array_equal(posd[i, :st.n_res], st.pos[:st.n_res]), tag
