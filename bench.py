@@ -41,81 +41,83 @@ def parse_args():
 
 
 class Job:
-    """All device state of the benchmark: per-layer caches, step-major inputs, shared outputs."""
+    """All device state of the benchmark: every layer's caches as one layer-major batch,
+    step-major inputs, and the per-step launch sequence."""
 
     def __init__(self, wl, n_layers, device):
         import torch
         from paper_2506_18226_amd import binding as B
         from paper_2506_18226_amd import workloads as WL
-        from paper_2506_18226_amd.batch import LayerBatch
+        from paper_2506_18226_amd.batch import ModelBatch
 
         self.torch, self.B, self.wl, self.n_layers, self.device = torch, B, wl, n_layers, device
         P, n, h, D = wl.prefix_len, wl.n_seq, wl.n_heads, wl.head_dim
         self.n_steps_total = wl.n_image_tokens          # s = 0 .. H*W-1
-        self.params = B.make_params(
+        self.layer_params = B.make_params(
             n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w,
             win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
             dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=wl.score_mode,
             cap=wl.cap(), sel_cap=wl.sel_cap())
-        self.layers = []
+        mb = self.mb = ModelBatch(self.layer_params, n_layers, device)
         self.q, self.kn, self.vn = [], [], []
         S = self.n_steps_total
         for l in range(n_layers):
-            lb = LayerBatch(self.params, device, with_outputs=False)
             qd, kd, vd = WL.gen_tokens_device(wl, l, device)        # [n][L][h][D]
-            lb.K[:, :P] = kd[:, :P]
-            lb.V[:, :P] = vd[:, :P]
-            lb.pos[:, :P] = torch.arange(P, dtype=torch.int32, device=device)[None, :]
+            mb.K[l * n:(l + 1) * n, :P] = kd[:, :P]
+            mb.V[l * n:(l + 1) * n, :P] = vd[:, :P]
             # step s queries with the token at position P+s-1: step-major [S][n][h][D]
             self.q.append(qd[:, P - 1:P - 1 + S].permute(1, 0, 2, 3).contiguous())
             self.kn.append(kd[:, P - 1:P - 1 + S].permute(1, 0, 2, 3).contiguous())
             self.vn.append(vd[:, P - 1:P - 1 + S].permute(1, 0, 2, 3).contiguous())
             del qd, kd, vd
-            self.layers.append(lb)
-        p = self.params
-        tdt = self.layers[0].tdtype
-        self.out = torch.zeros((n, h, D), dtype=tdt, device=device)
-        self.lse = torch.zeros((n, h), dtype=torch.float32, device=device)
-        self.sel_idx = torch.zeros((n, p.sel_cap), dtype=torch.int32, device=device)
-        self.keep_map = torch.zeros((n, p.cap), dtype=torch.int32, device=device)
-        self.sel_cnt_log = torch.zeros((S, n_layers, n), dtype=torch.int32, device=device)
-        self.workspace = self.layers[0].workspace
-        self.row_bytes = n * h * D * self.out.element_size()
+        mb.pos[:, :P] = torch.arange(P, dtype=torch.int32, device=device)[None, :]
+        self.sel_cnt_log = torch.zeros((S, n_layers * n), dtype=torch.int32, device=device)
+        self.row_bytes = n * h * D * mb.K.element_size()
         self.reset()
 
     def reset(self):
-        wl, P = self.wl, self.wl.prefix_len
-        for lb in self.layers:
-            for b in range(wl.n_seq):
-                s = lb.seqs_host[b]
-                s["n_res"], s["step"], s["grid_origin"], s["n_keep_prefix"] = P, 0, P, P
-                s["budget"], s["budget_num"], s["budget_den"] = wl.budget, wl.budget_num, wl.budget_den
-                s["status"], s["compacted"] = 0, 0
-            lb.upload_seqs()
-            lb.score.zero_()
+        wl, P, mb = self.wl, self.wl.prefix_len, self.mb
+        for s in mb.seqs_host:
+            s["n_res"], s["step"], s["grid_origin"], s["n_keep_prefix"] = P, 0, P, P
+            s["budget"], s["budget_num"], s["budget_den"] = wl.budget, wl.budget_num, wl.budget_den
+            s["status"], s["compacted"] = 0, 0
+        mb.upload_seqs()
+        mb.score.zero_()
         self.sel_cnt_log.zero_()
         self.torch.cuda.synchronize()
 
     def run(self, s_begin, s_end, on_row_end=None):
-        """Enqueue decode steps s_begin .. s_end-1 for every layer (no host sync inside)."""
-        B, wl = self.B, self.wl
+        """Enqueue decode steps s_begin .. s_end-1 (no host sync inside).  Per step: ONE selection
+        launch for every layer's sequences (it does not depend on q/k/v), one attention launch per
+        layer (append + gather attention + merge + score update), and at row ends ONE
+        eviction/compaction launch pair for every layer."""
+        B, wl, mb = self.B, self.wl, self.mb
         W = wl.grid_w
         stream = self.torch.cuda.current_stream().cuda_stream
-        ptr = lambda t: t.data_ptr()
-        seqs = [ptr(lb.seqs) for lb in self.layers]
-        qb, kb, vb = [ptr(t) for t in self.q], [ptr(t) for t in self.kn], [ptr(t) for t in self.vn]
-        out, lse, sel_idx, keep_map = ptr(self.out), ptr(self.lse), ptr(self.sel_idx), ptr(self.keep_map)
-        cnt0 = ptr(self.sel_cnt_log)
         n, L = wl.n_seq, self.n_layers
+        lp, tp = mb.layer_params, mb.params
+        seqs0, sel0 = mb.seqs.data_ptr(), mb.sel_idx.data_ptr()
+        out0, lse0 = mb.out.data_ptr(), mb.lse.data_ptr()
+        qb = [t.data_ptr() for t in self.q]
+        kb = [t.data_ptr() for t in self.kn]
+        vb = [t.data_ptr() for t in self.vn]
+        cnt0 = self.sel_cnt_log.data_ptr()
+        seq_sz, sel_row = B.SEQ_DTYPE.itemsize, lp.sel_cap * 4
+        out_row, lse_row = n * lp.n_heads * lp.head_dim * mb.out.element_size(), n * lp.n_heads * 4
         for s in range(s_begin, s_end):
             row_end = s >= 1 and (s - 1) % W == W - 1
-            flags = 0 if row_end else B.FLAG_NO_COMPACT
+            cnt_s = cnt0 + s * L * n * 4
+            B.adsa_select(tp, seqs0, sel0, cnt_s, None, B.FLAG_PLAN_APPEND, stream)
+            flags = B.FLAG_APPEND | (0 if row_end else B.FLAG_ADVANCE)
             off = s * self.row_bytes
             for l in range(L):
-                B.adsa_step(self.params, seqs[l], qb[l] + off, kb[l] + off, vb[l] + off, out, lse, sel_idx,
-                            cnt0 + ((s * L + l) * n) * 4, keep_map, self.workspace, flags, stream)
-            if row_end and on_row_end is not None:
-                on_row_end(s)
+                B.adsa_attend(lp, seqs0 + l * n * seq_sz, qb[l] + off, sel0 + l * n * sel_row, cnt_s + l * n * 4,
+                              out0 + l * out_row, lse0 + l * lse_row, mb.layer_workspace, flags,
+                              kb[l] + off, vb[l] + off, stream)
+            if row_end:
+                B.adsa_compact(tp, seqs0, mb.keep_map, mb.workspace, B.FLAG_ADVANCE, stream)
+                if on_row_end is not None:
+                    on_row_end(s)
 
 
 def cpu_baseline(wl, n_layers, seconds):
@@ -187,9 +189,8 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    seq_status = np.concatenate([lb.read_seqs()["status"] for lb in job.layers])
-    assert (seq_status == 0).all(), "a sequence reported a device-side error"
-    cnt_log = job.sel_cnt_log.cpu().numpy().astype(np.int64)           # [S][layers][n_seq]
+    assert (job.mb.read_seqs()["status"] == 0).all(), "a sequence reported a device-side error"
+    cnt_log = job.sel_cnt_log.cpu().numpy().astype(np.int64)           # [S][layers * n_seq]
     tau = wl.token_bytes
     tokens = wl.n_seq * K
     result = {
@@ -219,8 +220,7 @@ def main():
         torch.cuda.synchronize()
         n_after = []
         B.adsa_profile_enable(True)
-        job.run(s0, S, on_row_end=lambda s: n_after.append(
-            (s, [int(x) for lb in job.layers for x in lb.read_seqs()["n_res"]])))
+        job.run(s0, S, on_row_end=lambda s: n_after.append((s, [int(x) for x in job.mb.read_seqs()["n_res"]])))
         torch.cuda.synchronize()
         n_launch, att_ms = B.adsa_profile_read()
         B.adsa_profile_enable(False)

@@ -77,9 +77,11 @@ typedef enum {
 /* Flags of adsa_select / adsa_attend / adsa_compact / adsa_step. */
 #define ADSA_FLAG_NO_COMPACT    1u  /* caller guarantees no sequence closes a grid row in this step */
 #define ADSA_FLAG_NO_ACCUMULATE 2u  /* adsa_attend: do not add attention mass to score[] */
-#define ADSA_FLAG_PLAN_APPEND   4u  /* adsa_select: rank as if the query token already sat at slot n_res
-                                       (it is always local); adsa_attend with ADSA_FLAG_APPEND puts it there */
-#define ADSA_FLAG_APPEND        8u  /* adsa_attend: append (k_new, v_new) at slot n_res while attending */
+#define ADSA_FLAG_PLAN_APPEND   4u  /* adsa_select: reserve slot n_res for the query token (pos, zero score,
+                                       n_res += 1, pending_slot) and rank with it in place (it is always
+                                       local); its K/V rows arrive with adsa_attend(ADSA_FLAG_APPEND).
+                                       Once per decode step */
+#define ADSA_FLAG_APPEND        8u  /* adsa_attend: write (k_new, v_new) into pending_slot while attending */
 #define ADSA_FLAG_ADVANCE      16u  /* adsa_attend / adsa_compact: step += 1 for every active sequence when
                                        the call is done; give it to the LAST call of a decode step only
                                        (adsa_compact tests the row end on the step before the increment) */
@@ -110,7 +112,10 @@ typedef struct adsa_seq {
   void*    k;                  /* this sequence's K cache (dtype elements) */
   void*    v;                  /* this sequence's V cache */
   int32_t* pos;                /* [cap] absolute position of each resident slot, strictly ascending */
-  float*   score;              /* [cap] ranking score of each resident slot */
+  float*   score;              /* [score_rows][cap] ranking score of each resident slot: the rank of slot i
+                                  is the sum over rows (ascending, fp32) of score[row][i].
+                                  ADSA_SCORE_ATTN_MASS: score_rows = n_heads, one accumulator per head
+                                  (each head's workgroup updates only its own row); else score_rows = 1 */
   int32_t  n_res;              /* resident slots */
   int32_t  step;               /* s (see the decode-step convention above); < 0: inactive */
   int32_t  grid_origin;        /* P: absolute position of image token 0 (= prefix length) */
@@ -120,7 +125,9 @@ typedef struct adsa_seq {
   int32_t  budget_den;
   int32_t  status;             /* ADSA_SEQ_* bits, set by the device, cleared by the caller */
   int32_t  compacted;          /* 1 if the last adsa_step/adsa_compact evicted+compacted this sequence */
-  int32_t  reserved[3];
+  int32_t  pending_slot;       /* slot adsa_select(PLAN_APPEND) reserved for the query token, whose K/V rows
+                                  the next adsa_attend(APPEND) fills; -1 if none.  Written by adsa_select */
+  int32_t  reserved[2];
 } adsa_seq;
 
 /* Bytes of device scratch the entry points need for these parameters (0 if they are invalid). */
@@ -140,7 +147,8 @@ int adsa_workspace_init(const adsa_params* p, void* workspace, size_t workspace_
  * the query of its current `step`, rank the candidates, and write the attended set
  *   PREFIX u LOCAL u top-min(B, |candidates|)
  * as an ascending slot list.  Ties go to the lower slot; -0 == +0; NaN scores are a
- * precondition violation.  Reads seqs[].pos/score/n_res/step; VCOS mode first writes Eq. 3's
+ * precondition violation.  Reads seqs[].pos/score/n_res/step, writes pending_slot (and, with
+ * ADSA_FLAG_PLAN_APPEND, pos / score / n_res of the reserved slot); VCOS mode first writes Eq. 3's
  * S_i into score[] at the candidate slots (reads V, needs the workspace; other modes accept a
  * NULL workspace).  The ranking does not depend on the query token's q/k/v, so one call may
  * cover the sequences of every layer of a model (n_seq = layers x batch) before the layers run.
@@ -159,10 +167,10 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
  *   lse  float [n_seq][n_heads]   natural-log sum-exp of the scaled logits
  *   k_new, v_new  dtype [n_seq][n_heads][head_dim], only read with ADSA_FLAG_APPEND (else may be NULL)
  * For ADSA_SCORE_ATTN_MASS and unless ADSA_FLAG_NO_ACCUMULATE is set, score[slot] of every
- * attended slot gains the probability it received summed over heads.
- * ADSA_FLAG_APPEND (Section 4.2, "appended to the end of the cache"): for sequences with
- * step >= 1 the row (k_new, v_new) is written to slot n_res, pos = P+s-1, score starts at 0,
- * n_res += 1; sel_idx must come from adsa_select with ADSA_FLAG_PLAN_APPEND.
+ * attended slot gains, in row h of score[], the probability head h gave it.
+ * ADSA_FLAG_APPEND (Section 4.2, new tokens go to the end of the cache): the row (k_new, v_new)
+ * is written to the slot adsa_select(ADSA_FLAG_PLAN_APPEND) reserved (pending_slot >= 0), and that
+ * slot is attended from k_new / v_new directly.
  * flags: ADSA_FLAG_NO_ACCUMULATE, ADSA_FLAG_APPEND, ADSA_FLAG_ADVANCE.
  */
 int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
@@ -174,7 +182,7 @@ int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void*
  * ((s-1) % grid_w == grid_w-1, s >= 1): keep the pinned prefix, the last R completed rows and
  * the top min(B, |rest|) of the rest by the same ranking as adsa_select; write
  *   keep_map int32 [n_seq][cap]: new slot of old slot i, or -1 (entries >= old n_res untouched)
- * move K, V, pos, score rows to the front in place, order preserved, and set n_res, compacted.
+ * move K, V, pos and every score row to the front in place, order preserved, and set n_res, compacted.
  * Other sequences are untouched (compacted = 0, keep_map row untouched).  Like adsa_select it
  * may cover every layer's sequences in one call.  flags: ADSA_FLAG_ADVANCE.
  */

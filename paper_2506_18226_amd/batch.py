@@ -37,13 +37,19 @@ class LayerBatch:
         p = params
         self.tdtype = torch.float32 if p.dtype == B.F32 else torch.bfloat16
         n, cap, h, D = p.n_seq, p.cap, p.n_heads, p.head_dim
-        if p.kv_slot_stride != h * D or p.kv_head_stride != D:
-            raise ValueError("LayerBatch allocates the [slot][head][D] layout only")
+        if p.kv_slot_stride == D and p.kv_head_stride == cap * D:
+            self.head_major = True
+        elif p.kv_slot_stride == h * D and p.kv_head_stride == D:
+            self.head_major = False
+        else:
+            raise ValueError("LayerBatch allocates dense [head][slot][D] or [slot][head][D] caches only")
         dev = self.device
-        self.K = torch.zeros((n, cap, h, D), dtype=self.tdtype, device=dev)
-        self.V = torch.zeros((n, cap, h, D), dtype=self.tdtype, device=dev)
+        shape = (n, h, cap, D) if self.head_major else (n, cap, h, D)
+        self.K = torch.zeros(shape, dtype=self.tdtype, device=dev)
+        self.V = torch.zeros(shape, dtype=self.tdtype, device=dev)
         self.pos = torch.zeros((n, cap), dtype=torch.int32, device=dev)
-        self.score = torch.zeros((n, cap), dtype=torch.float32, device=dev)
+        self.rows = B.score_rows(p)
+        self.score = torch.zeros((n, self.rows, cap), dtype=torch.float32, device=dev)
         self.seqs_host = np.zeros(n, dtype=B.SEQ_DTYPE)
         elem = self.K.element_size()
         for b in range(n):
@@ -51,8 +57,9 @@ class LayerBatch:
             s["k"] = self.K.data_ptr() + b * cap * h * D * elem
             s["v"] = self.V.data_ptr() + b * cap * h * D * elem
             s["pos"] = self.pos.data_ptr() + b * cap * 4
-            s["score"] = self.score.data_ptr() + b * cap * 4
+            s["score"] = self.score.data_ptr() + b * self.rows * cap * 4
             s["step"] = -1
+            s["pending_slot"] = -1
         self.seqs = torch.zeros(n * B.SEQ_DTYPE.itemsize, dtype=torch.uint8, device=dev)
         if with_outputs:
             self.out = torch.zeros((n, h, D), dtype=self.tdtype, device=dev)
@@ -71,21 +78,47 @@ class LayerBatch:
                      score: Optional[np.ndarray], step: int, grid_origin: int,
                      n_keep_prefix: Optional[int] = None, budget: int = 0, budget_num: int = 0,
                      budget_den: int = 0) -> None:
+        """k, v: [n][h][D] host rows; score: [n] (goes to score row 0, the other rows are zeroed)
+        or [rows][n]."""
         n = len(pos)
         p = self.params
         if n > p.cap:
             raise ValueError("more resident slots than cap")
         if n:
-            self.K[b, :n] = to_device(k[:n], p.dtype, self.device)
-            self.V[b, :n] = to_device(v[:n], p.dtype, self.device)
+            kd, vd = to_device(k[:n], p.dtype, self.device), to_device(v[:n], p.dtype, self.device)
+            if self.head_major:
+                self.K[b, :, :n] = kd.transpose(0, 1)
+                self.V[b, :, :n] = vd.transpose(0, 1)
+            else:
+                self.K[b, :n] = kd
+                self.V[b, :n] = vd
             self.pos[b, :n] = torch.from_numpy(np.ascontiguousarray(pos[:n], dtype=np.int32)).to(self.device)
-            sc = np.zeros(n, np.float32) if score is None else np.ascontiguousarray(score[:n], dtype=np.float32)
-            self.score[b, :n] = torch.from_numpy(sc).to(self.device)
+            self.score[b].zero_()
+            if score is not None:
+                sc = np.ascontiguousarray(score, dtype=np.float32)
+                if sc.ndim == 1:
+                    self.score[b, 0, :n] = torch.from_numpy(sc[:n]).to(self.device)
+                else:
+                    self.score[b, :, :n] = torch.from_numpy(np.ascontiguousarray(sc[:, :n])).to(self.device)
         s = self.seqs_host[b]
         s["n_res"], s["step"], s["grid_origin"] = n, step, grid_origin
         s["n_keep_prefix"] = grid_origin if n_keep_prefix is None else n_keep_prefix
         s["budget"], s["budget_num"], s["budget_den"] = budget, budget_num, budget_den
-        s["status"], s["compacted"] = 0, 0
+        s["status"], s["compacted"], s["pending_slot"] = 0, 0, -1
+
+    # ---- device -> host, layout-independent views
+    def k_host(self) -> np.ndarray:
+        """K as float32 [n_seq][cap][h][D]."""
+        k = to_host(self.K)
+        return k.transpose(0, 2, 1, 3) if self.head_major else k
+
+    def v_host(self) -> np.ndarray:
+        v = to_host(self.V)
+        return v.transpose(0, 2, 1, 3) if self.head_major else v
+
+    def rank_host(self) -> np.ndarray:
+        """Ranking value of every slot, [n_seq][cap]: the score rows summed (float64 on the host)."""
+        return self.score.cpu().numpy().astype(np.float64).sum(axis=1)
 
     def upload_seqs(self) -> None:
         raw = torch.from_numpy(self.seqs_host.view(np.uint8).reshape(-1).copy())

@@ -45,7 +45,7 @@ SEQ_DTYPE = np.dtype([
     ("k", np.uint64), ("v", np.uint64), ("pos", np.uint64), ("score", np.uint64),
     ("n_res", np.int32), ("step", np.int32), ("grid_origin", np.int32), ("n_keep_prefix", np.int32),
     ("budget", np.int32), ("budget_num", np.int32), ("budget_den", np.int32), ("status", np.int32),
-    ("compacted", np.int32), ("reserved", np.int32, (3,)),
+    ("compacted", np.int32), ("pending_slot", np.int32), ("reserved", np.int32, (2,)),
 ])
 assert SEQ_DTYPE.itemsize == 80
 
@@ -126,16 +126,22 @@ def _check(rc: int, where: str) -> None:
 
 
 def make_params(*, n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, dtype,
-                score_mode, cap, sel_cap=None, sel_groups=1, kv_slot_stride=None, kv_head_stride=None,
-                softmax_scale=0.0) -> AdsaParams:
-    """Fill `adsa_params`; strides default to the [slot][head][D] layout."""
+                score_mode, cap, sel_cap=None, sel_groups=1, layout="head_major", kv_slot_stride=None,
+                kv_head_stride=None, softmax_scale=0.0) -> AdsaParams:
+    """Fill `adsa_params`.  layout "head_major" = [head][slot][D] (a head's rows are contiguous: the
+    fast path), "slot_major" = [slot][head][D]; explicit strides override it."""
     if kv_head_stride is None:
-        kv_head_stride = head_dim
+        kv_head_stride = cap * head_dim if layout == "head_major" else head_dim
     if kv_slot_stride is None:
-        kv_slot_stride = n_heads * head_dim
+        kv_slot_stride = head_dim if layout == "head_major" else n_heads * head_dim
     return AdsaParams(n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, sel_groups,
                       dtype, score_mode, cap, cap if sel_cap is None else sel_cap,
                       kv_slot_stride, kv_head_stride, softmax_scale, 0)
+
+
+def score_rows(params: AdsaParams) -> int:
+    """Rows of adsa_seq.score: one per head for ATTN_MASS, else one."""
+    return params.n_heads if params.score_mode == SCORE_ATTN_MASS else 1
 
 
 def strerror(code: int) -> str:

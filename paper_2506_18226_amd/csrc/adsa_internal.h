@@ -19,19 +19,23 @@ constexpr int kMoveThreads = 256;
 
 // Attend launch plan: a workgroup handles (sequence, head group, token chunk).
 struct AttendPlan {
-  int lanes_per_row;   // lanes that cover one (token, head) row with 16-byte loads
-  int heads_per_wave;  // heads one wave covers per load instruction
-  int n_head_groups;   // ceil(n_heads / heads_per_wave)
-  int n_chunks;        // token chunks per sequence (grid.x); every sequence splits its own count evenly
-  int chunk_max;       // upper bound of tokens in one chunk: ceil(sel_cap / n_chunks)
+  int lanes_per_row;    // lanes that cover one (token, head) row with 16-byte loads
+  bool head_major;      // [head][slot][D] cache: a wave-load takes consecutive tokens of ONE head
+  int heads_per_group;  // heads one workgroup covers: 1 (head-major) or rows-per-wave-load (slot-major)
+  int n_head_groups;    // ceil(n_heads / heads_per_group)
+  int n_chunks;         // token chunks per sequence (grid.x); every sequence splits its own count evenly
+  int chunk_max;        // upper bound of tokens in one chunk, + 1
 };
+
+// Rows of adsa_seq.score: one accumulator per head for ATTN_MASS (the rank of a slot is their sum),
+// a single row otherwise.
+static inline int score_rows(const adsa_params& p) { return p.score_mode == ADSA_SCORE_ATTN_MASS ? p.n_heads : 1; }
 
 // Workspace layout (byte offsets from a 256-byte aligned base).
 struct Workspace {
-  size_t counters_off;     // int32 [n_seq][n_head_groups + 1]  arrival counters (zero between launches)
+  size_t counters_off;     // int32 [n_seq][n_head_groups]  arrival counters (zero between launches)
   size_t persistent_bytes; // leading bytes that adsa_workspace_init zeroes and every launch leaves zero
   size_t logits_off;       // float [n_seq][n_heads][lg_stride]  scaled logits in log2 units
-  size_t psum_off;         // float [n_seq][n_head_groups][lg_stride]  probability summed over a head group
   size_t part_ml_off;      // float [n_seq][n_heads][n_chunks][2]   (m, l) per chunk
   size_t part_acc_off;     // float [n_seq][n_heads][n_chunks][head_dim]
   size_t plan_off;         // int32 [n_seq][4]   compaction: old n_res, first moved slot, did, new n_res

@@ -1,29 +1,29 @@
 // Gather flash-decode of the ADSA decode path (gfx950): Eq. 5's gather fused with softmax
-// attention over the selected slots, split over the index list, with the cache append
-// (Section 4.2), the split merge and the attention-mass update fused into the same launch.
+// attention over the selected slots, plus the cache append (Section 4.2) and the per-head
+// attention-mass update, in ONE launch.
 //
-//  k_attend : grid (token chunk, head group, sequence).  Every sequence splits ITS OWN attended
-//             count evenly over the chunks.  A wave reads one token's rows for `heads_per_wave`
-//             heads with a single streaming 16-byte-per-lane load (1 KiB contiguous in
-//             [slot][head][D] layout), reduces q.k over the lanes of a row with DPP, and keeps an
-//             online-softmax state (m, l, acc) in registers, fp32, log2 domain.  The four waves of
-//             a workgroup interleave the chunk's tokens and merge through LDS; one partial per
-//             (sequence, head, chunk) and the scaled logits go to the workspace.
-//             The LAST workgroup to finish a (sequence, head group) merges its partials into
-//             out / lse and sums, per attended token, the probability over its heads; the LAST
-//             head group of a sequence adds those sums to score[] in head-group order, finishes the
-//             append (pos, n_res) and advances the step.  "Last" is decided by an arrival counter
-//             after a device-scope fence, so nothing ever waits on another workgroup.
+//  k_attend<EB, D, HT, U> : grid (token chunk, head group, sequence), 256 threads.
+//    A 16-byte-per-lane streaming load of one wave covers RPW = 64 / (D*EB/16) rows of D
+//    elements.  HT of them are different heads of one token ([slot][head][D] caches: HT = RPW, one
+//    contiguous burst per token) or HT = 1 and they are RPW consecutive tokens of ONE head
+//    ([head][slot][D] caches: a workgroup streams one head's rows back to back).  q.k is reduced
+//    over the lanes of a row with DPP; every lane keeps an online-softmax state (m, l, acc) in
+//    registers, fp32, log2 domain.  Lane groups and the four waves merge through shuffles + LDS.
+//    With one chunk per (sequence, head group) -- the plan whenever that already fills the chip --
+//    the workgroup writes out / lse itself and adds the probabilities it produced to its OWN
+//    heads' rows of score[]: no workgroup ever talks to another one.
+//    With several chunks, each writes a partial and the scaled logits to the workspace and the
+//    LAST one to arrive (an arrival counter, nothing waits) merges them and updates the scores.
 #include <hip/hip_ext.h>
 
 #include "adsa_internal.h"
-#include "adsa_partition.h"
 
 namespace adsa {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kMaxChunks = 16;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -74,6 +74,22 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Data handed from one workgroup to another inside a launch (chunk partials, logits) is written
+// and read with device-scope relaxed atomics: they go through to the level where all XCDs agree,
+// so no L2 write-back / invalidate (a device-scope fence) is needed.  Order is kept by the issue
+// order: the writer waits for its stores (workgroup release + barrier) before it bumps the arrival
+// counter; the reader issues its loads after the counter's old value came back.
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev2(float* p, float a, float b) {   // 8-byte aligned pair
+  const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // chunk c of a list of cnt tokens split evenly over nc chunks
 __device__ __forceinline__ int chunk_begin(int cnt, int c, int nc) { return (int)(((long long)cnt * c) / nc); }
 
@@ -86,27 +102,64 @@ struct AttendArgs {
   const int32_t* sel_cnt;
   char* out;
   float* lse;
-  float* logits;        // [n_seq][n_heads][lg_stride]   scaled logits, log2 units
+  float* logits;        // [n_seq][n_heads][lg_stride]   scaled logits, log2 units (split launches)
   float* part_ml;       // [n_seq][n_heads][n_chunks][2]
   float* part_acc;      // [n_seq][n_heads][n_chunks][D]
-  float* psum;          // [n_seq][n_hg][lg_stride]      per head group: sum over its heads of p
-  int32_t* counters;    // [n_seq][n_hg + 1]             arrival counters, zero between launches
+  int32_t* counters;    // [n_seq][n_hg]                 arrival counters, zero between launches
   int n_heads, n_hg, sel_cap, lg_stride, chunk_max, cap;
-  int grid_h, grid_w;
   int accumulate, append, advance;     // advance: step += 1 at the end
   long long slot_stride_b, head_stride_b;
   float scale_log2;     // softmax scale * log2(e)
 };
 
-template <int EB, int D, int U>
+// merge two online-softmax states (log2 domain); (m, l) == (-inf, 0) is the neutral element
+template <int EPL>
+__device__ __forceinline__ void merge_state(float& m, float& l, float* acc, float m2, float l2, const float* acc2) {
+  const float M = fmaxf(m, m2);
+  const float w1 = (m == -INFINITY) ? 0.0f : fast_exp2(m - M);
+  const float w2 = (m2 == -INFINITY) ? 0.0f : fast_exp2(m2 - M);
+  l = l * w1 + l2 * w2;
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * w1 + acc2[e] * w2;
+  m = M;
+}
+
+// score[row][slot] += 2^(z - lse2[row]) for `total` (row, token) pairs, loads batched so that the
+// read-modify-write latencies overlap.  get(i, &row_local, &slot, &z) describes pair i.
+template <typename Get>
+__device__ __forceinline__ void add_mass(float* score, int cap, int row0, const float* s_lse2, int total, Get get) {
+  constexpr int B = 4;
+  for (int i0 = threadIdx.x; i0 < total; i0 += kAttThreads * B) {
+    float* ptr[B];
+    float inc[B], old[B];
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+      const int i = i0 + u * kAttThreads;
+      ptr[u] = nullptr; inc[u] = 0.0f; old[u] = 0.0f;
+      if (i < total) {
+        int sb, slot; float z;
+        get(i, &sb, &slot, &z);
+        ptr[u] = score + (size_t)(row0 + sb) * cap + slot;
+        old[u] = *ptr[u];
+        inc[u] = fast_exp2(z - s_lse2[sb]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < B; ++u)
+      if (ptr[u]) *ptr[u] = old[u] + inc[u];
+  }
+}
+
+template <int EB, int D, int HT, int U>
 __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   constexpr int EPL = Elems<EB>::N;                 // elements per lane
   constexpr int LPR = D / EPL;                      // lanes per row
-  constexpr int HPW = kWave / LPR;                  // heads per wave
-  extern __shared__ float s_dyn[];                  // logits tile [HPW][chunk_max]
-  __shared__ float s_m[kAttWaves][HPW], s_l[kAttWaves][HPW];
-  __shared__ float s_acc[kAttWaves][kWave][EPL];
-  __shared__ float s_lse2[HPW];
+  constexpr int RPW = kWave / LPR;                  // rows per wave-load
+  constexpr int TT = RPW / HT;                      // tokens per wave-load
+  extern __shared__ float s_dyn[];                  // [chunk_max] slots, then logits tile [HT][chunk_max]
+  __shared__ float s_m[kAttWaves][HT], s_l[kAttWaves][HT];
+  __shared__ float s_acc[kAttWaves][HT][LPR][EPL];
+  __shared__ float s_lse2[HT];
   __shared__ int s_ticket;
 
   const int chunk = blockIdx.x, hg = blockIdx.y, b = blockIdx.z, n_chunks = gridDim.x;
@@ -114,8 +167,8 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   const int cnt = min(A.sel_cnt[b], A.sel_cap);
   if (cnt <= 0) {                                   // inactive or rejected sequence: zero-filled row
     if (chunk == 0) {
-      for (int o = tid; o < HPW * D; o += kAttThreads) {
-        const int head = hg * HPW + o / D;
+      for (int o = tid; o < HT * D; o += kAttThreads) {
+        const int head = hg * HT + o / D;
         if (head < A.n_heads) {
           const size_t oi = ((size_t)b * A.n_heads + head) * D + (o % D);
           if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = 0.0f;
@@ -128,17 +181,24 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   }
   const int t_begin = chunk_begin(cnt, chunk, n_chunks), t_end = chunk_begin(cnt, chunk + 1, n_chunks);
   if (t_begin >= t_end) return;                     // fewer tokens than chunks
-  const int n_nonempty = min(cnt, n_chunks);
+  const int len = t_end - t_begin;
 
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int sub = lane / LPR, dl = lane - sub * LPR;
-  const int head = hg * HPW + sub;
+  const int hs = sub % HT, ts = sub / HT;           // head and token of this lane's row within a wave-load
+  const int head = hg * HT + hs;
   const bool head_ok = head < A.n_heads;
   const int head_c = head_ok ? head : A.n_heads - 1;
 
   adsa_seq& sq = A.seqs[b];
-  const int step = sq.step, n_res = sq.n_res;
-  const int new_slot = (A.append && step >= 1) ? n_res : -1;   // n_res is bumped by the very last workgroup
+  // the slot adsa_select reserved for the query token (Section 4.2 append), if this launch fills it
+  int new_slot = A.append ? sq.pending_slot : -1;
+  if (new_slot >= A.cap) new_slot = -1;
+  int32_t* s_slot = reinterpret_cast<int32_t*>(s_dyn);
+  float* s_logit = s_dyn + A.chunk_max;
+  const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
+  for (int i = tid; i < len; i += kAttThreads) s_slot[i] = min(max(idx[t_begin + i], 0), A.cap - 1);
+
   float qf[EPL];
   const size_t row_off = ((size_t)b * A.n_heads + head_c) * D * EB + dl * 16;
   {
@@ -150,30 +210,31 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   const long long lane_off = (long long)head_c * A.head_stride_b + dl * 16;
   char* kb = reinterpret_cast<char*>(sq.k) + lane_off;
   char* vb = reinterpret_cast<char*>(sq.v) + lane_off;
-  const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
+  const char* kn = A.k_new + row_off;
+  const char* vn = A.v_new + row_off;
+  if (new_slot >= 0 && chunk == n_chunks - 1 && wave == 0 && ts == 0 && head_ok) {
+    const long long off = (long long)new_slot * A.slot_stride_b;     // this group's rows of the new token
+    *reinterpret_cast<uint4*>(kb + off) = *reinterpret_cast<const uint4*>(kn);
+    *reinterpret_cast<uint4*>(vb + off) = *reinterpret_cast<const uint4*>(vn);
+  }
+  __syncthreads();                                  // s_slot ready
 
   float m = -INFINITY, l = 0.0f, acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.0f;
 
-  for (int t = t_begin + wave * U; t < t_end; t += kAttWaves * U) {
+  // wave w takes token groups w, w+4, ...; a group is TT*U consecutive tokens of the chunk
+  for (int g0 = wave * TT * U; g0 < len; g0 += kAttWaves * TT * U) {
     uint4 kr[U], vr[U];
+    int tl[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int tt = min(t + u, t_end - 1);         // wave-uniform: scalar index load
-      const int slot = min(max(idx[tt], 0), A.cap - 1);   // never touch memory outside the cache
-      if (slot == new_slot) {                       // the query token itself: take it from k_new / v_new
-        kr[u] = *reinterpret_cast<const uint4*>(A.k_new + row_off);
-        vr[u] = *reinterpret_cast<const uint4*>(A.v_new + row_off);
-        if (head_ok && t + u < t_end) {             // ... and append it to the cache (Section 4.2)
-          *reinterpret_cast<uint4*>(kb + (long long)slot * A.slot_stride_b) = kr[u];
-          *reinterpret_cast<uint4*>(vb + (long long)slot * A.slot_stride_b) = vr[u];
-        }
-      } else {
-        const long long off = (long long)slot * A.slot_stride_b;
-        kr[u] = load_stream16(kb + off);
-        vr[u] = load_stream16(vb + off);
-      }
+      tl[u] = g0 + u * TT + ts;
+      const int slot = s_slot[min(tl[u], len - 1)];
+      const long long off = (long long)slot * A.slot_stride_b;
+      const bool is_new = slot == new_slot;         // the query token itself: read it from k_new / v_new
+      kr[u] = load_stream16(is_new ? kn : kb + off);
+      vr[u] = load_stream16(is_new ? vn : vb + off);
     }
     float z[U];
     float m_new = m;
@@ -185,153 +246,178 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
 #pragma unroll
       for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kf[e], d);
       d = row_sum<LPR>(d);
-      z[u] = (t + u < t_end) ? d : -INFINITY;
+      z[u] = (tl[u] < len) ? d : -INFINITY;
       m_new = fmaxf(m_new, z[u]);
     }
     if (A.accumulate && dl == 0) {
 #pragma unroll
       for (int u = 0; u < U; ++u)
-        if (t + u < t_end) s_dyn[sub * A.chunk_max + (t + u - t_begin)] = z[u];
+        if (tl[u] < len) s_logit[hs * A.chunk_max + tl[u]] = z[u];
     }
-    const float corr = fast_exp2(m - m_new);
-    l *= corr;
+    if (m_new != -INFINITY) {                       // false only while a lane group has seen no token yet
+      const float corr = fast_exp2(m - m_new);
+      l *= corr;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] *= corr;
+      for (int e = 0; e < EPL; ++e) acc[e] *= corr;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const float pr = fast_exp2(z[u] - m_new);
-      float vf[EPL];
-      Elems<EB>::unpack(vr[u], vf);
-      l += pr;
+      for (int u = 0; u < U; ++u) {
+        const float pr = fast_exp2(z[u] - m_new);
+        float vf[EPL];
+        Elems<EB>::unpack(vr[u], vf);
+        l += pr;
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[e] = fmaf(pr, vf[e], acc[e]);
+        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(pr, vf[e], acc[e]);
+      }
+      m = m_new;
     }
-    m = m_new;
   }
 
-  // ---- merge the four waves through LDS, one partial per (head, chunk) to the workspace
-  if (dl == 0) { s_m[wave][sub] = m; s_l[wave][sub] = l; }
+  // ---- merge the TT lane groups of a wave that hold the same head (lane bits above HT*LPR) ...
 #pragma unroll
-  for (int e = 0; e < EPL; ++e) s_acc[wave][lane][e] = acc[e];
+  for (int d = HT * LPR; d < kWave; d <<= 1) {
+    const float m2 = __shfl_xor(m, d, kWave), l2 = __shfl_xor(l, d, kWave);
+    float a2[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) a2[e] = __shfl_xor(acc[e], d, kWave);
+    merge_state<EPL>(m, l, acc, m2, l2, a2);
+  }
+  // ---- ... then the four waves through LDS
+  if (ts == 0) {
+    if (dl == 0) { s_m[wave][hs] = m; s_l[wave][hs] = l; }
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) s_acc[wave][hs][dl][e] = acc[e];
+  }
   __syncthreads();
-  if (wave == 0 && head_ok) {
-    float M = s_m[0][sub];
+  if (wave == 0 && ts == 0) {
+    float M = -INFINITY, L = 0.0f;
 #pragma unroll
-    for (int w = 1; w < kAttWaves; ++w) M = fmaxf(M, s_m[w][sub]);
-    float lt = 0.0f, at[EPL];
+    for (int w = 0; w < kAttWaves; ++w) M = fmaxf(M, s_m[w][hs]);
+    float at[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) at[e] = 0.0f;
 #pragma unroll
     for (int w = 0; w < kAttWaves; ++w) {
-      const float wgt = fast_exp2(s_m[w][sub] - M);   // a wave without tokens has m = -inf -> 0
-      lt = fmaf(s_l[w][sub], wgt, lt);
+      const float mw = s_m[w][hs];
+      const float wgt = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);   // a wave without tokens
+      L = fmaf(s_l[w][hs], wgt, L);
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) at[e] = fmaf(s_acc[w][lane][e], wgt, at[e]);
+      for (int e = 0; e < EPL; ++e) at[e] = fmaf(s_acc[w][hs][dl][e], wgt, at[e]);
     }
-    const size_t pidx = ((size_t)b * A.n_heads + head) * n_chunks + chunk;
-    if (dl == 0) { A.part_ml[pidx * 2] = M; A.part_ml[pidx * 2 + 1] = lt; }
-    float* pa = A.part_acc + pidx * D + dl * EPL;
+    if (n_chunks == 1) {
+      // -------- the whole list was here: final output of this head
+      if (head_ok) {
+        const float inv = 1.0f / L;
+        const size_t oi = ((size_t)b * A.n_heads + head) * D + dl * EPL;
+        if constexpr (EB == 4) {
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(A.out) + oi) =
+              make_float4(at[0] * inv, at[1] * inv, at[2] * inv, at[3] * inv);
+        } else {
+          uint32_t pk[4];
 #pragma unroll
-    for (int e = 0; e < EPL; e += 4)
-      *reinterpret_cast<float4*>(pa + e) = make_float4(at[e], at[e + 1], at[e + 2], at[e + 3]);
-  }
-  if (A.accumulate) {
-    const int len = t_end - t_begin;
-    for (int i = tid; i < HPW * len; i += kAttThreads) {
-      const int sb = i / len, j = i - sb * len;
-      const int hd = hg * HPW + sb;
-      if (hd < A.n_heads)
-        A.logits[((size_t)b * A.n_heads + hd) * A.lg_stride + t_begin + j] = s_dyn[sb * A.chunk_max + j];
+          for (int e = 0; e < 8; e += 2)
+            pk[e / 2] = f32_to_bf16_rne(at[e] * inv) | (f32_to_bf16_rne(at[e + 1] * inv) << 16);
+          *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(A.out) + oi) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+        }
+        if (dl == 0) {
+          const float lse2 = M + __log2f(L);
+          A.lse[(size_t)b * A.n_heads + head] = lse2 * kLn2;
+          s_lse2[hs] = lse2;
+        }
+      }
+    } else if (head_ok) {
+      const size_t pidx = ((size_t)b * A.n_heads + head) * n_chunks + chunk;
+      if (dl == 0) st_dev2(A.part_ml + pidx * 2, M, L);
+      float* pa = A.part_acc + pidx * D + dl * EPL;
+#pragma unroll
+      for (int e = 0; e < EPL; e += 2) st_dev2(pa + e, at[e], at[e + 1]);
     }
   }
 
-  // ---- arrival: the last workgroup of this (sequence, head group) merges the chunks
-  int32_t* ctr = A.counters + (size_t)b * (A.n_hg + 1);
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) s_ticket = atomicAdd(&ctr[hg], 1);
+  const int heads_here = min(HT, A.n_heads - hg * HT);
+  if (n_chunks == 1) {
+    // -------- per-head attention mass: score[head][slot] += p, from the logits still in LDS
+    if (A.accumulate) {
+      __syncthreads();
+      const int cm = A.chunk_max;
+      add_mass(sq.score, A.cap, hg * HT, s_lse2, heads_here * len, [=](int i, int* sb, int* slot, float* z) {
+        *sb = i / len; const int j = i - *sb * len; *slot = s_slot[j]; *z = s_logit[*sb * cm + j];
+      });
+    }
+    if (hg == 0 && tid == 0 && A.advance) sq.step = sq.step + 1;   // no other workgroup reads step
+    return;
+  }
+
+  // -------- several chunks: publish logits, arrive, and let the last workgroup finish the group
+  if (A.accumulate) {
+    for (int i = tid; i < heads_here * len; i += kAttThreads) {
+      const int sb = i / len, j = i - sb * len;
+      st_dev(A.logits + ((size_t)b * A.n_heads + hg * HT + sb) * A.lg_stride + t_begin + j, s_logit[sb * A.chunk_max + j]);
+    }
+  }
+  const int n_nonempty = min(cnt, n_chunks);
+  int32_t* ctr = A.counters + (size_t)b * A.n_hg + hg;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // every thread's stores have completed ...
+  __syncthreads();                                          // ... before thread 0 announces them
+  if (tid == 0) s_ticket = atomicAdd(ctr, 1);
   __syncthreads();
   if (s_ticket != n_nonempty - 1) return;
-  __threadfence();                                  // acquire: see every chunk's partials and logits
-  if (tid == 0) ctr[hg] = 0;                        // ready for the next launch
+  if (tid == 0) *ctr = 0;                           // ready for the next launch
 
-  for (int o = tid; o < HPW * D; o += kAttThreads) {
+  const bool all_full = cnt >= n_chunks;            // else only `cnt` scattered chunks hold a token
+  for (int o = tid; o < heads_here * D; o += kAttThreads) {
     const int sb = o / D, d = o - sb * D;
-    const int hd = hg * HPW + sb;
-    if (hd >= A.n_heads) continue;
+    const int hd = hg * HT + sb;
     const size_t pbase = ((size_t)b * A.n_heads + hd) * n_chunks;
-    float M = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c)
-      if (chunk_begin(cnt, c, n_chunks) < chunk_begin(cnt, c + 1, n_chunks)) M = fmaxf(M, A.part_ml[(pbase + c) * 2]);
-    float L = 0.0f, a = 0.0f;
-    for (int c = 0; c < n_chunks; ++c) {
-      if (chunk_begin(cnt, c, n_chunks) >= chunk_begin(cnt, c + 1, n_chunks)) continue;   // empty chunk
-      const float wgt = fast_exp2(A.part_ml[(pbase + c) * 2] - M);
-      L = fmaf(A.part_ml[(pbase + c) * 2 + 1], wgt, L);
-      a = fmaf(A.part_acc[(pbase + c) * D + d], wgt, a);
+    float mc[kMaxChunks], lc[kMaxChunks], ac[kMaxChunks];
+#pragma unroll
+    for (int c = 0; c < kMaxChunks; ++c) {          // all loads in flight together
+      const bool on = c < n_chunks && (all_full || chunk_begin(cnt, c, n_chunks) < chunk_begin(cnt, c + 1, n_chunks));
+      mc[c] = on ? ld_dev(A.part_ml + (pbase + c) * 2) : -INFINITY;
+      lc[c] = on ? ld_dev(A.part_ml + (pbase + c) * 2 + 1) : 0.0f;
+      ac[c] = on ? ld_dev(A.part_acc + (pbase + c) * D + d) : 0.0f;
     }
-    const float val = a / L;
+    float Mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < kMaxChunks; ++c) Mx = fmaxf(Mx, mc[c]);
+    float Lx = 0.0f, a = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kMaxChunks; ++c) {
+      const float wgt = (mc[c] == -INFINITY) ? 0.0f : fast_exp2(mc[c] - Mx);
+      Lx = fmaf(lc[c], wgt, Lx);
+      a = fmaf(ac[c], wgt, a);
+    }
+    const float val = a / Lx;
     const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
     if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
     else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
     if (d == 0) {
-      const float lse2 = M + __log2f(L);
+      const float lse2 = Mx + __log2f(Lx);
       A.lse[(size_t)b * A.n_heads + hd] = lse2 * kLn2;
       s_lse2[sb] = lse2;
     }
   }
-  if (!(A.accumulate || A.append || A.advance)) return;
-  __syncthreads();
   if (A.accumulate) {
-    // per attended token: probability summed over this group's heads, ascending head order
-    const float* lg = A.logits + ((size_t)b * A.n_heads + hg * HPW) * A.lg_stride;
-    float* ps = A.psum + ((size_t)b * A.n_hg + hg) * A.lg_stride;
-    const int heads_here = min(HPW, A.n_heads - hg * HPW);
-    for (int j = tid; j < cnt; j += kAttThreads) {
-      float t = 0.0f;
-      for (int sb = 0; sb < heads_here; ++sb) t += fast_exp2(lg[(size_t)sb * A.lg_stride + j] - s_lse2[sb]);
-      ps[j] = t;
-    }
+    __syncthreads();
+    const float* lg = A.logits + ((size_t)b * A.n_heads + hg * HT) * A.lg_stride;
+    const int lgs = A.lg_stride, cap = A.cap;
+    add_mass(sq.score, A.cap, hg * HT, s_lse2, heads_here * cnt, [=](int i, int* sb, int* slot, float* z) {
+      *sb = i / cnt; const int j = i - *sb * cnt;
+      *slot = min(max(idx[j], 0), cap - 1); *z = ld_dev(lg + (size_t)*sb * lgs + j);
+    });
   }
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) s_ticket = atomicAdd(&ctr[A.n_hg], 1);
-  __syncthreads();
-  if (s_ticket != A.n_hg - 1) return;
-  __threadfence();
-  if (tid == 0) ctr[A.n_hg] = 0;
-
-  // ---- the last head group of the sequence: score update, end of append, step counter
-  if (A.accumulate) {
-    const float* ps = A.psum + (size_t)b * A.n_hg * A.lg_stride;
-    for (int j = tid; j < cnt; j += kAttThreads) {
-      const int slot = idx[j];
-      if (slot < 0 || slot >= A.cap) continue;
-      float inc = 0.0f;
-      for (int g = 0; g < A.n_hg; ++g) inc += ps[(size_t)g * A.lg_stride + j];
-      const float base = slot == new_slot ? 0.0f : sq.score[slot];   // a new slot starts at 0
-      sq.score[slot] = base + inc;
-    }
-  } else if (new_slot >= 0 && tid == 0) {
-    sq.score[new_slot] = 0.0f;
-  }
-  if (tid == 0) {
-    if (new_slot >= 0) { sq.pos[new_slot] = sq.grid_origin + step - 1; sq.n_res = n_res + 1; }
-    if (A.advance) sq.step = step + 1;
-  }
+  if (hg == 0 && tid == 0 && A.advance) sq.step = sq.step + 1;
 }
 
-template <int EB, int D>
+template <int EB, int D, int HT>
 hipError_t launch_attend_t(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
   constexpr int U = 4;
-  constexpr int HPW = kWave / (D / Elems<EB>::N);
-  const size_t lds = A.accumulate ? (size_t)HPW * plan.chunk_max * sizeof(float) : 0;
+  const size_t lds = (size_t)(1 + HT) * plan.chunk_max * sizeof(float);
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_attend<EB, D, U>), grid, dim3(kAttThreads), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
+    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U>), grid, dim3(kAttThreads), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
   else
-    hipLaunchKernelGGL((k_attend<EB, D, U>), grid, dim3(kAttThreads), lds, st, A);
+    hipLaunchKernelGGL((k_attend<EB, D, HT, U>), grid, dim3(kAttThreads), lds, st, A);
   return hipGetLastError();
 }
 
@@ -345,17 +431,22 @@ AttendPlan make_attend_plan(const adsa_params& p) {
   AttendPlan a;
   const int epl = 16 / elem_bytes(p);
   a.lanes_per_row = p.head_dim / epl;
-  a.heads_per_wave = kWave / a.lanes_per_row;
-  a.n_head_groups = (p.n_heads + a.heads_per_wave - 1) / a.heads_per_wave;
-  // enough workgroups to put ~3 on each of the 256 CUs, but never chunks shorter than 16 tokens
-  const int target_wgs = 768;
-  int pairs = p.n_seq * a.n_head_groups;
-  int nc = (target_wgs + pairs - 1) / pairs;
-  int max_by_len = p.sel_cap / 16;
-  if (max_by_len < 1) max_by_len = 1;
-  if (nc > max_by_len) nc = max_by_len;
-  if (nc > 64) nc = 64;
-  if (nc < 1) nc = 1;
+  const int rpw = kWave / a.lanes_per_row;
+  // [slot][head][D]: a wave-load takes rpw heads of one token; [head][slot][D]: rpw tokens of one head
+  a.head_major = p.kv_slot_stride < p.kv_head_stride;
+  a.heads_per_group = a.head_major ? 1 : rpw;
+  a.n_head_groups = (p.n_heads + a.heads_per_group - 1) / a.heads_per_group;
+  // one chunk when (sequence, head group) pairs alone put >= 2 workgroups on each of the 256 CUs;
+  // else split the list until ~3 per CU, but never below 32 tokens per chunk
+  const long long pairs = (long long)p.n_seq * a.n_head_groups;
+  int nc = 1;
+  if (pairs < 512) {
+    nc = (int)((768 + pairs - 1) / pairs);
+    int max_by_len = p.sel_cap / 32;
+    if (max_by_len < 1) max_by_len = 1;
+    if (nc > max_by_len) nc = max_by_len;
+    if (nc > kMaxChunks) nc = kMaxChunks;
+  }
   a.n_chunks = nc;
   a.chunk_max = (p.sel_cap + nc - 1) / nc + 1;
   return a;
@@ -366,18 +457,17 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 Workspace make_workspace(const adsa_params& p, const AttendPlan& plan) {
   Workspace w;
   size_t off = 0;
+  const bool split = plan.n_chunks > 1;
   w.lg_stride = (int)align_up((size_t)p.sel_cap, 4);
   w.counters_off = off;
-  off = align_up(off + sizeof(int32_t) * (size_t)p.n_seq * (plan.n_head_groups + 1), 256);
+  off = align_up(off + sizeof(int32_t) * (size_t)p.n_seq * plan.n_head_groups, 256);
   w.persistent_bytes = off;     // must stay zero between launches
   w.logits_off = off;
-  off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * w.lg_stride, 256);
-  w.psum_off = off;
-  off = align_up(off + sizeof(float) * (size_t)p.n_seq * plan.n_head_groups * w.lg_stride, 256);
+  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * w.lg_stride, 256);
   w.part_ml_off = off;
-  off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * 2, 256);
+  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * 2, 256);
   w.part_acc_off = off;
-  off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * p.head_dim, 256);
+  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * p.head_dim, 256);
   w.plan_off = off;
   off = align_up(off + sizeof(int32_t) * (size_t)p.n_seq * 4, 256);
   w.vcos_off = off;
@@ -408,20 +498,27 @@ hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq*
   A.logits = reinterpret_cast<float*>(ws + w.logits_off);
   A.part_ml = reinterpret_cast<float*>(ws + w.part_ml_off);
   A.part_acc = reinterpret_cast<float*>(ws + w.part_acc_off);
-  A.psum = reinterpret_cast<float*>(ws + w.psum_off);
   A.counters = reinterpret_cast<int32_t*>(ws + w.counters_off);
   A.n_heads = p.n_heads; A.n_hg = plan.n_head_groups; A.sel_cap = p.sel_cap; A.lg_stride = w.lg_stride;
-  A.chunk_max = plan.chunk_max; A.cap = p.cap; A.grid_h = p.grid_h; A.grid_w = p.grid_w;
+  A.chunk_max = plan.chunk_max; A.cap = p.cap;
   A.accumulate = accumulate ? 1 : 0; A.append = append ? 1 : 0; A.advance = advance ? 1 : 0;
   const int eb = elem_bytes(p);
   A.slot_stride_b = (long long)p.kv_slot_stride * eb;
   A.head_stride_b = (long long)p.kv_head_stride * eb;
   const float scale = p.softmax_scale != 0.0f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
   A.scale_log2 = scale * kLog2e;
-  if (eb == 2 && p.head_dim == 64) return launch_attend_t<2, 64>(A, plan, p.n_seq, st, ev_start, ev_stop);
-  if (eb == 2 && p.head_dim == 128) return launch_attend_t<2, 128>(A, plan, p.n_seq, st, ev_start, ev_stop);
-  if (eb == 4 && p.head_dim == 64) return launch_attend_t<4, 64>(A, plan, p.n_seq, st, ev_start, ev_stop);
-  if (eb == 4 && p.head_dim == 128) return launch_attend_t<4, 128>(A, plan, p.n_seq, st, ev_start, ev_stop);
+  const int key = eb * 1000 + p.head_dim;
+  if (plan.head_major) {
+    if (key == 2064) return launch_attend_t<2, 64, 1>(A, plan, p.n_seq, st, ev_start, ev_stop);
+    if (key == 2128) return launch_attend_t<2, 128, 1>(A, plan, p.n_seq, st, ev_start, ev_stop);
+    if (key == 4064) return launch_attend_t<4, 64, 1>(A, plan, p.n_seq, st, ev_start, ev_stop);
+    if (key == 4128) return launch_attend_t<4, 128, 1>(A, plan, p.n_seq, st, ev_start, ev_stop);
+  } else {
+    if (key == 2064) return launch_attend_t<2, 64, 8>(A, plan, p.n_seq, st, ev_start, ev_stop);
+    if (key == 2128) return launch_attend_t<2, 128, 4>(A, plan, p.n_seq, st, ev_start, ev_stop);
+    if (key == 4064) return launch_attend_t<4, 64, 4>(A, plan, p.n_seq, st, ev_start, ev_stop);
+    if (key == 4128) return launch_attend_t<4, 128, 2>(A, plan, p.n_seq, st, ev_start, ev_stop);
+  }
   return hipErrorInvalidValue;
 }
 

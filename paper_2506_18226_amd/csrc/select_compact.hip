@@ -123,9 +123,16 @@ __device__ __forceinline__ int effective_budget(const adsa_seq& q, int s) {
 struct LaunchShape {
   int n_heads, head_dim, elem_bytes;
   int grid_h, grid_w, R, w;
-  int cap, sel_cap, score_mode;
+  int cap, sel_cap, score_mode, score_rows;
   long long slot_stride_b, head_stride_b;    // bytes
 };
+
+// Rank of slot i: sum over the score rows, ascending row order, plain fp32 adds.
+__device__ __forceinline__ float rank_value(const float* score, int rows, int cap, int i) {
+  float v = score[i];
+  for (int r = 1; r < rows; ++r) v += score[(size_t)r * cap + i];
+  return v;
+}
 
 __device__ __forceinline__ bool keep_largest_of(int mode) {
   return mode == ADSA_SCORE_ATTN_MASS || mode == ADSA_SCORE_EXT_LARGEST;
@@ -142,9 +149,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   const int status_in = sq.status;
   if (tid == 0) s_bad = 0;
   __syncthreads();
-  if (s < 0 || status_in != 0) { if (tid == 0) sel_cnt[b] = 0; return; }
+  if (s < 0 || status_in != 0) { if (tid == 0) { sel_cnt[b] = 0; sq.pending_slot = -1; } return; }
   if (n < 0 || n > L.cap || s > L.grid_h * L.grid_w) {
-    if (tid == 0) { sq.status = status_in | ADSA_SEQ_BAD_STATE; sel_cnt[b] = 0; }
+    if (tid == 0) { sq.status = status_in | ADSA_SEQ_BAD_STATE; sel_cnt[b] = 0; sq.pending_slot = -1; }
     return;
   }
   // Section 4.2: the query token goes to the end of the cache.  When the append itself happens
@@ -152,7 +159,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   int n_real = n;
   if (plan_append && s >= 1) {
     if (n + 1 > L.cap) {
-      if (tid == 0) { sq.status = status_in | ADSA_SEQ_CACHE_FULL; sel_cnt[b] = 0; }
+      if (tid == 0) { sq.status = status_in | ADSA_SEQ_CACHE_FULL; sel_cnt[b] = 0; sq.pending_slot = -1; }
       return;
     }
     n += 1;
@@ -167,13 +174,13 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
     const int c = planned ? 0 : select_class(cell, sq.pos[i]);
     if (c < 0) s_bad = 1;
     sh.cls[i] = c == 1 ? kCand : kFixed;
-    sh.key[i] = order_key(planned ? 0.0f : sq.score[i], largest);
+    sh.key[i] = order_key(planned ? 0.0f : rank_value(sq.score, L.score_rows, L.cap, i), largest);
     my_cand += (c == 1);
   }
   uint32_t n_cand;
   block_excl_scan(sh, my_cand, &n_cand);   // also orders the LDS writes above before the reads below
   if (s_bad) {
-    if (tid == 0) { sq.status = status_in | ADSA_SEQ_BAD_STATE; sel_cnt[b] = 0; }
+    if (tid == 0) { sq.status = status_in | ADSA_SEQ_BAD_STATE; sel_cnt[b] = 0; sq.pending_slot = -1; }
     return;
   }
 
@@ -205,10 +212,18 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
     if (eq) { take = e_run < need_eq; ++e_run; } else if (take) ++a_run;
     if (take && dest < (uint32_t)L.sel_cap) out[dest] = i;
   }
+  const uint32_t cnt = (total & 0xFFFFu) + min(total >> 16, need_eq);
+  const bool ok = cnt <= (uint32_t)L.sel_cap;
+  const bool reserve = ok && n > n_real;             // commit the planned append: the slot now exists
+  if (reserve)
+    for (int r = tid; r < L.score_rows; r += kSelThreads) sq.score[(size_t)r * L.cap + n_real] = 0.0f;
   if (tid == 0) {
-    const uint32_t cnt = (total & 0xFFFFu) + min(total >> 16, need_eq);
-    if (cnt > (uint32_t)L.sel_cap) { sq.status = status_in | ADSA_SEQ_SEL_OVERFLOW; sel_cnt[b] = 0; }
-    else sel_cnt[b] = (int32_t)cnt;
+    if (!ok) { sq.status = status_in | ADSA_SEQ_SEL_OVERFLOW; sel_cnt[b] = 0; sq.pending_slot = -1; }
+    else {
+      sel_cnt[b] = (int32_t)cnt;
+      sq.pending_slot = reserve ? n_real : -1;
+      if (reserve) { sq.pos[n_real] = sq.grid_origin + s - 1; sq.n_res = n; }
+    }
   }
 }
 
@@ -235,7 +250,7 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   for (int i = tid; i < n; i += kSelThreads) {
     const int c = evict_class(cell, sq.pos[i]);
     sh.cls[i] = c == 1 ? kCand : kFixed;
-    sh.key[i] = order_key(sq.score[i], largest);
+    sh.key[i] = order_key(rank_value(sq.score, L.score_rows, L.cap, i), largest);
     my_rest += (c == 1);
   }
   uint32_t n_rest;
@@ -279,15 +294,21 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   const int first = (int)sh.bcast[2];
   const uint32_t n_new = (total & 0xFFFFu) + min(total >> 16, need_eq);
 
-  // in-place, order-preserving move of pos[] and score[]: ascending tiles, load -> barrier -> store.
-  // A tile's destinations are <= its sources and below the next tile's sources.
-  for (int base = (first / kSelThreads) * kSelThreads; base < n; base += kSelThreads) {
-    const int i = base + tid;
-    int m = -1, pv = 0;
-    float sv = 0.0f;
-    if (i < n) { m = (int)sh.key[i]; if (m >= 0 && m != i) { pv = sq.pos[i]; sv = sq.score[i]; } }
-    __syncthreads();
-    if (m >= 0 && m != i) { sq.pos[m] = pv; sq.score[m] = sv; }
+  // in-place, order-preserving move of pos[] and every score row: ascending tiles, load -> barrier ->
+  // store.  A tile's destinations are <= its sources and below the next tile's sources.
+  for (int row = -1; row < L.score_rows; ++row) {
+    float* srow = row >= 0 ? sq.score + (size_t)row * L.cap : nullptr;
+    for (int base = (first / kSelThreads) * kSelThreads; base < n; base += kSelThreads) {
+      const int i = base + tid;
+      int m = -1, pv = 0;
+      float sv = 0.0f;
+      if (i < n) {
+        m = (int)sh.key[i];
+        if (m >= 0 && m != i) { if (row < 0) pv = sq.pos[i]; else sv = srow[i]; }
+      }
+      __syncthreads();
+      if (m >= 0 && m != i) { if (row < 0) sq.pos[m] = pv; else srow[m] = sv; }
+    }
   }
   if (tid == 0) {
     plan[4 * b + 0] = n; plan[4 * b + 1] = first; plan[4 * b + 2] = 1; plan[4 * b + 3] = (int32_t)n_new;
@@ -343,7 +364,7 @@ LaunchShape shape_of(const adsa_params& p) {
   LaunchShape L;
   L.n_heads = p.n_heads; L.head_dim = p.head_dim; L.elem_bytes = elem_bytes(p);
   L.grid_h = p.grid_h; L.grid_w = p.grid_w; L.R = p.win_rows_back; L.w = p.win_col_radius;
-  L.cap = p.cap; L.sel_cap = p.sel_cap; L.score_mode = p.score_mode;
+  L.cap = p.cap; L.sel_cap = p.sel_cap; L.score_mode = p.score_mode; L.score_rows = score_rows(p);
   L.slot_stride_b = (long long)p.kv_slot_stride * L.elem_bytes;
   L.head_stride_b = (long long)p.kv_head_stride * L.elem_bytes;
   return L;

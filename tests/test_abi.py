@@ -38,11 +38,12 @@ def test_struct_mirrors_match_the_header():
     assert C.sizeof(B.AdsaParams) == 12 * 4 + 2 * 8 + 4 + 4
     assert B.SEQ_DTYPE.itemsize == 80
     assert B.SEQ_DTYPE.fields["n_res"][1] == 32 and B.SEQ_DTYPE.fields["status"][1] == 60
+    assert B.SEQ_DTYPE.fields["pending_slot"][1] == 68
 
 
 def good(**kw):
     base = dict(n_seq=2, n_heads=4, head_dim=64, grid_h=8, grid_w=8, win_rows_back=1, win_col_radius=2,
-                dtype=B.BF16, score_mode=B.SCORE_ATTN_MASS, cap=128, sel_cap=128)
+                dtype=B.BF16, score_mode=B.SCORE_ATTN_MASS, cap=128, sel_cap=128, layout="slot_major")
     base.update(kw)
     return B.make_params(**base)
 
@@ -51,6 +52,9 @@ def test_workspace_size_is_positive_and_monotone(lib):
     a = B.adsa_workspace_bytes(good())
     b = B.adsa_workspace_bytes(good(n_seq=8))
     assert a > 0 and b > a and a % 256 == 0
+    assert B.adsa_workspace_bytes(good(layout="head_major")) > 0
+    # head-major rows of different heads must not overlap: head stride >= cap * slot stride
+    assert B.adsa_workspace_bytes(good(layout="head_major", kv_head_stride=127 * 64)) == 0
 
 
 @pytest.mark.parametrize("kw,code", [

@@ -24,12 +24,15 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def params_for(wl, n_seq, cap, score_mode=None, sel_cap=None):
+def params_for(wl, n_seq, cap, score_mode=None, sel_cap=None, layout="head_major"):
     return B.make_params(n_seq=n_seq, n_heads=wl.n_heads, head_dim=wl.head_dim, grid_h=wl.grid_h,
                          grid_w=wl.grid_w, win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
                          dtype=B.F32 if wl.dtype == "f32" else B.BF16,
                          score_mode=wl.score_mode if score_mode is None else score_mode,
-                         cap=cap, sel_cap=sel_cap)
+                         cap=cap, sel_cap=sel_cap, layout=layout)
+
+
+LAYOUTS = ["head_major", "slot_major"]
 
 
 def load_state(batch, b, st, cfg, step):
@@ -57,20 +60,21 @@ def lse_tol(wl):
 SMALL = dict(n_heads=4, head_dim=64, grid_h=6, grid_w=8, prefix_len=5)
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("name,over,budget,steps", [
     ("tiny", dict(), None, [0, 1, 5, 16, 17, 40, 96, 97, 200, 255, 256]),
     ("tiny", dict(SMALL, win_rows_back=2, win_col_radius=1), 6, [0, 1, 8, 9, 16, 24, 25, 40, 47, 48]),
     ("xl", dict(n_seq=1, n_heads=20, grid_h=6, grid_w=12, prefix_len=17), None, [0, 3, 12, 13, 30, 36, 60, 72]),
     ("long", dict(n_seq=1, n_heads=3, grid_h=5, grid_w=16, prefix_len=9), 20, [0, 1, 16, 33, 48, 64, 80]),
 ])
-def test_step_teacher_forced(name, over, budget, steps):
+def test_step_teacher_forced(name, over, budget, steps, layout):
     """adsa_step on the oracle's state at step s must reproduce the oracle's step: same attended
     set, same keep map and n_res, same moved rows, outputs within the float bars."""
     wl = WL.get_workload(name, **over)
     cfg = oracle_cfg(wl, budget=budget)
     q, k, v, _, snaps = replay(wl, cfg, 0, 0, max(steps), snapshots=set(steps))
     P = cfg.grid_origin
-    params = params_for(wl, len(steps), cfg.cap)
+    params = params_for(wl, len(steps), cfg.cap, layout=layout)
     batch = LayerBatch(params, DEV)
     qs, kn, vn = [], [], []
     for b, s in enumerate(steps):
@@ -87,8 +91,8 @@ def test_step_teacher_forced(name, over, budget, steps):
     out, lse = to_host(batch.out), batch.lse.cpu().numpy()
     sel_idx, sel_cnt = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
     keep_map = batch.keep_map.cpu().numpy()
-    Kd, Vd = to_host(batch.K), to_host(batch.V)
-    posd, scored = batch.pos.cpu().numpy(), batch.score.cpu().numpy()
+    Kd, Vd = batch.k_host(), batch.v_host()
+    posd, scored = batch.pos.cpu().numpy(), batch.rank_host()
     for b, s in enumerate(steps):
         st = snaps[s].copy()
         p = P + s - 1
@@ -189,13 +193,14 @@ def test_select_at_maximum_capacity():
 
 
 # ----------------------------------------------------------------------------- attend alone
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("name,over", [
     ("tiny", dict(n_heads=16, head_dim=64)),
     ("tiny", dict(n_heads=3, head_dim=128)),
     ("xl", dict(n_heads=20, head_dim=64)),
     ("long", dict(n_heads=5, head_dim=128)),
 ])
-def test_attend_matches_oracle_on_ragged_index_lists(name, over):
+def test_attend_matches_oracle_on_ragged_index_lists(name, over, layout):
     """Eq. 5 + attention for index lists of many lengths (1 .. several tiles + ragged tails),
     and the ATTN_MASS accumulation that follows it."""
     wl = WL.get_workload(name, n_seq=1, grid_h=20, grid_w=20, prefix_len=30, **over)
@@ -204,7 +209,7 @@ def test_attend_matches_oracle_on_ragged_index_lists(name, over):
     n_tok = k.shape[0]
     lens = [1, 2, 3, 5, 16, 17, 63, 64, 65, 127, 200, 301, 430]
     cap = n_tok
-    params = params_for(wl, len(lens), cap, score_mode=B.SCORE_ATTN_MASS)
+    params = params_for(wl, len(lens), cap, score_mode=B.SCORE_ATTN_MASS, layout=layout)
     batch = LayerBatch(params, DEV)
     cfg = oracle_cfg(wl, budget=cap, cap=cap, score_mode=B.SCORE_ATTN_MASS)
     sels, score0 = [], []
@@ -223,7 +228,7 @@ def test_attend_matches_oracle_on_ragged_index_lists(name, over):
     qd = to_device(np.stack([q[100 + b] for b in range(len(lens))]), params.dtype, DEV)
     batch.attend(qd)
     torch.cuda.synchronize()
-    out, lse, score = to_host(batch.out), batch.lse.cpu().numpy(), batch.score.cpu().numpy()
+    out, lse, score = to_host(batch.out), batch.lse.cpu().numpy(), batch.rank_host()
     for b, n in enumerate(lens):
         ro, rl, probs = oracle.attend(cfg, k, v, q[100 + b], sels[b], want_probs=True)
         check_out(wl, out[b], ro, f"len={n}")
@@ -238,9 +243,10 @@ def test_attend_matches_oracle_on_ragged_index_lists(name, over):
 
 
 # ----------------------------------------------------------------------------- compact alone
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("name,over", [("tiny", dict(n_heads=2, head_dim=64)), ("xl", dict(n_heads=20, head_dim=64)),
                                        ("long", dict(n_heads=2, head_dim=128))])
-def test_compact_bit_exact(name, over):
+def test_compact_bit_exact(name, over, layout):
     """Section 4.2 per-row eviction given the same score array: keep map, n_res and every moved
     row (K, V, pos, score) bit-exact; sequences not at a row end are untouched."""
     rng = np.random.default_rng(17)
@@ -250,7 +256,7 @@ def test_compact_bit_exact(name, over):
     cases = [(W, 3), (2 * W, 0), (5 * W, 7), (20 * W, 50), (33 * W, 1000), (33 * W - 1, 5), (40 * W, 64), (7 * W, 10)]
     cap = P + H * W
     mode = B.SCORE_EXT_LARGEST
-    params = params_for(wl, len(cases), cap, score_mode=mode)
+    params = params_for(wl, len(cases), cap, score_mode=mode, layout=layout)
     batch = LayerBatch(params, DEV)
     states = []
     for b, (s, Bud) in enumerate(cases):
@@ -270,7 +276,7 @@ def test_compact_bit_exact(name, over):
     torch.cuda.synchronize()
     seqs = batch.read_seqs()
     km = batch.keep_map.cpu().numpy()
-    Kd, Vd, posd, scored = to_host(batch.K), to_host(batch.V), batch.pos.cpu().numpy(), batch.score.cpu().numpy()
+    Kd, Vd, posd, scored = batch.k_host(), batch.v_host(), batch.pos.cpu().numpy(), batch.rank_host()
     for b, (s, Bud) in enumerate(cases):
         cfg, st = states[b]
         n_old = st.n_res
@@ -401,3 +407,48 @@ def test_split_phase_steps_over_several_layers():
                 check_out(wl, out[i], ref["out"], tag)
                 assert seqs["n_res"][i] == st.n_res, tag
                 assert np.array_equal(posd[i, :st.n_res], st.pos[:st.n_res]), tag
+
+
+# ----------------------------------------------------------------------------- per-head score rows
+def test_rank_is_the_sum_of_the_per_head_score_rows():
+    """ATTN_MASS keeps one accumulator row per head; a slot's rank is their sum.  With rows whose
+    sums are exact in fp32 (multiples of 1/8) the sum is order-free, so the oracle given the summed
+    array must agree bit for bit, both for the attended set and for the keep map; compaction must
+    move every row."""
+    rng = np.random.default_rng(31)
+    W, H, P, h = 8, 12, 6, 5
+    wl = WL.get_workload("tiny", n_heads=h, head_dim=64, grid_h=H, grid_w=W, prefix_len=P, win_rows_back=1, win_col_radius=2)
+    q, k, v = WL.gen_tokens(wl, 0, 0)
+    cases = [(5 * W, 7), (9 * W, 20), (9 * W - 3, 11), (12 * W, 3)]
+    cap = P + H * W
+    params = params_for(wl, len(cases), cap, score_mode=B.SCORE_ATTN_MASS)
+    batch = LayerBatch(params, DEV)
+    rows_all, cfgs, poss = [], [], []
+    for b, (s, Bud) in enumerate(cases):
+        n = P + s
+        rows = (rng.integers(0, 9, size=(h, n)) / 8.0).astype(np.float32)
+        rows_all.append(rows)
+        cfg = oracle_cfg(wl, P=P, budget=Bud, score_mode=B.SCORE_ATTN_MASS, cap=cap)
+        cfgs.append(cfg)
+        pos = np.arange(n, dtype=np.int32)
+        poss.append(pos)
+        batch.set_sequence(b, k=k[:n], v=v[:n], pos=pos, score=rows, step=s, grid_origin=P, budget=Bud)
+    batch.upload_seqs()
+    batch.select()
+    batch.compact()
+    torch.cuda.synchronize()
+    sel_idx, sel_cnt, km = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy(), batch.keep_map.cpu().numpy()
+    score_rows = batch.score.cpu().numpy()
+    seqs = batch.read_seqs()
+    for b, (s, Bud) in enumerate(cases):
+        total = rows_all[b].sum(axis=0, dtype=np.float32)
+        ref_sel, _ = oracle.select(cfgs[b], poss[b], total, None, s)
+        assert np.array_equal(sel_idx[b, :sel_cnt[b]], ref_sel), (s, Bud)
+        n = P + s
+        st = oracle.CacheState.from_arrays(cfgs[b], k[:n], v[:n], poss[b], total)
+        ref_map, did = oracle.compact(cfgs[b], st, s)
+        assert bool(seqs["compacted"][b]) == did
+        if did:
+            assert np.array_equal(km[b, :n], ref_map)
+            kept = np.nonzero(ref_map >= 0)[0]
+            assert np.array_equal(score_rows[b, :, :kept.size], rows_all[b][:, kept])
