@@ -63,8 +63,8 @@ class Job:
         S = self.n_steps_total
         for l in range(n_layers):
             qd, kd, vd = WL.gen_tokens_device(wl, l, device)        # [n][L][h][D]
-            mb.K[l * n:(l + 1) * n, :P] = kd[:, :P]
-            mb.V[l * n:(l + 1) * n, :P] = vd[:, :P]
+            mb.K[l * n:(l + 1) * n, :, :P] = kd[:, :P].transpose(1, 2)      # [head][slot][D] caches
+            mb.V[l * n:(l + 1) * n, :, :P] = vd[:, :P].transpose(1, 2)
             # step s queries with the token at position P+s-1: step-major [S][n][h][D]
             self.q.append(qd[:, P - 1:P - 1 + S].permute(1, 0, 2, 3).contiguous())
             self.kn.append(kd[:, P - 1:P - 1 + S].permute(1, 0, 2, 3).contiguous())
@@ -80,7 +80,7 @@ class Job:
         for s in mb.seqs_host:
             s["n_res"], s["step"], s["grid_origin"], s["n_keep_prefix"] = P, 0, P, P
             s["budget"], s["budget_num"], s["budget_den"] = wl.budget, wl.budget_num, wl.budget_den
-            s["status"], s["compacted"] = 0, 0
+            s["status"], s["compacted"], s["pending_slot"] = 0, 0, -1
         mb.upload_seqs()
         mb.score.zero_()
         self.sel_cnt_log.zero_()

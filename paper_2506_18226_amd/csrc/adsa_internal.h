@@ -13,7 +13,10 @@ namespace adsa {
 
 constexpr int kWave = 64;
 constexpr int kSelThreads = 256;       // select / compact-plan workgroup
-constexpr int kAttThreads = 256;       // attend workgroup: 4 waves share one token chunk
+#ifndef ADSA_ATT_THREADS
+#define ADSA_ATT_THREADS 256
+#endif
+constexpr int kAttThreads = ADSA_ATT_THREADS;   // attend workgroup: its waves share one token chunk
 constexpr int kAttWaves = kAttThreads / kWave;
 constexpr int kMoveThreads = 256;
 

@@ -156,7 +156,8 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   constexpr int LPR = D / EPL;                      // lanes per row
   constexpr int RPW = kWave / LPR;                  // rows per wave-load
   constexpr int TT = RPW / HT;                      // tokens per wave-load
-  extern __shared__ float s_dyn[];                  // [chunk_max] slots, then logits tile [HT][chunk_max]
+  constexpr int PF = 4;                             // score read-modify-writes a thread starts early
+  extern __shared__ float s_logit[];                // logits tile [HT][chunk_max]
   __shared__ float s_m[kAttWaves][HT], s_l[kAttWaves][HT];
   __shared__ float s_acc[kAttWaves][HT][LPR][EPL];
   __shared__ float s_lse2[HT];
@@ -164,16 +165,46 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
 
   const int chunk = blockIdx.x, hg = blockIdx.y, b = blockIdx.z, n_chunks = gridDim.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
-  const int cnt = min(A.sel_cnt[b], A.sel_cap);
+  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int sub = lane / LPR, dl = lane - sub * LPR;
+  const int hs = sub % HT, ts = sub / HT;           // head and token of this lane's row within a wave-load
+  const int head = hg * HT + hs;
+  const bool head_ok = head < A.n_heads;
+  const int head_c = head_ok ? head : A.n_heads - 1;
+  const int heads_here = min(HT, A.n_heads - hg * HT);
+  const bool direct = n_chunks == 1;                // this workgroup sees the whole list of its heads
+
+  // ---- everything the first K/V loads depend on is requested here, in one round trip: the
+  // count, the sequence record, q, and (when the list is not split, so its chunk starts at 0)
+  // the first slots of the loop and the score words this thread will update at the end.
+  adsa_seq& sq = A.seqs[b];
+  const int cnt_raw = A.sel_cnt[b];
+  char* const k_base = reinterpret_cast<char*>(sq.k);
+  char* const v_base = reinterpret_cast<char*>(sq.v);
+  float* const score = sq.score;
+  const int pending = sq.pending_slot;
+  const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
+  const size_t row_off = ((size_t)b * A.n_heads + head_c) * D * EB + dl * 16;
+  const uint4 qr = *reinterpret_cast<const uint4*>(A.q + row_off);
+  int slot_cur[U];
+  int pf_slot[PF];
+  if (direct) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot_cur[u] = idx[min(wave * TT * U + u * TT + ts, A.sel_cap - 1)];
+#pragma unroll
+    for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * kAttThreads, A.sel_cap - 1)];
+  }
+
+  const int cnt = min(cnt_raw, A.sel_cap);
   if (cnt <= 0) {                                   // inactive or rejected sequence: zero-filled row
     if (chunk == 0) {
       for (int o = tid; o < HT * D; o += kAttThreads) {
-        const int head = hg * HT + o / D;
-        if (head < A.n_heads) {
-          const size_t oi = ((size_t)b * A.n_heads + head) * D + (o % D);
+        const int hd = hg * HT + o / D;
+        if (hd < A.n_heads) {
+          const size_t oi = ((size_t)b * A.n_heads + hd) * D + (o % D);
           if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = 0.0f;
           else reinterpret_cast<uint16_t*>(A.out)[oi] = 0;
-          if (o % D == 0) A.lse[(size_t)b * A.n_heads + head] = 0.0f;
+          if (o % D == 0) A.lse[(size_t)b * A.n_heads + hd] = 0.0f;
         }
       }
     }
@@ -182,34 +213,38 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   const int t_begin = chunk_begin(cnt, chunk, n_chunks), t_end = chunk_begin(cnt, chunk + 1, n_chunks);
   if (t_begin >= t_end) return;                     // fewer tokens than chunks
   const int len = t_end - t_begin;
-
-  const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-  const int sub = lane / LPR, dl = lane - sub * LPR;
-  const int hs = sub % HT, ts = sub / HT;           // head and token of this lane's row within a wave-load
-  const int head = hg * HT + hs;
-  const bool head_ok = head < A.n_heads;
-  const int head_c = head_ok ? head : A.n_heads - 1;
-
-  adsa_seq& sq = A.seqs[b];
   // the slot adsa_select reserved for the query token (Section 4.2 append), if this launch fills it
-  int new_slot = A.append ? sq.pending_slot : -1;
-  if (new_slot >= A.cap) new_slot = -1;
-  int32_t* s_slot = reinterpret_cast<int32_t*>(s_dyn);
-  float* s_logit = s_dyn + A.chunk_max;
-  const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
-  for (int i = tid; i < len; i += kAttThreads) s_slot[i] = min(max(idx[t_begin + i], 0), A.cap - 1);
+  const int new_slot = (A.append && pending < A.cap) ? pending : -1;
+
+  // pair i of the final score update is (head i / len, token i % len); start the first PF reads now
+  const int n_pairs = heads_here * len;
+  float pf_old[PF];
+  if (direct && A.accumulate) {
+#pragma unroll
+    for (int k = 0; k < PF; ++k) {
+      const int i = tid + k * kAttThreads;
+      pf_old[k] = 0.0f;
+      if (i < n_pairs) {
+        const int sb = i / len;
+        int slot = pf_slot[k];
+        if (HT > 1) slot = idx[i - sb * len];        // several heads per workgroup: pair i is not token i
+        pf_slot[k] = min(max(slot, 0), A.cap - 1);
+        pf_old[k] = score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]];
+      }
+    }
+  }
+  if (!direct) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot_cur[u] = idx[t_begin + min(wave * TT * U + u * TT + ts, len - 1)];
+  }
 
   float qf[EPL];
-  const size_t row_off = ((size_t)b * A.n_heads + head_c) * D * EB + dl * 16;
-  {
-    const uint4 qr = *reinterpret_cast<const uint4*>(A.q + row_off);
-    Elems<EB>::unpack(qr, qf);
+  Elems<EB>::unpack(qr, qf);
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) qf[e] *= A.scale_log2;
-  }
+  for (int e = 0; e < EPL; ++e) qf[e] *= A.scale_log2;
   const long long lane_off = (long long)head_c * A.head_stride_b + dl * 16;
-  char* kb = reinterpret_cast<char*>(sq.k) + lane_off;
-  char* vb = reinterpret_cast<char*>(sq.v) + lane_off;
+  char* kb = k_base + lane_off;
+  char* vb = v_base + lane_off;
   const char* kn = A.k_new + row_off;
   const char* vn = A.v_new + row_off;
   if (new_slot >= 0 && chunk == n_chunks - 1 && wave == 0 && ts == 0 && head_ok) {
@@ -217,25 +252,28 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
     *reinterpret_cast<uint4*>(kb + off) = *reinterpret_cast<const uint4*>(kn);
     *reinterpret_cast<uint4*>(vb + off) = *reinterpret_cast<const uint4*>(vn);
   }
-  __syncthreads();                                  // s_slot ready
 
   float m = -INFINITY, l = 0.0f, acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.0f;
 
-  // wave w takes token groups w, w+4, ...; a group is TT*U consecutive tokens of the chunk
+  // wave w takes token groups w, w+4, ...; a group is TT*U consecutive tokens of the chunk.
+  // The slots of the next group are fetched while this group's rows are in flight.
   for (int g0 = wave * TT * U; g0 < len; g0 += kAttWaves * TT * U) {
     uint4 kr[U], vr[U];
     int tl[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       tl[u] = g0 + u * TT + ts;
-      const int slot = s_slot[min(tl[u], len - 1)];
+      const int slot = min(max(slot_cur[u], 0), A.cap - 1);   // never touch memory outside the cache
       const long long off = (long long)slot * A.slot_stride_b;
       const bool is_new = slot == new_slot;         // the query token itself: read it from k_new / v_new
       kr[u] = load_stream16(is_new ? kn : kb + off);
       vr[u] = load_stream16(is_new ? vn : vb + off);
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      slot_cur[u] = idx[t_begin + min(tl[u] + kAttWaves * TT * U, len - 1)];
     float z[U];
     float m_new = m;
 #pragma unroll
@@ -303,7 +341,7 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
 #pragma unroll
       for (int e = 0; e < EPL; ++e) at[e] = fmaf(s_acc[w][hs][dl][e], wgt, at[e]);
     }
-    if (n_chunks == 1) {
+    if (direct) {
       // -------- the whole list was here: final output of this head
       if (head_ok) {
         const float inv = 1.0f / L;
@@ -333,15 +371,27 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
     }
   }
 
-  const int heads_here = min(HT, A.n_heads - hg * HT);
-  if (n_chunks == 1) {
+  if (direct) {
     // -------- per-head attention mass: score[head][slot] += p, from the logits still in LDS
     if (A.accumulate) {
       __syncthreads();
-      const int cm = A.chunk_max;
-      add_mass(sq.score, A.cap, hg * HT, s_lse2, heads_here * len, [=](int i, int* sb, int* slot, float* z) {
-        *sb = i / len; const int j = i - *sb * len; *slot = s_slot[j]; *z = s_logit[*sb * cm + j];
-      });
+#pragma unroll
+      for (int k = 0; k < PF; ++k) {                // reads were started before the loop
+        const int i = tid + k * kAttThreads;
+        if (i < n_pairs) {
+          const int sb = i / len, j = i - sb * len;
+          score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]] =
+              pf_old[k] + fast_exp2(s_logit[sb * A.chunk_max + j] - s_lse2[sb]);
+        }
+      }
+      if (n_pairs > PF * kAttThreads) {
+        const int cm = A.chunk_max, cap = A.cap;
+        add_mass(score, A.cap, hg * HT, s_lse2, n_pairs - PF * kAttThreads, [=](int i, int* sb, int* slot, float* z) {
+          const int ii = i + PF * kAttThreads;
+          *sb = ii / len; const int j = ii - *sb * len;
+          *slot = min(max(idx[j], 0), cap - 1); *z = s_logit[*sb * cm + j];
+        });
+      }
     }
     if (hg == 0 && tid == 0 && A.advance) sq.step = sq.step + 1;   // no other workgroup reads step
     return;
@@ -400,7 +450,7 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
     __syncthreads();
     const float* lg = A.logits + ((size_t)b * A.n_heads + hg * HT) * A.lg_stride;
     const int lgs = A.lg_stride, cap = A.cap;
-    add_mass(sq.score, A.cap, hg * HT, s_lse2, heads_here * cnt, [=](int i, int* sb, int* slot, float* z) {
+    add_mass(score, A.cap, hg * HT, s_lse2, heads_here * cnt, [=](int i, int* sb, int* slot, float* z) {
       *sb = i / cnt; const int j = i - *sb * cnt;
       *slot = min(max(idx[j], 0), cap - 1); *z = ld_dev(lg + (size_t)*sb * lgs + j);
     });
@@ -411,8 +461,11 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
 template <int EB, int D, int HT>
 hipError_t launch_attend_t(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
-  constexpr int U = 4;
-  const size_t lds = (size_t)(1 + HT) * plan.chunk_max * sizeof(float);
+#ifndef ADSA_ATT_U
+#define ADSA_ATT_U 4
+#endif
+  constexpr int U = ADSA_ATT_U;
+  const size_t lds = (size_t)HT * plan.chunk_max * sizeof(float);
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)
     hipExtLaunchKernelGGL((k_attend<EB, D, HT, U>), grid, dim3(kAttThreads), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
