@@ -49,3 +49,27 @@ def near_tie_ok(sel_gpu, sel_ref, score_ref, rel=1e-5, abs_tol=1e-7):
     vals = np.concatenate([score_ref[only_a], score_ref[only_b]]).astype(np.float64)
     spread = vals.max() - vals.min()
     return bool(spread <= abs_tol + rel * np.abs(vals).max())
+
+
+def oracle_step_phases(cfg, st, s, q, k_new, v_new):
+    """oracle.step spelled out phase by phase (append, select, attend, accumulate, compact) so that a
+    test can look at the scores the eviction ranked.  Returns the dict of oracle.step plus
+    'score_ranked': the score array just before compaction (slots before compaction)."""
+    n0 = st.n_res
+    if s >= 1:
+        if n0 + 1 > cfg.cap:
+            raise RuntimeError("cache full")
+        st.K[n0], st.V[n0], st.pos[n0], st.score[n0] = k_new, v_new, cfg.grid_origin + s - 1, 0.0
+        st.n_res = n0 + 1
+    n = st.n_res
+    sel, score = oracle.select(cfg, st.pos[:n], st.score[:n], st.V[:n], s)
+    st.score[:n] = score
+    out, lse, probs = oracle.attend(cfg, st.K, st.V, q, sel, want_probs=True)
+    if cfg.score_mode == 0:
+        st.score[:n] = oracle.accumulate(cfg, st.score[:n], sel, probs)
+    ranked = st.score[:n].copy()
+    keep_map, did = oracle.compact(cfg, st, s)
+    if did and cfg.score_mode == 1:
+        pass  # compact() recomputed the V-cosine over the rest itself
+    return {"out": out, "lse": lse, "sel_idx": sel, "keep_map": keep_map if did else None,
+            "compacted": did, "n_res": st.n_res, "score_ranked": ranked}

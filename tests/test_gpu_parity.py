@@ -17,7 +17,7 @@ from paper_2506_18226_amd import binding as B
 from paper_2506_18226_amd import workloads as WL
 from paper_2506_18226_amd.batch import LayerBatch, ModelBatch, to_device, to_host
 
-from common import oracle_cfg, replay, near_tie_ok
+from common import oracle_cfg, replay, near_tie_ok, oracle_step_phases
 
 pytestmark = pytest.mark.gpu
 
@@ -452,3 +452,161 @@ def test_rank_is_the_sum_of_the_per_head_score_rows():
             assert np.array_equal(km[b, :n], ref_map)
             kept = np.nonzero(ref_map >= 0)[0]
             assert np.array_equal(score_rows[b, :, :kept.size], rows_all[b][:, kept])
+
+
+# ----------------------------------------------------------------------------- TopK-V (Eq. 2-4) on the GPU
+def vcos_close(gpu, ref):
+    """fp32 two-pass closed form vs the fp64 pairwise definition: |S| <= 1, sums of up to ~1e3 unit
+    vectors of dimension up to 4096 in fp32 -> absolute error ~1e-7; bar 2e-6 + 1e-4 relative."""
+    return np.allclose(gpu, ref, rtol=1e-4, atol=2e-6)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("name,over,budget,steps", [
+    ("tiny", dict(n_heads=4, head_dim=64, grid_h=8, grid_w=8, prefix_len=6), 9, [0, 1, 9, 24, 25, 40, 63, 64]),
+    ("xl", dict(n_seq=1, n_heads=20, grid_h=6, grid_w=12, prefix_len=17, budget_num=0, budget_den=0), 21, [13, 36, 37, 60, 72]),
+    ("long", dict(n_seq=1, n_heads=3, grid_h=5, grid_w=16, prefix_len=9), 12, [17, 48, 64, 80]),
+])
+def test_vcos_step_teacher_forced(name, over, budget, steps, layout):
+    """The paper's own ranking: mean pairwise V-cosine over the candidates (Eq. 2-3), keep the K
+    lowest (Eq. 4), evict the most redundant at row ends (Section 4.2).  Scores within the float
+    bar of the O(N^2 D) definition; the attended set and the keep map equal the oracle's, or differ
+    only among candidates whose oracle scores tie within that bar."""
+    wl = WL.get_workload(name, score_mode=WL.SCORE_VCOS, **over)
+    cfg = oracle_cfg(wl, budget=budget, score_mode=WL.SCORE_VCOS)
+    q, k, v, _, snaps = replay(wl, cfg, 0, 0, max(steps), snapshots=set(steps))
+    P = cfg.grid_origin
+    params = params_for(wl, len(steps), cfg.cap, score_mode=B.SCORE_VCOS, layout=layout)
+    batch = LayerBatch(params, DEV)
+    qs, kn, vn = [], [], []
+    for b, s in enumerate(steps):
+        load_state(batch, b, snaps[s], cfg, s)
+        p = P + s - 1
+        qs.append(q[p]); kn.append(k[p]); vn.append(v[p])
+    batch.upload_seqs()
+    qd, kd, vd = (to_device(np.stack(x), params.dtype, DEV) for x in (qs, kn, vn))
+    batch.select(flags=B.FLAG_PLAN_APPEND)            # phase 1: scores + attended set
+    torch.cuda.synchronize()
+    score_sel = batch.rank_host()
+    sel_idx, sel_cnt = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
+    batch.attend(qd, flags=B.FLAG_APPEND, k_new=kd, v_new=vd)
+    batch.compact(flags=B.FLAG_ADVANCE)
+    torch.cuda.synchronize()
+    seqs = batch.read_seqs()
+    out, keep_map, posd = to_host(batch.out), batch.keep_map.cpu().numpy(), batch.pos.cpu().numpy()
+    for b, s in enumerate(steps):
+        st = snaps[s].copy()
+        p = P + s - 1
+        tag = f"{name} s={s}"
+        # oracle, phase by phase on the same state
+        n0 = st.n_res
+        if s >= 1:
+            st.K[n0], st.V[n0], st.pos[n0], st.score[n0] = k[p], v[p], P + s - 1, 0.0
+            st.n_res = n0 + 1
+        ref_sel, ref_score = oracle.select(cfg, st.pos[:st.n_res], st.score[:st.n_res], st.V[:st.n_res], s)
+        cls = oracle.classify(cfg, st.pos[:st.n_res], s)
+        cand = np.nonzero(cls == oracle.CANDIDATE)[0]
+        assert vcos_close(score_sel[b, cand], ref_score[cand]), tag
+        sel = sel_idx[b, :sel_cnt[b]]
+        assert sel.size == ref_sel.size, tag
+        assert near_tie_ok(sel, ref_sel, ref_score, rel=1e-4, abs_tol=4e-6), tag
+        if np.array_equal(sel, ref_sel):
+            ro, _ = oracle.attend(cfg, st.K, st.V, q[p], ref_sel)
+            check_out(wl, out[b], ro, tag)
+        st.score[:st.n_res] = ref_score
+        before = st.copy()
+        ref_map, did = oracle.compact(cfg, st, s)
+        assert bool(seqs["compacted"][b]) == did, tag
+        assert seqs["step"][b] == s + 1 and seqs["n_res"][b] == st.n_res, tag
+        if did:
+            gm = keep_map[b, :ref_map.size]
+            kept_g, kept_r = np.nonzero(gm >= 0)[0], np.nonzero(ref_map >= 0)[0]
+            assert gm[kept_g].tolist() == list(range(kept_g.size)), tag
+            assert near_tie_ok(kept_g, kept_r, before.score, rel=1e-4, abs_tol=4e-6), tag
+            if np.array_equal(kept_g, kept_r):
+                assert np.array_equal(posd[b, :st.n_res], st.pos[:st.n_res]), tag
+
+
+# ----------------------------------------------------------------------------- full-size launches
+def _full_layer(wl_name, steps, layout="head_major"):
+    """One layer of a full-size workload in the launch configuration the benchmark times: every
+    sequence at decode step `steps[b]`, legal synthetic states, split-phase calls."""
+    wl = WL.get_workload(wl_name)
+    n = wl.n_seq
+    cap = 120 + 512 + 2 * wl.grid_w if wl.ragged else wl.cap()
+    sel_cap = 120 + 512 + wl.grid_w + wl.win_rows_back * (2 * wl.win_col_radius + 1) if wl.ragged else wl.sel_cap()
+    params = params_for(wl, n, cap, sel_cap=sel_cap, layout=layout)
+    batch = LayerBatch(params, DEV)
+    items = []
+    for b in range(n):
+        P, Bud, s_r = WL.seq_geometry(wl, b)
+        s = s_r if wl.ragged else steps[b % len(steps)]
+        syn = WL.synthetic_state(wl, 0, b, s, prefix_len=P, budget=Bud)
+        cfg = oracle_cfg(wl, P=P, budget=Bud, cap=cap)
+        st = oracle.CacheState.from_arrays(cfg, syn["k"], syn["v"], syn["pos"], syn["score"])
+        load_state(batch, b, st, cfg, s)
+        items.append((cfg, st, s, syn))
+    batch.upload_seqs()
+    qd = to_device(np.stack([it[3]["q"] for it in items]), params.dtype, DEV)
+    kd = to_device(np.stack([it[3]["k_new"] for it in items]), params.dtype, DEV)
+    vd = to_device(np.stack([it[3]["v_new"] for it in items]), params.dtype, DEV)
+    return wl, params, batch, items, qd, kd, vd
+
+
+def _check_full_step(wl, batch, items):
+    seqs = batch.read_seqs()
+    out, lse = to_host(batch.out), batch.lse.cpu().numpy()
+    sel_idx, sel_cnt = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
+    keep_map, posd, rank = batch.keep_map.cpu().numpy(), batch.pos.cpu().numpy(), batch.rank_host()
+    Kd, Vd = batch.k_host(), batch.v_host()
+    n_compacted = 0
+    for b, (cfg, st, s, syn) in enumerate(items):
+        tag = f"{wl.name} seq={b} s={s}"
+        ref = oracle_step_phases(cfg, st, s, syn["q"], syn["k_new"], syn["v_new"])
+        assert seqs["status"][b] == 0 and seqs["step"][b] == s + 1, tag
+        assert np.array_equal(sel_idx[b, :sel_cnt[b]], ref["sel_idx"]), tag          # same score array: bit-exact
+        check_out(wl, out[b], ref["out"], tag)
+        assert np.abs(lse[b] - ref["lse"]).max() <= lse_tol(wl), tag
+        assert bool(seqs["compacted"][b]) == ref["compacted"], tag
+        n = st.n_res
+        assert seqs["n_res"][b] == n, tag
+        if ref["compacted"]:
+            n_compacted += 1
+            km = ref["keep_map"]
+            g = keep_map[b, :km.size]
+            if not np.array_equal(g, km):
+                # ranks were accumulated in fp32 on the GPU: only near-ties (by the oracle's scores) may differ
+                assert near_tie_ok(np.nonzero(g >= 0)[0], np.nonzero(km >= 0)[0], ref["score_ranked"], rel=1e-5), tag
+                continue
+        assert np.array_equal(posd[b, :n], st.pos[:n]), tag
+        assert np.array_equal(Kd[b, :n], st.K[:n]) and np.array_equal(Vd[b, :n], st.V[:n]), tag
+        assert np.allclose(rank[b, :n], st.score[:n], rtol=1e-5, atol=1e-6), tag
+    return n_compacted
+
+
+def test_full_size_xxl_layer():
+    """LlamaGen-XXL-shaped layer (32 sequences x 24 heads x 64, bf16, cap 696): deep steps incl. a
+    row end, every sequence checked against the oracle (selection bit-exact, float bars)."""
+    wl, params, batch, items, qd, kd, vd = _full_layer("xxl", steps=[1000, 992, 1024, 513, 33, 960, 1, 700])
+    batch.select(flags=B.FLAG_PLAN_APPEND)
+    batch.attend(qd, flags=B.FLAG_APPEND, k_new=kd, v_new=vd)
+    batch.compact(flags=B.FLAG_ADVANCE)
+    torch.cuda.synchronize()
+    assert _check_full_step(wl, batch, items) >= 8
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_ragged_serving_batch_in_one_step_call(layout):
+    """64 sequences, each at its own decode position, budget and prefix length, in ONE adsa_step."""
+    wl, params, batch, items, qd, kd, vd = _full_layer("ragged", steps=None, layout=layout)
+    batch.step(qd, kd, vd)
+    torch.cuda.synchronize()
+    _check_full_step(wl, batch, items)
+
+
+def test_full_size_long_context_layer():
+    """64x64 grid, 32 heads x 128, bf16, budget 1024, R = 2: the split-list launch (few sequences)."""
+    wl, params, batch, items, qd, kd, vd = _full_layer("long", steps=[4096, 4032, 2049, 130])
+    batch.step(qd, kd, vd)
+    torch.cuda.synchronize()
+    _check_full_step(wl, batch, items)
