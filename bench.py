@@ -27,6 +27,19 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E peak
 
 
+def measured_traffic_ratio(workload):
+    """HBM bytes / algorithmic bytes of k_attend from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy), or None if there is none for this workload."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_attend_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("k_attend_traffic_over_algorithmic:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -37,6 +50,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline-pass", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of known size (1 GiB read + 1 GiB written, 4 times): the "
+                         "reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -165,6 +181,15 @@ def main():
     B.load_library()                                   # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     device = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device=device)      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 2, "calibrate_copy_bytes_written": src.numel() * 2,
+                          "copies": 4}))
+        return
     wl = WL.get_workload(args.workload)
     n_layers = args.layers if args.layers > 0 else wl.n_layers
     t_setup = time.perf_counter()
@@ -227,9 +252,13 @@ def main():
         cnt2 = job.sel_cnt_log.cpu().numpy().astype(np.int64)
         att_bytes = int(cnt2[s0:S].sum()) * tau
         achieved = att_bytes / (att_ms * 1e-3) / 1e9
+        ratio = measured_traffic_ratio(wl.name)
         result["roofline"] = {
             "kernel": "k_attend", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None if ratio is None else ratio * att_bytes / max(1, n_launch),
+            "traffic_source": None if ratio is None else
+            f"profiles/{wl.name}_attend_hbm_traffic.txt: measured HBM bytes / algorithmic bytes = {ratio} x this run's bytes per launch",
             "launches": int(n_launch), "avg_launch_us": 1e3 * att_ms / max(1, n_launch),
             "algorithmic_bytes_per_launch": att_bytes / max(1, n_launch),
         }

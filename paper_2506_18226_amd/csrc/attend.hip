@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   constexpr int LPR = D / EPL;                      // lanes per row
   constexpr int RPW = kWave / LPR;                  // rows per wave-load
   constexpr int TT = RPW / HT;                      // tokens per wave-load
-  constexpr int PF = 4;                             // score read-modify-writes a thread starts early
+  constexpr int PF = kAttThreads >= 256 ? 4 : 1024 / kAttThreads;   // score read-modify-writes a thread starts early
   extern __shared__ float s_logit[];                // logits tile [HT][chunk_max]
   __shared__ float s_m[kAttWaves][HT], s_l[kAttWaves][HT];
   __shared__ float s_acc[kAttWaves][HT][LPR][EPL];
