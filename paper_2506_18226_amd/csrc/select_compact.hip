@@ -20,13 +20,15 @@ namespace {
 constexpr uint8_t kFixed = 0;      // prefix / local / protected row: always kept
 constexpr uint8_t kCand = 2;       // competes for the budget
 
+// LDS of one ranking workgroup.  key[] and cls[] are sized by the launch's cap (dynamic LDS:
+// 5 bytes per slot), so small caches leave room for many workgroups per CU.
 struct RankShared {
-  uint32_t key[ADSA_MAX_CAP];      // order-preserving key; later reused for the keep map
-  uint8_t  cls[ADSA_MAX_CAP];
   uint32_t hist[256];
   uint32_t wave_tot[kSelThreads / kWave];
   uint32_t bcast[4];
 };
+
+static size_t rank_lds_bytes(int cap) { return (size_t)cap * 4 + (((size_t)cap + 15) / 16) * 16; }
 
 // Larger key == kept first.  -0 is folded into +0 so that they tie (IEEE equality).
 __device__ __forceinline__ uint32_t order_key(float x, bool keep_largest) {
@@ -66,8 +68,8 @@ __device__ __forceinline__ uint32_t block_excl_scan(RankShared& sh, uint32_t v, 
 
 // Eq. 4 as a threshold: returns T and need_eq such that {key > T} plus the first need_eq slots
 // with key == T (ascending slot) are exactly the `want` best candidates.
-__device__ void radix_threshold(RankShared& sh, int n, uint32_t n_cand, uint32_t want,
-                                uint32_t* T_out, uint32_t* need_eq_out) {
+__device__ void radix_threshold(RankShared& sh, const uint32_t* key, const uint8_t* cls, int n, uint32_t n_cand,
+                                uint32_t want, uint32_t* T_out, uint32_t* need_eq_out) {
   if (want == 0) { *T_out = 0xFFFFFFFFu; *need_eq_out = 0; return; }
   if (want >= n_cand) { *T_out = 0u; *need_eq_out = 0xFFFFFFFFu; return; }
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -76,8 +78,8 @@ __device__ void radix_threshold(RankShared& sh, int n, uint32_t n_cand, uint32_t
     sh.hist[tid] = 0;
     __syncthreads();
     for (int i = tid; i < n; i += kSelThreads) {
-      uint32_t k = sh.key[i];
-      if (sh.cls[i] == kCand && (k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
+      uint32_t k = key[i];
+      if (cls[i] == kCand && (k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
     }
     __syncthreads();
     if (wave == 0) {
@@ -127,10 +129,18 @@ struct LaunchShape {
   long long slot_stride_b, head_stride_b;    // bytes
 };
 
-// Rank of slot i: sum over the score rows, ascending row order, plain fp32 adds.
+// Rank of slot i: sum over the score rows, ascending row order, plain fp32 adds (8 loads in flight).
 __device__ __forceinline__ float rank_value(const float* score, int rows, int cap, int i) {
   float v = score[i];
-  for (int r = 1; r < rows; ++r) v += score[(size_t)r * cap + i];
+  int r = 1;
+  for (; r + 8 <= rows; r += 8) {
+    float t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t[k] = score[(size_t)(r + k) * cap + i];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v += t[k];
+  }
+  for (; r < rows; ++r) v += score[(size_t)r * cap + i];
   return v;
 }
 
@@ -141,6 +151,9 @@ __device__ __forceinline__ bool keep_largest_of(int mode) {
 __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq* seqs, int32_t* sel_idx,
                                                        int32_t* sel_cnt, int plan_append) {
   __shared__ RankShared sh;
+  extern __shared__ uint32_t s_rank_dyn[];
+  uint32_t* key = s_rank_dyn;                                  // [cap] order-preserving keys
+  uint8_t* cls = reinterpret_cast<uint8_t*>(s_rank_dyn + L.cap);   // [cap]
   __shared__ int s_bad;
   const int b = blockIdx.x, tid = threadIdx.x;
   adsa_seq& sq = seqs[b];
@@ -173,8 +186,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
     const bool planned = i >= n_real;               // the slot the query token will occupy
     const int c = planned ? 0 : select_class(cell, sq.pos[i]);
     if (c < 0) s_bad = 1;
-    sh.cls[i] = c == 1 ? kCand : kFixed;
-    sh.key[i] = order_key(planned ? 0.0f : rank_value(sq.score, L.score_rows, L.cap, i), largest);
+    cls[i] = c == 1 ? kCand : kFixed;
+    key[i] = order_key(planned ? 0.0f : rank_value(sq.score, L.score_rows, L.cap, i), largest);
     my_cand += (c == 1);
   }
   uint32_t n_cand;
@@ -187,15 +200,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   // ---- Eq. 4: threshold of the top-B candidates
   const uint32_t B = (uint32_t)effective_budget(sq, s);
   uint32_t T, need_eq;
-  radix_threshold(sh, n, n_cand, B < n_cand ? B : n_cand, &T, &need_eq);
+  radix_threshold(sh, key, cls, n, n_cand, B < n_cand ? B : n_cand, &T, &need_eq);
 
   // ---- ascending slot list: contiguous run of slots per thread, packed (kept | equal<<16) scan
   const int per = (n + kSelThreads - 1) / kSelThreads;
   const int lo = tid * per, hi = min(n, lo + per);
   uint32_t a = 0, e = 0;
   for (int i = lo; i < hi; ++i) {
-    const uint32_t k = sh.key[i];
-    const bool cand = sh.cls[i] == kCand;
+    const uint32_t k = key[i];
+    const bool cand = cls[i] == kCand;
     a += (!cand) || (k > T);
     e += cand && (k == T);
   }
@@ -204,8 +217,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   uint32_t a_run = ex & 0xFFFFu, e_run = ex >> 16;
   int32_t* out = sel_idx + (size_t)b * L.sel_cap;
   for (int i = lo; i < hi; ++i) {
-    const uint32_t k = sh.key[i];
-    const bool cand = sh.cls[i] == kCand;
+    const uint32_t k = key[i];
+    const bool cand = cls[i] == kCand;
     bool take = (!cand) || (k > T);
     const bool eq = cand && (k == T);
     const uint32_t dest = a_run + min(e_run, need_eq);
@@ -232,6 +245,9 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
                                                              int32_t* keep_map, int32_t* plan,
                                                              int advance_step) {
   __shared__ RankShared sh;
+  extern __shared__ uint32_t s_rank_dyn[];
+  uint32_t* key = s_rank_dyn;                                  // [cap] keys, later the keep map
+  uint8_t* cls = reinterpret_cast<uint8_t*>(s_rank_dyn + L.cap);
   const int b = blockIdx.x, tid = threadIdx.x;
   adsa_seq& sq = seqs[b];
   const int s = sq.step, n = sq.n_res, W = L.grid_w;
@@ -249,22 +265,22 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   uint32_t my_rest = 0;
   for (int i = tid; i < n; i += kSelThreads) {
     const int c = evict_class(cell, sq.pos[i]);
-    sh.cls[i] = c == 1 ? kCand : kFixed;
-    sh.key[i] = order_key(rank_value(sq.score, L.score_rows, L.cap, i), largest);
+    cls[i] = c == 1 ? kCand : kFixed;
+    key[i] = order_key(rank_value(sq.score, L.score_rows, L.cap, i), largest);
     my_rest += (c == 1);
   }
   uint32_t n_rest;
   block_excl_scan(sh, my_rest, &n_rest);
   const uint32_t B = (uint32_t)effective_budget(sq, s);
   uint32_t T, need_eq;
-  radix_threshold(sh, n, n_rest, B < n_rest ? B : n_rest, &T, &need_eq);
+  radix_threshold(sh, key, cls, n, n_rest, B < n_rest ? B : n_rest, &T, &need_eq);
 
   const int per = (n + kSelThreads - 1) / kSelThreads;
   const int lo = tid * per, hi = min(n, lo + per);
   uint32_t a = 0, e = 0;
   for (int i = lo; i < hi; ++i) {
-    const uint32_t k = sh.key[i];
-    const bool cand = sh.cls[i] == kCand;
+    const uint32_t k = key[i];
+    const bool cand = cls[i] == kCand;
     a += (!cand) || (k > T);
     e += cand && (k == T);
   }
@@ -274,15 +290,15 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   int32_t* map = keep_map + (size_t)b * L.cap;
   int my_first = n;
   for (int i = lo; i < hi; ++i) {
-    const uint32_t k = sh.key[i];
-    const bool cand = sh.cls[i] == kCand;
+    const uint32_t k = key[i];
+    const bool cand = cls[i] == kCand;
     bool take = (!cand) || (k > T);
     const bool eq = cand && (k == T);
     const uint32_t dest = a_run + min(e_run, need_eq);
     if (eq) { take = e_run < need_eq; ++e_run; } else if (take) ++a_run;
     const int32_t m = take ? (int32_t)dest : -1;
     map[i] = m;
-    sh.key[i] = (uint32_t)m;                 // own run only: no other thread reads key[i] any more
+    key[i] = (uint32_t)m;                 // own run only: no other thread reads key[i] any more
     if (m != i && i < my_first) my_first = i;
   }
   // first slot whose content changes (evicted or moved): everything before it stays put
@@ -303,7 +319,7 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
       int m = -1, pv = 0;
       float sv = 0.0f;
       if (i < n) {
-        m = (int)sh.key[i];
+        m = (int)key[i];
         if (m >= 0 && m != i) { if (row < 0) pv = sq.pos[i]; else sv = srow[i]; }
       }
       __syncthreads();
@@ -374,8 +390,8 @@ LaunchShape shape_of(const adsa_params& p) {
 
 hipError_t launch_select(const adsa_params& p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
                          bool plan_append, hipStream_t st) {
-  hipLaunchKernelGGL(k_select, dim3(p.n_seq), dim3(kSelThreads), 0, st, shape_of(p), seqs, sel_idx, sel_cnt,
-                     plan_append ? 1 : 0);
+  hipLaunchKernelGGL(k_select, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, shape_of(p), seqs,
+                     sel_idx, sel_cnt, plan_append ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -383,8 +399,8 @@ hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_ma
                           const Workspace& w, bool advance_step, hipStream_t st) {
   int32_t* plan = reinterpret_cast<int32_t*>(ws + w.plan_off);
   LaunchShape L = shape_of(p);
-  hipLaunchKernelGGL(k_compact_plan, dim3(p.n_seq), dim3(kSelThreads), 0, st, L, seqs, keep_map, plan,
-                     advance_step ? 1 : 0);
+  hipLaunchKernelGGL(k_compact_plan, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, L, seqs,
+                     keep_map, plan, advance_step ? 1 : 0);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // one workgroup per 128-byte column slice of a head row (whole head row when it is narrower)
