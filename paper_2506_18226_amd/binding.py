@@ -71,6 +71,10 @@ def load_library() -> C.CDLL:
         if not os.path.exists(path):
             raise FileNotFoundError(f"{path} is missing: run `python -m paper_2506_18226_amd.build` "
                                     "(or __graft_entry__.build()) first; there is no fallback path")
+        # torch ships its own HIP runtime: bring it in first so that this library binds to the SAME
+        # runtime instance that owns the tensors' memory and streams (two runtimes in one process
+        # do not see each other's allocations)
+        import torch  # noqa: F401
         lib = C.CDLL(path)
         vp, i32p, f32p = C.c_void_p, C.c_void_p, C.c_void_p
         pp = C.POINTER(AdsaParams)

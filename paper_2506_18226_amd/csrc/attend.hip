@@ -500,6 +500,8 @@ AttendPlan make_attend_plan(const adsa_params& p) {
     if (nc > max_by_len) nc = max_by_len;
     if (nc > kMaxChunks) nc = kMaxChunks;
   }
+  // the logits tile [heads_per_group][chunk] must fit in LDS next to the merge buffers
+  while (nc < kMaxChunks && (size_t)a.heads_per_group * ((p.sel_cap + nc - 1) / nc + 1) * sizeof(float) > 40 * 1024) ++nc;
   a.n_chunks = nc;
   a.chunk_max = (p.sel_cap + nc - 1) / nc + 1;
   return a;

@@ -610,3 +610,71 @@ def test_full_size_long_context_layer():
     batch.step(qd, kd, vd)
     torch.cuda.synchronize()
     _check_full_step(wl, batch, items)
+
+
+# ----------------------------------------------------------------------------- degenerate shapes
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("geom", [
+    dict(grid_h=6, grid_w=1, prefix_len=3, win_rows_back=1, win_col_radius=0, budget=2),    # every step closes a row
+    dict(grid_h=1, grid_w=9, prefix_len=2, win_rows_back=1, win_col_radius=1, budget=3),    # a single row
+    dict(grid_h=4, grid_w=5, prefix_len=0, win_rows_back=0, win_col_radius=0, budget=4),    # no prefix, no previous rows
+    dict(grid_h=3, grid_w=4, prefix_len=5, win_rows_back=3, win_col_radius=9, budget=0),    # window wider than the grid, B = 0
+    dict(grid_h=1, grid_w=1, prefix_len=1, win_rows_back=1, win_col_radius=1, budget=1),    # one image token
+])
+def test_degenerate_grids_free_running(geom, layout):
+    """Whole free-running trajectories on degenerate geometries (1-wide grids, one row, empty prefix
+    so the cache starts EMPTY, zero budget, window larger than the grid) through adsa_step."""
+    geom = dict(geom)
+    budget = geom.pop("budget")
+    wl = WL.get_workload("tiny", n_heads=3, head_dim=64, **geom)
+    P = wl.prefix_len
+    cfg = oracle_cfg(wl, budget=budget, score_mode=B.SCORE_EXT_LARGEST)   # fixed scores: no fp-dependent ranking
+    q, k, v = WL.gen_tokens(wl, 0, 0)
+    st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+    rng = np.random.default_rng(1)
+    params = params_for(wl, 1, cfg.cap, score_mode=B.SCORE_EXT_LARGEST, layout=layout)
+    batch = LayerBatch(params, DEV)
+    s0 = 0 if P > 0 else 1
+    load_state(batch, 0, st, cfg, s0)
+    batch.upload_seqs()
+    qd, kd, vd = (to_device(x, params.dtype, DEV) for x in (q, k, v))
+    for s in range(s0, wl.n_image_tokens + 1):
+        p = P + s - 1
+        batch.step(qd[p:p + 1], kd[p:p + 1], vd[p:p + 1])
+        ref = oracle.step(cfg, st, s, q[p], k[p], v[p])
+        torch.cuda.synchronize()
+        seqs = batch.read_seqs()
+        assert seqs["status"][0] == 0 and seqs["step"][0] == s + 1 and seqs["n_res"][0] == st.n_res, s
+        cnt = int(batch.sel_cnt.cpu()[0])
+        assert np.array_equal(batch.sel_idx.cpu().numpy()[0, :cnt], ref["sel_idx"]), s
+        check_out(wl, to_host(batch.out)[0], ref["out"], f"s={s}")
+        assert np.array_equal(batch.pos.cpu().numpy()[0, :st.n_res], st.pos[:st.n_res]), s
+        assert np.array_equal(batch.k_host()[0, :st.n_res], st.K[:st.n_res]), s
+        # give the slots fresh external scores so that later evictions have something to rank
+        new_scores = (rng.integers(0, 4, st.n_res) / 2.0).astype(np.float32)
+        st.score[:st.n_res] = new_scores
+        batch.score[0, 0, :st.n_res] = torch.from_numpy(new_scores).to(DEV)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_attend_on_a_maximum_length_list(layout):
+    """One sequence attending cap = ADSA_MAX_CAP slots (list split into the maximum number of chunks)."""
+    wl = WL.get_workload("tiny", n_heads=2, head_dim=64, grid_h=91, grid_w=90, prefix_len=2)
+    rng = np.random.default_rng(3)
+    n = B.MAX_CAP
+    k = (rng.standard_normal((n, 2, 64)) / 8).astype(np.float32)
+    v = rng.standard_normal((n, 2, 64)).astype(np.float32)
+    q = rng.standard_normal((2, 64)).astype(np.float32)
+    params = params_for(wl, 1, n, score_mode=B.SCORE_ATTN_MASS, layout=layout)
+    batch = LayerBatch(params, DEV)
+    batch.set_sequence(0, k=k, v=v, pos=np.arange(n, dtype=np.int32), score=None, step=n - 2, grid_origin=2, budget=n)
+    batch.upload_seqs()
+    batch.sel_idx[0] = torch.arange(n, dtype=torch.int32, device=DEV)
+    batch.sel_cnt[0] = n
+    batch.attend(to_device(q[None], params.dtype, DEV))
+    torch.cuda.synchronize()
+    cfg = oracle_cfg(wl, P=2, budget=n, cap=n)
+    ro, rl, probs = oracle.attend(cfg, k, v, q, np.arange(n, dtype=np.int32), want_probs=True)
+    check_out(wl, to_host(batch.out)[0], ro)
+    assert np.abs(batch.lse.cpu().numpy()[0] - rl).max() <= 1e-5
+    assert np.allclose(batch.rank_host()[0], probs.sum(axis=0), rtol=1e-5, atol=1e-7)
