@@ -50,6 +50,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline-pass", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU time budget of the oracle sample")
+    ap.add_argument("--paper-cache", action="store_true",
+                    help="run the paper's own cache policy instead of the headline one: capacity = prefix + half the "
+                         "image tokens, V-cosine ranking (Eq. 2-3), evict one when full, 1-D window, dense attention "
+                         "over everything resident (Section 4.2, Tables 1-2)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (1 GiB read + 1 GiB written, 4 times): the "
                          "reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -60,7 +64,7 @@ class Job:
     """All device state of the benchmark: every layer's caches as one layer-major batch,
     step-major inputs, and the per-step launch sequence."""
 
-    def __init__(self, wl, n_layers, device):
+    def __init__(self, wl, n_layers, device, paper_cache=False):
         import torch
         from paper_2506_18226_amd import binding as B
         from paper_2506_18226_amd import workloads as WL
@@ -69,11 +73,19 @@ class Job:
         self.torch, self.B, self.wl, self.n_layers, self.device = torch, B, wl, n_layers, device
         P, n, h, D = wl.prefix_len, wl.n_seq, wl.n_heads, wl.head_dim
         self.n_steps_total = wl.n_image_tokens          # s = 0 .. H*W-1
-        self.layer_params = B.make_params(
-            n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w,
-            win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
-            dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=wl.score_mode,
-            cap=wl.cap(), sel_cap=wl.sel_cap())
+        self.paper_cache = paper_cache
+        if paper_cache:      # Section 4.2 as written: half-length cache, evict one when full, TopK-V ranking
+            cap = P + wl.n_image_tokens // 2
+            self.layer_params = B.make_params(
+                n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w, win_rows_back=0,
+                win_col_radius=0, dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=B.SCORE_VCOS,
+                cap=cap, sel_cap=cap, win_recent_m=2 * wl.grid_w + 1, evict_policy=B.EVICT_WHEN_FULL)
+        else:
+            self.layer_params = B.make_params(
+                n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w,
+                win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
+                dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=wl.score_mode,
+                cap=wl.cap(), sel_cap=wl.sel_cap())
         mb = self.mb = ModelBatch(self.layer_params, n_layers, device)
         self.q, self.kn, self.vn = [], [], []
         S = self.n_steps_total
@@ -123,6 +135,11 @@ class Job:
         for s in range(s_begin, s_end):
             row_end = s >= 1 and (s - 1) % W == W - 1
             cnt_s = cnt0 + s * L * n * 4
+            if self.paper_cache:
+                # evict-one-if-full for every layer, then plan, then the layers; nothing happens at row ends
+                if s >= 1:
+                    B.adsa_compact(tp, seqs0, mb.keep_map, mb.workspace, 0, stream)
+                row_end = False
             B.adsa_select(tp, seqs0, sel0, cnt_s, None, B.FLAG_PLAN_APPEND, stream)
             flags = B.FLAG_APPEND | (0 if row_end else B.FLAG_ADVANCE)
             off = s * self.row_bytes
@@ -193,7 +210,7 @@ def main():
     wl = WL.get_workload(args.workload)
     n_layers = args.layers if args.layers > 0 else wl.n_layers
     t_setup = time.perf_counter()
-    job = Job(wl, n_layers, device)
+    job = Job(wl, n_layers, device, paper_cache=args.paper_cache)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
     S = job.n_steps_total
@@ -228,7 +245,9 @@ def main():
                         f"{wl.dtype}, prefix {wl.prefix_len} + {wl.grid_h}x{wl.grid_w} grid, window R={wl.win_rows_back} "
                         f"w={wl.win_col_radius}, budget "
                         + (f"{wl.budget}" if wl.budget_den == 0 else f"{wl.budget_num}/{wl.budget_den} of context")
-                        + ", ranking=accumulated attention mass, row-end eviction",
+                        + (", ranking=accumulated attention mass, row-end eviction" if not args.paper_cache else
+                           f"; PAPER CACHE POLICY: capacity {job.layer_params.cap}, V-cosine ranking, evict one when "
+                           f"full, 1-D window of {job.layer_params.win_recent_m}, attention over everything resident"),
             "decode_steps_timed": [s0, S], "global_batch": wl.n_seq, "layers": n_layers,
             "setup_seconds": round(t_setup, 1),
         },
@@ -262,6 +281,11 @@ def main():
             "launches": int(n_launch), "avg_launch_us": 1e3 * att_ms / max(1, n_launch),
             "algorithmic_bytes_per_launch": att_bytes / max(1, n_launch),
         }
+        if args.paper_cache:       # fixed-capacity cache: resident = what the sequences hold at the end
+            n_end = [int(x) for x in job.mb.read_seqs()["n_res"]]
+            dense = (wl.prefix_len + wl.n_image_tokens) * wl.n_seq * n_layers * tau
+            result["kv_bytes_resident"] = {"max": sum(n_end) * tau, "dense_cache": dense,
+                                           "ratio_max_to_dense": sum(n_end) * tau / dense}
         # KV bytes resident: between row ends n_res grows by one per step
         if n_after:
             W = wl.grid_w

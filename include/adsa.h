@@ -68,6 +68,16 @@ typedef enum {
   ADSA_SCORE_EXT_SMALLEST = 3  /* caller-maintained score[]; keep smallest */
 } adsa_score_mode;
 
+/* When the dynamic cache evicts (Section 4.2). */
+typedef enum {
+  ADSA_EVICT_ROW_END = 0,      /* once per completed grid row: keep prefix + last R rows + top-B of the rest */
+  ADSA_EVICT_WHEN_FULL = 1     /* the paper's own rule: when n_res == cap and a token is about to be inserted,
+                                  evict the ONE last-ranked candidate (most redundant) before the insertion;
+                                  needs win_recent_m > 0 (a token that left a 1-D window is never local again).
+                                  Attention then covers everything resident (Tables 1-2: context == KV cache):
+                                  the budget fields are ignored */
+} adsa_evict_policy;
+
 /* Device-side per-sequence status bits (adsa_seq.status). */
 #define ADSA_SEQ_OK            0
 #define ADSA_SEQ_CACHE_FULL    1   /* append would exceed cap */
@@ -103,6 +113,9 @@ typedef struct adsa_params {
   int64_t kv_slot_stride;      /* elements */
   int64_t kv_head_stride;      /* elements */
   float   softmax_scale;       /* 0 => 1/sqrt(head_dim) */
+  int32_t win_recent_m;        /* > 0: the paper's own 1-D local region (Section 4.1), the m most recent image
+                                  tokens incl. the query token, instead of the 2-D window (R, w ignored) */
+  int32_t evict_policy;        /* adsa_evict_policy */
   int32_t reserved;
 } adsa_params;
 
@@ -185,6 +198,9 @@ int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void*
  * move K, V, pos and every score row to the front in place, order preserved, and set n_res, compacted.
  * Other sequences are untouched (compacted = 0, keep_map row untouched).  Like adsa_select it
  * may cover every layer's sequences in one call.  flags: ADSA_FLAG_ADVANCE.
+ * With ADSA_EVICT_WHEN_FULL the call acts instead on the sequences whose cache is full
+ * (n_res == cap, step >= 1), BEFORE the step's adsa_select: it removes the one candidate ranked
+ * last for the incoming query's partition (ties: the highest slot goes) and closes the hole.
  */
 int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map, uint32_t flags,
                  void* workspace, size_t workspace_bytes, void* stream);
@@ -195,6 +211,7 @@ int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map, uint32
  * token is appended at slot n_res (skipped when s == 0), the attended set is chosen and attended,
  * attention mass is accumulated (ATTN_MASS), sequences that closed a row are evicted+compacted,
  * and step += 1.  keep_map may be NULL only with ADSA_FLAG_NO_COMPACT.
+ * With ADSA_EVICT_WHEN_FULL the order is the paper's: evict one if full, then append/select/attend.
  */
 int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
               const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,

@@ -36,8 +36,12 @@ int orc_classify(const orc_cfg* c, int32_t n_res, const int32_t* pos, int32_t s,
     if (j > jq) return -1;                                   /* entry from the future */
     int32_t rj = j / W, cj = j % W;
     int local = 0;
-    if (rj == r) local = 1;                                  /* current row so far */
-    else if (rj >= r - R && rj <= r - 1 && abs(cj - col) <= w) local = 1;
+    if (c->win_recent_m > 0) {                               /* Section 4.1: the most recent m tokens */
+      local = j > jq - c->win_recent_m;
+    } else {
+      if (rj == r) local = 1;                                /* current row so far */
+      else if (rj >= r - R && rj <= r - 1 && abs(cj - col) <= w) local = 1;
+    }
     cls[i] = local ? ORC_LOCAL : ORC_CANDIDATE;
   }
   return 0;
@@ -177,13 +181,63 @@ int orc_accumulate(const orc_cfg* c, float* score, const int32_t* sel_idx, int32
   return 0;
 }
 
+/* stable removal of the slots with flag == 0 */
+static void move_kept(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, int32_t n,
+                      const uint8_t* flag, int32_t* keep_map, int32_t* n_out) {
+  int64_t row = (int64_t)c->n_heads * c->head_dim;
+  int32_t dst = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    if (!flag[i]) { keep_map[i] = -1; continue; }
+    keep_map[i] = dst;
+    if (dst != i) {
+      memcpy(K + (int64_t)dst * row, K + (int64_t)i * row, sizeof(float) * (size_t)row);
+      memcpy(V + (int64_t)dst * row, V + (int64_t)i * row, sizeof(float) * (size_t)row);
+      pos[dst] = pos[i];
+      score[dst] = score[i];
+    }
+    ++dst;
+  }
+  *n_out = dst;
+}
+
+int orc_evict_one(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, int32_t* n_res,
+                  int32_t s, int32_t* keep_map, int32_t* did) {
+  int32_t n = *n_res;
+  *did = 0;
+  if (s < 1 || s > c->grid_h * c->grid_w || n < c->cap) return 0;   /* not full: behave like the baseline */
+  int32_t* cls = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n + 1));
+  int32_t* cand = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n + 1));
+  uint8_t* keep = (uint8_t*)malloc((size_t)(n + 1));
+  uint8_t* flag = (uint8_t*)malloc((size_t)(n + 1));
+  if (!cls || !cand || !keep || !flag) return -1;
+  /* partition for the token about to be inserted: it will be the newest member of the local region */
+  int rc = orc_classify(c, n, pos, s, cls);
+  if (rc) return rc;
+  int32_t nc = 0;
+  for (int32_t i = 0; i < n; ++i) { flag[i] = 1; if (cls[i] == ORC_CANDIDATE) cand[nc++] = i; }
+  if (nc == 0) { free(cls); free(cand); free(keep); free(flag); return 0; }   /* nothing may go */
+  if (c->score_mode == ORC_SCORE_VCOS) {
+    double* S = (double*)malloc(sizeof(double) * (size_t)nc);
+    if (!S) return -1;
+    orc_vcos(c, V, nc, cand, S);
+    for (int32_t a = 0; a < nc; ++a) score[cand[a]] = (float)S[a];
+    free(S);
+  }
+  orc_rank_keep(nc, cand, score, keep_largest_of(c->score_mode), nc - 1, keep);   /* all but the last-ranked */
+  for (int32_t a = 0; a < nc; ++a) flag[cand[a]] = keep[a];
+  move_kept(c, K, V, pos, score, n, flag, keep_map, n_res);
+  *did = 1;
+  free(cls); free(cand); free(keep); free(flag);
+  return 0;
+}
+
 int orc_compact(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, int32_t* n_res,
                 int32_t s, int32_t* keep_map, int32_t* did) {
   int32_t W = c->grid_w, R = c->win_rows_back, P = c->grid_origin, n = *n_res;
   *did = 0;
+  if (c->evict_when_full) return orc_evict_one(c, K, V, pos, score, n_res, s, keep_map, did);
   if (s < 1 || s > c->grid_h * W || (s - 1) % W != W - 1) return 0;
   int32_t r = (s - 1) / W;
-  int64_t row = (int64_t)c->n_heads * c->head_dim;
   int32_t* rest = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n + 1));
   uint8_t* flag = (uint8_t*)malloc((size_t)(n + 1));
   uint8_t* keep = (uint8_t*)malloc((size_t)(n + 1));
@@ -209,19 +263,7 @@ int orc_compact(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score
   }
   orc_rank_keep(nr, rest, score, keep_largest_of(c->score_mode), orc_budget(c, s), keep);
   for (int32_t a = 0; a < nr; ++a) flag[rest[a]] = keep[a];
-  int32_t dst = 0;
-  for (int32_t i = 0; i < n; ++i) {
-    if (!flag[i]) { keep_map[i] = -1; continue; }
-    keep_map[i] = dst;
-    if (dst != i) {
-      memcpy(K + (int64_t)dst * row, K + (int64_t)i * row, sizeof(float) * (size_t)row);
-      memcpy(V + (int64_t)dst * row, V + (int64_t)i * row, sizeof(float) * (size_t)row);
-      pos[dst] = pos[i];
-      score[dst] = score[i];
-    }
-    ++dst;
-  }
-  *n_res = dst;
+  move_kept(c, K, V, pos, score, n, flag, keep_map, n_res);
   *did = 1;
   free(rest); free(flag); free(keep);
   return 0;
@@ -233,6 +275,11 @@ int orc_step(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, i
              int32_t* keep_map, int32_t* did_compact) {
   int64_t row = (int64_t)c->n_heads * c->head_dim;
   if (s < 0 || s > c->grid_h * c->grid_w) return -1;
+  *did_compact = 0;
+  if (c->evict_when_full) {                                  /* Section 4.2: evict BEFORE inserting */
+    int rc0 = orc_evict_one(c, K, V, pos, score, n_res, s, keep_map, did_compact);
+    if (rc0) return rc0;
+  }
   if (s >= 1) {                                              /* Section 4.2: append at the end */
     if (*n_res + 1 > c->cap) return -2;
     int32_t i = *n_res;
@@ -251,5 +298,6 @@ int orc_step(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, i
     rc = orc_accumulate(c, score, sel_idx, *sel_cnt, probs);
   free(probs);
   if (rc) return rc;
+  if (c->evict_when_full) return 0;
   return orc_compact(c, K, V, pos, score, n_res, s, keep_map, did_compact);
 }

@@ -40,6 +40,8 @@
  *    rows (every later window needs them), and the top min(B,|rest|) of the
  *    rest by the same ranking; survivors move to the front in order.
  *  - Budget B counts global tokens only; B = floor((P+s)*num/den) if den > 0.
+ *  - evict_when_full (Section 4.2 as written): requires the 1-D window (win_recent_m > 0), for which
+ *    a token that leaves the window never re-enters it, so evicting any candidate is safe.
  *
  * parity unpinned: the ATTN_MASS values themselves and the split of a context
  * length into prefix / window / budget are not in the paper; they are pinned
@@ -68,6 +70,11 @@ typedef struct {
   int32_t budget_num, budget_den;
   int32_t score_mode;
   int32_t cap;
+  int32_t win_recent_m;    /* > 0: the paper's own 1-D window, local = the m most recent image tokens
+                              (query included), instead of the 2-D neighbourhood */
+  int32_t evict_when_full; /* 1: the paper's own cache policy (Section 4.2): when the cache holds `cap`
+                              entries, evict the single most redundant candidate BEFORE inserting the
+                              new token; 0: evict once per completed grid row */
   double  softmax_scale;   /* 0 => 1/sqrt(head_dim) */
 } orc_cfg;
 
@@ -109,7 +116,15 @@ int orc_accumulate(const orc_cfg* c, float* score, const int32_t* sel_idx, int32
 int orc_compact(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, int32_t* n_res,
                 int32_t s, int32_t* keep_map, int32_t* did);
 
-/* One whole decode step (append, select, attend, accumulate, row-end compact).
+/* Section 4.2 literally: if the cache is full (n_res == cap) and a token is about to be inserted
+   (s >= 1), rank the candidates of the incoming query's partition (prefix and the m-1 most recent
+   tokens are exempt), evict the ONE ranked last (highest mean cosine; among equals the highest slot),
+   close the hole keeping the order.  keep_map as in orc_compact; *did = 1 if a token was evicted. */
+int orc_evict_one(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, int32_t* n_res,
+                  int32_t s, int32_t* keep_map, int32_t* did);
+
+/* One whole decode step (append, select, attend, accumulate, row-end compact), or with
+   evict_when_full: (evict one if full, append, select, attend, accumulate).
    Returns 0, or a negative code (-1 bad argument, -2 capacity overflow). */
 int orc_step(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, int32_t* n_res,
              int32_t s, const float* q, const float* k_new, const float* v_new,

@@ -36,6 +36,7 @@ class OracleCfg(C.Structure):
         ("grid_origin", C.c_int32), ("n_keep_prefix", C.c_int32),
         ("budget", C.c_int32), ("budget_num", C.c_int32), ("budget_den", C.c_int32),
         ("score_mode", C.c_int32), ("cap", C.c_int32),
+        ("win_recent_m", C.c_int32), ("evict_when_full", C.c_int32),
         ("softmax_scale", C.c_double),
     ]
 
@@ -206,7 +207,7 @@ def step(cfg: OracleCfg, st: CacheState, s: int, q, k_new, v_new):
                           _p(lse, C.c_double), _p(sel, C.c_int32), C.byref(cnt), _p(keep_map, C.c_int32),
                           C.byref(did))
     _chk(rc, "step")
-    n_before = st.n_res + (1 if s >= 1 else 0)
+    n_before = st.n_res if cfg.evict_when_full else st.n_res + (1 if s >= 1 else 0)
     st.n_res = n_res.value
     return {"out": out, "lse": lse, "sel_idx": sel[:cnt.value].copy(),
             "keep_map": keep_map[:n_before].copy() if did.value else None,
@@ -215,7 +216,7 @@ def step(cfg: OracleCfg, st: CacheState, s: int, q, k_new, v_new):
 
 def make_cfg(*, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, grid_origin,
              n_keep_prefix=None, budget=0, budget_num=0, budget_den=0, score_mode=0, cap=0,
-             softmax_scale=0.0) -> OracleCfg:
+             softmax_scale=0.0, win_recent_m=0, evict_when_full=0) -> OracleCfg:
     """Fill an OracleCfg; n_keep_prefix defaults to grid_origin, cap to the no-overflow bound."""
     if n_keep_prefix is None:
         n_keep_prefix = grid_origin
@@ -223,4 +224,5 @@ def make_cfg(*, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius
         bmax = budget if budget_den == 0 else ((grid_origin + grid_h * grid_w) * budget_num) // budget_den
         cap = max(grid_origin, n_keep_prefix) + bmax + (win_rows_back + 1) * grid_w
     return OracleCfg(n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, grid_origin,
-                     n_keep_prefix, budget, budget_num, budget_den, score_mode, cap, softmax_scale)
+                     n_keep_prefix, budget, budget_num, budget_den, score_mode, cap, win_recent_m,
+                     evict_when_full, softmax_scale)

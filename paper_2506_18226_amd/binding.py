@@ -19,6 +19,7 @@ SCORE_ATTN_MASS, SCORE_VCOS, SCORE_EXT_LARGEST, SCORE_EXT_SMALLEST = 0, 1, 2, 3
 FLAG_NO_COMPACT, FLAG_NO_ACCUMULATE, FLAG_PLAN_APPEND, FLAG_APPEND, FLAG_ADVANCE = 1, 2, 4, 8, 16
 SEQ_CACHE_FULL, SEQ_BAD_STATE, SEQ_SEL_OVERFLOW = 1, 2, 4
 MAX_CAP = 8192
+EVICT_ROW_END, EVICT_WHEN_FULL = 0, 1
 
 ERRORS = {0: "ADSA_OK", -1: "ADSA_ERR_NULL", -2: "ADSA_ERR_SHAPE", -3: "ADSA_ERR_DTYPE", -4: "ADSA_ERR_ALIGN",
           -5: "ADSA_ERR_CAPACITY", -6: "ADSA_ERR_WORKSPACE", -7: "ADSA_ERR_LAUNCH", -8: "ADSA_ERR_UNSUPPORTED"}
@@ -36,7 +37,8 @@ class AdsaParams(C.Structure):
         ("sel_groups", C.c_int32), ("dtype", C.c_int32), ("score_mode", C.c_int32),
         ("cap", C.c_int32), ("sel_cap", C.c_int32),
         ("kv_slot_stride", C.c_int64), ("kv_head_stride", C.c_int64),
-        ("softmax_scale", C.c_float), ("reserved", C.c_int32),
+        ("softmax_scale", C.c_float), ("win_recent_m", C.c_int32), ("evict_policy", C.c_int32),
+        ("reserved", C.c_int32),
     ]
 
 
@@ -131,7 +133,7 @@ def _check(rc: int, where: str) -> None:
 
 def make_params(*, n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, dtype,
                 score_mode, cap, sel_cap=None, sel_groups=1, layout="head_major", kv_slot_stride=None,
-                kv_head_stride=None, softmax_scale=0.0) -> AdsaParams:
+                kv_head_stride=None, softmax_scale=0.0, win_recent_m=0, evict_policy=0) -> AdsaParams:
     """Fill `adsa_params`.  layout "head_major" = [head][slot][D] (a head's rows are contiguous: the
     fast path), "slot_major" = [slot][head][D]; explicit strides override it."""
     if kv_head_stride is None:
@@ -140,7 +142,7 @@ def make_params(*, n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_
         kv_slot_stride = head_dim if layout == "head_major" else n_heads * head_dim
     return AdsaParams(n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, sel_groups,
                       dtype, score_mode, cap, cap if sel_cap is None else sel_cap,
-                      kv_slot_stride, kv_head_stride, softmax_scale, 0)
+                      kv_slot_stride, kv_head_stride, softmax_scale, win_recent_m, evict_policy, 0)
 
 
 def score_rows(params: AdsaParams) -> int:

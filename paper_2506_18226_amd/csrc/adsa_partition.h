@@ -13,14 +13,16 @@ struct QueryCell {
   int jq;             // image index of the query token (s - 1)
   int r, col;         // its grid cell
   int W, R, w;
+  int recent_m;       // > 0: 1-D window of the m most recent image tokens instead of the 2-D one
 };
 
-__device__ __forceinline__ QueryCell make_query_cell(const adsa_seq& sq, int s, int W, int R, int w) {
+__device__ __forceinline__ QueryCell make_query_cell(const adsa_seq& sq, int s, int W, int R, int w,
+                                                     int recent_m = 0) {
   QueryCell c;
   c.P = sq.grid_origin; c.n_keep_prefix = sq.n_keep_prefix; c.jq = s - 1;
   c.r = s >= 1 ? c.jq / W : 0;
   c.col = s >= 1 ? c.jq - c.r * W : 0;
-  c.W = W; c.R = R; c.w = w;
+  c.W = W; c.R = R; c.w = w; c.recent_m = recent_m;
   return c;
 }
 
@@ -31,6 +33,7 @@ __device__ __forceinline__ int select_class(const QueryCell& c, int pos) {
   if (pos < c.P) return 1;
   const int j = pos - c.P;
   if (j > c.jq) return -1;
+  if (c.recent_m > 0) return j > c.jq - c.recent_m ? 0 : 1;
   const int rj = j / c.W, cj = j - rj * c.W;
   const int dc = cj > c.col ? cj - c.col : c.col - cj;
   const bool local = (rj == c.r) || (rj >= c.r - c.R && rj < c.r && dc <= c.w);

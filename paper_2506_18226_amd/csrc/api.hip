@@ -32,6 +32,9 @@ int validate_params(const adsa_params* p) {
                           p->kv_head_stride >= (long long)p->cap * p->kv_slot_stride;
   if (!slot_major && !head_major) return ADSA_ERR_SHAPE;
   if (!(p->softmax_scale >= 0.0f)) return ADSA_ERR_SHAPE;
+  if (p->win_recent_m < 0) return ADSA_ERR_SHAPE;
+  if (p->evict_policy != ADSA_EVICT_ROW_END && p->evict_policy != ADSA_EVICT_WHEN_FULL) return ADSA_ERR_DTYPE;
+  if (p->evict_policy == ADSA_EVICT_WHEN_FULL && p->win_recent_m == 0) return ADSA_ERR_UNSUPPORTED;
   return ADSA_OK;
 }
 
@@ -122,7 +125,8 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
   if (rc) return rc;
   if (!seqs || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  if (p->score_mode == ADSA_SCORE_VCOS) {
+  // (with ADSA_EVICT_WHEN_FULL everything resident is attended: nothing to rank at selection time)
+  if (p->score_mode == ADSA_SCORE_VCOS && p->evict_policy != ADSA_EVICT_WHEN_FULL) {
     AttendPlan plan; Workspace w;
     rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
     if (rc) return rc;
@@ -188,12 +192,17 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
   char* ws = (char*)workspace;
   const bool vcos = p->score_mode == ADSA_SCORE_VCOS;
   const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS;
-  if (vcos && launch_vcos(*p, seqs, false, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  const bool streaming = p->evict_policy == ADSA_EVICT_WHEN_FULL;
+  if (streaming && compact) {          // Section 4.2 as written: make room BEFORE the insertion
+    if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+    if (launch_compact(*p, seqs, keep_map, ws, w, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  }
+  if (vcos && !streaming && launch_vcos(*p, seqs, false, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
   if (launch_select(*p, seqs, sel_idx, sel_cnt, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
   if (timed_attend(*p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, ws, w, accumulate, true,
-                   !compact, st) != hipSuccess)
+                   !compact || streaming, st) != hipSuccess)
     return ADSA_ERR_LAUNCH;
-  if (compact) {
+  if (compact && !streaming) {
     if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
     if (launch_compact(*p, seqs, keep_map, ws, w, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
   }

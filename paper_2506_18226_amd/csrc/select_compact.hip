@@ -125,7 +125,7 @@ __device__ __forceinline__ int effective_budget(const adsa_seq& q, int s) {
 struct LaunchShape {
   int n_heads, head_dim, elem_bytes;
   int grid_h, grid_w, R, w;
-  int cap, sel_cap, score_mode, score_rows;
+  int cap, sel_cap, score_mode, score_rows, recent_m, evict_policy;
   long long slot_stride_b, head_stride_b;    // bytes
 };
 
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   }
 
   // ---- Eq. 1: partition, keys into LDS
-  const QueryCell cell = make_query_cell(sq, s, L.grid_w, L.R, L.w);
+  const QueryCell cell = make_query_cell(sq, s, L.grid_w, L.R, L.w, L.recent_m);
   const bool largest = keep_largest_of(L.score_mode);
   uint32_t my_cand = 0;
   for (int i = tid; i < n; i += kSelThreads) {
@@ -198,7 +198,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   }
 
   // ---- Eq. 4: threshold of the top-B candidates
-  const uint32_t B = (uint32_t)effective_budget(sq, s);
+  // the streaming policy attends everything resident (context == cache, Tables 1-2)
+  const uint32_t B = L.evict_policy == ADSA_EVICT_WHEN_FULL ? n_cand : (uint32_t)effective_budget(sq, s);
   uint32_t T, need_eq;
   radix_threshold(sh, key, cls, n, n_cand, B < n_cand ? B : n_cand, &T, &need_eq);
 
@@ -252,7 +253,11 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   adsa_seq& sq = seqs[b];
   const int s = sq.step, n = sq.n_res, W = L.grid_w;
   const bool active = s >= 0 && sq.status == 0;
-  const bool row_end = active && is_row_end(s, L.grid_h, W) && n >= 0 && n <= L.cap;
+  // per-row policy: act when the query token closed a grid row; streaming policy (Section 4.2 as
+  // written): act when the cache is full and a token is about to be inserted
+  const bool streaming = L.evict_policy == ADSA_EVICT_WHEN_FULL;
+  const bool row_end = active && n >= 0 && n <= L.cap &&
+                       (streaming ? (s >= 1 && s <= L.grid_h * W && n == L.cap) : is_row_end(s, L.grid_h, W));
   if (!row_end) {
     if (tid == 0) {
       plan[4 * b + 0] = 0; plan[4 * b + 1] = 0; plan[4 * b + 2] = 0; plan[4 * b + 3] = n;
@@ -260,18 +265,20 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
     }
     return;
   }
-  const QueryCell cell = make_query_cell(sq, s, W, L.R, L.w);
+  const QueryCell cell = make_query_cell(sq, s, W, L.R, L.w, L.recent_m);
   const bool largest = keep_largest_of(L.score_mode);
   uint32_t my_rest = 0;
   for (int i = tid; i < n; i += kSelThreads) {
-    const int c = evict_class(cell, sq.pos[i]);
+    // streaming: the partition of the incoming query (its local region must survive)
+    const int c = streaming ? (select_class(cell, sq.pos[i]) == 1 ? 1 : 0) : evict_class(cell, sq.pos[i]);
     cls[i] = c == 1 ? kCand : kFixed;
     key[i] = order_key(rank_value(sq.score, L.score_rows, L.cap, i), largest);
     my_rest += (c == 1);
   }
   uint32_t n_rest;
   block_excl_scan(sh, my_rest, &n_rest);
-  const uint32_t B = (uint32_t)effective_budget(sq, s);
+  uint32_t B = (uint32_t)effective_budget(sq, s);
+  if (streaming) B = n_rest > 0 ? n_rest - 1 : 0;      // all candidates but the one ranked last
   uint32_t T, need_eq;
   radix_threshold(sh, key, cls, n, n_rest, B < n_rest ? B : n_rest, &T, &need_eq);
 
@@ -380,7 +387,7 @@ LaunchShape shape_of(const adsa_params& p) {
   LaunchShape L;
   L.n_heads = p.n_heads; L.head_dim = p.head_dim; L.elem_bytes = elem_bytes(p);
   L.grid_h = p.grid_h; L.grid_w = p.grid_w; L.R = p.win_rows_back; L.w = p.win_col_radius;
-  L.cap = p.cap; L.sel_cap = p.sel_cap; L.score_mode = p.score_mode; L.score_rows = score_rows(p);
+  L.cap = p.cap; L.sel_cap = p.sel_cap; L.score_mode = p.score_mode; L.score_rows = score_rows(p); L.recent_m = p.win_recent_m; L.evict_policy = p.evict_policy;
   L.slot_stride_b = (long long)p.kv_slot_stride * L.elem_bytes;
   L.head_stride_b = (long long)p.kv_head_stride * L.elem_bytes;
   return L;

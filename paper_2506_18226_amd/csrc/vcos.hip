@@ -28,7 +28,7 @@ struct VcosArgs {
   float* inv_norm;      // [n_seq][cap]
   float* u_part;        // [n_seq][n_tiles][dim]
   int n_heads, head_dim, elem_bytes, cap, n_tiles;
-  int grid_h, grid_w, R, w, for_compaction;
+  int grid_h, grid_w, R, w, for_compaction, recent_m, evict_policy;
   long long slot_stride_b, head_stride_b;
 };
 
@@ -40,13 +40,16 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 // candidate test for slot i of sequence sq (false for inactive sequences / non row-end compaction)
 __device__ __forceinline__ bool vcos_candidate(const VcosArgs& A, const QueryCell& c, int pos) {
-  return A.for_compaction ? evict_class(c, pos) == 1 : select_class(c, pos) == 1;
+  if (A.for_compaction && A.evict_policy != ADSA_EVICT_WHEN_FULL) return evict_class(c, pos) == 1;
+  return select_class(c, pos) == 1;     // also the streaming eviction: the incoming query's partition
 }
 
 __device__ __forceinline__ bool vcos_active(const VcosArgs& A, const adsa_seq& sq) {
   if (sq.step < 0 || sq.status != 0 || sq.n_res < 0 || sq.n_res > A.cap) return false;
   if (sq.step > A.grid_h * A.grid_w) return false;
-  return A.for_compaction ? is_row_end(sq.step, A.grid_h, A.grid_w) : true;
+  if (!A.for_compaction) return true;
+  if (A.evict_policy == ADSA_EVICT_WHEN_FULL) return sq.step >= 1 && sq.n_res == A.cap;
+  return is_row_end(sq.step, A.grid_h, A.grid_w);
 }
 
 // load 4 consecutive elements (column group g of the concatenated row) of slot `slot`
@@ -68,7 +71,7 @@ __global__ __launch_bounds__(kVcThreads) void k_vcos_norm_usum(VcosArgs A) {
   const int n = sq.n_res, s0 = tile * kVcTile;
   if (s0 >= n) return;
   const int s1 = min(n, s0 + kVcTile);
-  const QueryCell cell = make_query_cell(sq, sq.step, A.grid_w, A.R, A.w);
+  const QueryCell cell = make_query_cell(sq, sq.step, A.grid_w, A.R, A.w, A.recent_m);
   const char* vbase = reinterpret_cast<const char*>(sq.v);
   const int groups = A.n_heads * A.head_dim / 4;
   for (int i = s0 + wave; i < s1; i += kVcWaves) {
@@ -161,7 +164,7 @@ hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction
   A.n_heads = p.n_heads; A.head_dim = p.head_dim; A.elem_bytes = elem_bytes(p); A.cap = p.cap;
   A.n_tiles = (p.cap + kVcTile - 1) / kVcTile;
   A.grid_h = p.grid_h; A.grid_w = p.grid_w; A.R = p.win_rows_back; A.w = p.win_col_radius;
-  A.for_compaction = for_compaction ? 1 : 0;
+  A.for_compaction = for_compaction ? 1 : 0; A.recent_m = p.win_recent_m; A.evict_policy = p.evict_policy;
   A.slot_stride_b = (long long)p.kv_slot_stride * A.elem_bytes;
   A.head_stride_b = (long long)p.kv_head_stride * A.elem_bytes;
   dim3 grid(A.n_tiles, p.n_seq);

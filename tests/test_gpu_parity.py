@@ -678,3 +678,64 @@ def test_attend_on_a_maximum_length_list(layout):
     check_out(wl, to_host(batch.out)[0], ro)
     assert np.abs(batch.lse.cpu().numpy()[0] - rl).max() <= 1e-5
     assert np.allclose(batch.rank_host()[0], probs.sum(axis=0), rtol=1e-5, atol=1e-7)
+
+
+# ----------------------------------------------------------------------------- Section 4.2 as written
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("mode", [B.SCORE_VCOS, B.SCORE_ATTN_MASS])
+def test_streaming_cache_evict_one_when_full(mode, layout):
+    """The paper's own cache policy: fixed capacity, 1-D window of the m most recent tokens, dense
+    attention over everything resident, and once full the single most redundant candidate is evicted
+    before each insertion.  Teacher-forced adsa_step on oracle states before, at and after the cache
+    fills up."""
+    P, H, W, m, cap = 5, 8, 8, 6, 30
+    wl = WL.get_workload("xl", n_seq=1, n_heads=4, head_dim=64, grid_h=H, grid_w=W, prefix_len=P, score_mode=mode)
+    cfg = oracle.make_cfg(n_heads=4, head_dim=64, grid_h=H, grid_w=W, win_rows_back=0, win_col_radius=0,
+                          grid_origin=P, budget=10 ** 6, score_mode=mode, cap=cap, win_recent_m=m, evict_when_full=1)
+    steps = [0, 1, 24, 25, 26, 27, 40, 63, 64]
+    q, k, v, _, snaps = replay(wl, cfg, 0, 0, max(steps), snapshots=set(steps))
+    params = B.make_params(n_seq=len(steps), n_heads=4, head_dim=64, grid_h=H, grid_w=W, win_rows_back=0,
+                           win_col_radius=0, dtype=B.BF16, score_mode=mode, cap=cap, layout=layout,
+                           win_recent_m=m, evict_policy=B.EVICT_WHEN_FULL)
+    batch = LayerBatch(params, DEV)
+    for b, s in enumerate(steps):
+        load_state(batch, b, snaps[s], cfg, s)
+    batch.upload_seqs()
+    pp = [P + s - 1 for s in steps]
+    qd, kd, vd = (to_device(np.stack([x[p] for p in pp]), params.dtype, DEV) for x in (q, k, v))
+    batch.step(qd, kd, vd)
+    torch.cuda.synchronize()
+    seqs = batch.read_seqs()
+    out, keep_map = to_host(batch.out), batch.keep_map.cpu().numpy()
+    sel_idx, sel_cnt, posd = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy(), batch.pos.cpu().numpy()
+    Kd = batch.k_host()
+    n_evictions = 0
+    for b, s in enumerate(steps):
+        st = snaps[s].copy()
+        n_before = st.n_res
+        score_before = st.score.copy()
+        ref = oracle.step(cfg, st, s, q[pp[b]], k[pp[b]], v[pp[b]])
+        tag = f"mode={mode} s={s}"
+        assert seqs["status"][b] == 0 and seqs["step"][b] == s + 1 and seqs["n_res"][b] == st.n_res, tag
+        assert bool(seqs["compacted"][b]) == ref["compacted"], tag
+        same = True
+        if ref["compacted"]:
+            n_evictions += 1
+            g, r = keep_map[b, :n_before], ref["keep_map"]
+            assert (g < 0).sum() == 1, tag
+            if not np.array_equal(g, r):
+                same = False        # only a near tie between the two evicted candidates is acceptable
+                if mode == B.SCORE_VCOS:
+                    cls = oracle.classify(cfg, snaps[s].pos[:n_before], s)
+                    cand = np.nonzero(cls == oracle.CANDIDATE)[0]
+                    sc = np.zeros(n_before)
+                    sc[cand] = oracle.vcos(cfg, snaps[s].V, cand)
+                else:
+                    sc = score_before[:n_before].astype(np.float64)
+                assert near_tie_ok(np.nonzero(g >= 0)[0], np.nonzero(r >= 0)[0], sc, rel=1e-4, abs_tol=4e-6), tag
+        if same:
+            assert sel_cnt[b] == st.n_res and np.array_equal(sel_idx[b, :sel_cnt[b]], ref["sel_idx"]), tag
+            check_out(wl, out[b], ref["out"], tag)
+            assert np.array_equal(posd[b, :st.n_res], st.pos[:st.n_res]), tag
+            assert np.array_equal(Kd[b, :st.n_res], st.K[:st.n_res]), tag
+    assert n_evictions == 5

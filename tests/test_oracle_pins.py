@@ -433,3 +433,84 @@ def test_fractional_budget_and_overflow():
     oracle.step(small, st, 1, one, one, one)
     with pytest.raises(RuntimeError):
         oracle.step(small, st, 2, one, one, one)
+
+
+# ----------------------------------------------------------------------------- Section 4.2 as written
+def test_recent_m_window_partition_by_hand():
+    """Section 4.1: 'the most recent m tokens closest to the current step' -- m = 3, prefix n = 2
+    (positions 0, 1), 7 image tokens: written out by hand for every step."""
+    cfg = tiny_cfg(grid_h=1, grid_w=7, win_recent_m=3)
+    P, L, C = oracle.PREFIX, oracle.LOCAL, oracle.CANDIDATE
+    want = {0: [P, P], 1: [P, P, L], 2: [P, P, L, L], 3: [P, P, L, L, L], 4: [P, P, C, L, L, L],
+            5: [P, P, C, C, L, L, L], 7: [P, P, C, C, C, C, L, L, L]}
+    for s, w in want.items():
+        assert oracle.classify(cfg, np.arange(2 + s, dtype=np.int32), s).tolist() == w, s
+
+
+def test_streaming_cache_is_the_baseline_until_full_then_evicts_the_most_redundant_token():
+    """Section 4.2: 'behaves identically to the baseline when the cache is not full.  Once the cache
+    reaches its capacity, we compute pairwise token similarity using Eq. 2-3 and evict the most
+    redundant token -- the one most similar to others -- before inserting the newly generated token.'
+    Checked against torch: dense SDPA while not full; afterwards the evicted token is the argmax of
+    the mean pairwise cosine (torch) over the candidates, the cache stays exactly full, prefix and the
+    recent window are never touched, order is preserved, and attention runs over everything resident
+    (Tables 1-2: KV cache == context)."""
+    P, H, W, h, D, m, cap = 3, 5, 6, 2, 8, 4, 14
+    wl = WL.get_workload("tiny", n_heads=h, head_dim=D, grid_h=H, grid_w=W, prefix_len=P)
+    cfg = oracle.make_cfg(n_heads=h, head_dim=D, grid_h=H, grid_w=W, win_rows_back=0, win_col_radius=0,
+                          grid_origin=P, budget=10 ** 6, score_mode=WL.SCORE_VCOS, cap=cap, win_recent_m=m,
+                          evict_when_full=1)
+    q, k, v = WL.gen_tokens(wl, 0, 0)
+    st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+    evicted_ever = set()
+    for s in range(0, H * W + 1):
+        p = P + s - 1
+        before = st.copy()
+        res = oracle.step(cfg, st, s, q[p], k[p], v[p])
+        n_dense = P + s
+        if n_dense <= cap:                               # not full yet: the baseline
+            assert not res["compacted"]
+            assert res["sel_idx"].tolist() == list(range(n_dense))
+            want, _ = _sdpa(q[p], k[:n_dense], v[:n_dense])
+            assert np.allclose(res["out"], want, atol=1e-12)
+            continue
+        assert res["compacted"] and st.n_res == cap      # evict one, insert one
+        assert res["sel_idx"].tolist() == list(range(cap))           # context == cache
+        pos_b = before.pos[:before.n_res]
+        cand = [i for i, pp in enumerate(pos_b) if pp >= P and (pp - P) <= (s - 1) - m]   # neither prefix nor recent
+        vt = torch.from_numpy(before.V[cand].reshape(len(cand), -1).astype(np.float64))
+        S = torch.nn.functional.cosine_similarity(vt[:, None, :], vt[None, :, :], dim=-1)
+        S.fill_diagonal_(0.0)
+        mean = (S.sum(1) / (len(cand) - 1)).numpy()
+        worst = max(i for i in range(len(cand)) if mean[i] >= mean.max() - 1e-15)
+        km = res["keep_map"]
+        gone = np.nonzero(km < 0)[0].tolist()
+        assert gone == [cand[worst]], s
+        evicted_ever.add(int(pos_b[cand[worst]]))
+        assert st.pos[:P].tolist() == list(range(P))
+        assert st.pos[cap - 1] == p and (np.diff(st.pos[:cap]) > 0).all()
+        assert not (set(st.pos[:cap].tolist()) & evicted_ever)
+        kept = np.nonzero(km >= 0)[0]
+        assert np.array_equal(st.K[:cap - 1], before.K[kept]) and np.array_equal(st.V[:cap - 1], before.V[kept])
+        want, _ = _sdpa(q[p], st.K[:cap], st.V[:cap])
+        assert np.allclose(res["out"], want, atol=1e-12)
+
+
+def test_streaming_cache_reproduces_the_tables_cache_lengths():
+    """Tables 1-2: KV cache = context = 384 / 256 of 576 and 768 / 640 / 512 of 1024 image tokens
+    (-33.3, -55.6, -25, -37.5, -50 %).  The paper's cache 'initialises with only half the length':
+    capacity is the only knob; run the policy (tiny head size) and read the final cache length."""
+    for W, cap, pct in [(24, 384, "33.3"), (24, 256, "55.6"), (32, 768, "25.0"), (32, 640, "37.5"), (32, 512, "50.0")]:
+        cfg = oracle.make_cfg(n_heads=1, head_dim=2, grid_h=W, grid_w=W, win_rows_back=0, win_col_radius=0,
+                              grid_origin=0, n_keep_prefix=8, budget=10 ** 6, score_mode=WL.SCORE_EXT_SMALLEST,
+                              cap=cap, win_recent_m=W + 2, evict_when_full=1)
+        st = oracle.CacheState.from_prefix(cfg, np.zeros((0, 1, 2), np.float32), np.zeros((0, 1, 2), np.float32))
+        one = np.ones((1, 2), np.float32)
+        rng = np.random.default_rng(W + cap)
+        longest = 0
+        for s in range(1, W * W + 1):
+            res = oracle.step(cfg, st, s, one, one, one)
+            st.score[st.n_res - 1] = rng.random()
+            longest = max(longest, st.n_res, res["sel_idx"].size)
+        assert st.n_res == cap and longest == cap
+        assert f"{100.0 * (1 - cap / (W * W)):.1f}" == pct
