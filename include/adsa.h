@@ -105,7 +105,10 @@ typedef struct adsa_params {
   int32_t win_rows_back;       /* R: rows above the query's row that belong to the local window */
   int32_t win_col_radius;      /* w: column radius in those rows; w >= grid_w-1 gives the paper's
                                   1-D "most recent m tokens" window */
-  int32_t sel_groups;          /* 1: one attended set per sequence shared by all heads */
+  int32_t sel_groups;          /* 1: one attended set per sequence shared by all heads.  For one set PER HEAD
+                                  pass every (sequence, head) as its own adsa_seq with n_heads = 1: its K/V are
+                                  that head's rows, and q / out rows [n_seq*heads][1][D] are the same memory as
+                                  [n_seq][heads][D] */
   int32_t dtype;               /* adsa_dtype of q, K, V, out */
   int32_t score_mode;          /* adsa_score_mode */
   int32_t cap;                 /* slots allocated per sequence (<= ADSA_MAX_CAP) */
