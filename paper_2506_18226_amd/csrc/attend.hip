@@ -158,8 +158,8 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   constexpr int TT = RPW / HT;                      // tokens per wave-load
   constexpr int PF = kAttThreads >= 256 ? 4 : 1024 / kAttThreads;   // score read-modify-writes a thread starts early
   extern __shared__ float s_logit[];                // logits tile [HT][chunk_max]
-  __shared__ float s_m[kAttWaves][HT], s_l[kAttWaves][HT];
-  __shared__ float s_acc[kAttWaves][HT][LPR][EPL];
+  __shared__ float s_pm[kAttWaves * TT][HT], s_pl[kAttWaves * TT][HT];   // partial (m, l) per lane group
+  __shared__ float s_pacc[kAttWaves * TT][HT][D];                          // partial accumulators
   __shared__ float s_lse2[HT];
   __shared__ int s_ticket;
 
@@ -310,81 +310,85 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
     }
   }
 
-  // ---- merge the TT lane groups of a wave that hold the same head (lane bits above HT*LPR) ...
+  // ---- merge: every lane group of every wave leaves its partial state in LDS; after ONE barrier each
+  // thread works out, redundantly, the maxima and normalisers it needs (no second barrier), the first
+  // HT*D threads each reduce one output element, and everybody goes on to the score update.
+  constexpr int NP = kAttWaves * TT;                // partial states per head
+  {
+    const int pi = wave * TT + ts;
+    if (dl == 0) { s_pm[pi][hs] = m; s_pl[pi][hs] = l; }
 #pragma unroll
-  for (int d = HT * LPR; d < kWave; d <<= 1) {
-    const float m2 = __shfl_xor(m, d, kWave), l2 = __shfl_xor(l, d, kWave);
-    float a2[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) a2[e] = __shfl_xor(acc[e], d, kWave);
-    merge_state<EPL>(m, l, acc, m2, l2, a2);
-  }
-  // ---- ... then the four waves through LDS
-  if (ts == 0) {
-    if (dl == 0) { s_m[wave][hs] = m; s_l[wave][hs] = l; }
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) s_acc[wave][hs][dl][e] = acc[e];
+    for (int e = 0; e < EPL; ++e) s_pacc[pi][hs][dl * EPL + e] = acc[e];
   }
   __syncthreads();
-  if (wave == 0 && ts == 0) {
-    float M = -INFINITY, L = 0.0f;
+  float lse2_h[HT];                                 // log2-domain log-sum-exp of this chunk, per head
+  float M_mine = -INFINITY, L_mine = 1.0f;
+  const int o_sb = (tid / D) % HT;                 // head of the output element this thread reduces first
 #pragma unroll
-    for (int w = 0; w < kAttWaves; ++w) M = fmaxf(M, s_m[w][hs]);
-    float at[EPL];
+  for (int sb = 0; sb < HT; ++sb) {
+    float M = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) at[e] = 0.0f;
+    for (int pi = 0; pi < NP; ++pi) M = fmaxf(M, s_pm[pi][sb]);
+    float L = 0.0f;
 #pragma unroll
-    for (int w = 0; w < kAttWaves; ++w) {
-      const float mw = s_m[w][hs];
-      const float wgt = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);   // a wave without tokens
-      L = fmaf(s_l[w][hs], wgt, L);
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) at[e] = fmaf(s_acc[w][hs][dl][e], wgt, at[e]);
+    for (int pi = 0; pi < NP; ++pi) {
+      const float mp = s_pm[pi][sb];
+      L = fmaf(s_pl[pi][sb], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - M), L);   // empty partial: weight 0
     }
-    if (direct) {
-      // -------- the whole list was here: final output of this head
-      if (head_ok) {
-        const float inv = 1.0f / L;
-        const size_t oi = ((size_t)b * A.n_heads + head) * D + dl * EPL;
-        if constexpr (EB == 4) {
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(A.out) + oi) =
-              make_float4(at[0] * inv, at[1] * inv, at[2] * inv, at[3] * inv);
-        } else {
-          uint32_t pk[4];
-#pragma unroll
-          for (int e = 0; e < 8; e += 2)
-            pk[e / 2] = f32_to_bf16_rne(at[e] * inv) | (f32_to_bf16_rne(at[e + 1] * inv) << 16);
-          *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(A.out) + oi) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-        }
-        if (dl == 0) {
-          const float lse2 = M + __log2f(L);
-          A.lse[(size_t)b * A.n_heads + head] = lse2 * kLn2;
-          s_lse2[hs] = lse2;
-        }
+    lse2_h[sb] = M + __log2f(L);
+    if (sb == o_sb) { M_mine = M; L_mine = L; }
+  }
+  for (int o = tid; o < heads_here * D; o += kAttThreads) {
+    const int sb = o / D, d = o - sb * D;
+    float Mo = M_mine, Lo = L_mine;
+    if (o >= kAttThreads) {                         // second pass (HT*D > 256): redo this head's scalars
+      Mo = -INFINITY;
+      for (int pi = 0; pi < NP; ++pi) Mo = fmaxf(Mo, s_pm[pi][sb]);
+      Lo = 0.0f;
+      for (int pi = 0; pi < NP; ++pi) {
+        const float mp = s_pm[pi][sb];
+        Lo = fmaf(s_pl[pi][sb], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - Mo), Lo);
       }
-    } else if (head_ok) {
-      const size_t pidx = ((size_t)b * A.n_heads + head) * n_chunks + chunk;
-      if (dl == 0) st_dev2(A.part_ml + pidx * 2, M, L);
-      float* pa = A.part_acc + pidx * D + dl * EPL;
+    }
+    float a = 0.0f;
 #pragma unroll
-      for (int e = 0; e < EPL; e += 2) st_dev2(pa + e, at[e], at[e + 1]);
+    for (int pi = 0; pi < NP; ++pi) {
+      const float mp = s_pm[pi][sb];
+      a = fmaf(s_pacc[pi][sb][d], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - Mo), a);
+    }
+    const int hd = hg * HT + sb;
+    if (direct) {
+      const float val = a / Lo;
+      const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
+      if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
+      else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
+      if (d == 0) A.lse[(size_t)b * A.n_heads + hd] = (Mo + __log2f(Lo)) * kLn2;
+    } else {
+      const size_t pidx = ((size_t)b * A.n_heads + hd) * n_chunks + chunk;
+      st_dev(A.part_acc + pidx * D + d, a);
+      if (d == 0) st_dev2(A.part_ml + pidx * 2, Mo, Lo);
     }
   }
 
   if (direct) {
     // -------- per-head attention mass: score[head][slot] += p, from the logits still in LDS
     if (A.accumulate) {
-      __syncthreads();
 #pragma unroll
       for (int k = 0; k < PF; ++k) {                // reads were started before the loop
         const int i = tid + k * kAttThreads;
         if (i < n_pairs) {
           const int sb = i / len, j = i - sb * len;
-          score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]] =
-              pf_old[k] + fast_exp2(s_logit[sb * A.chunk_max + j] - s_lse2[sb]);
+          float lse2 = lse2_h[0];
+#pragma unroll
+          for (int x = 1; x < HT; ++x) lse2 = sb == x ? lse2_h[x] : lse2;
+          score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]] = pf_old[k] + fast_exp2(s_logit[sb * A.chunk_max + j] - lse2);
         }
       }
       if (n_pairs > PF * kAttThreads) {
+        if (tid < HT) s_lse2[tid] = lse2_h[0];      // rare long lists: hand the per-head values over through LDS
+#pragma unroll
+        for (int x = 1; x < HT; ++x) if (tid == x) s_lse2[x] = lse2_h[x];
+        __syncthreads();
         const int cm = A.chunk_max, cap = A.cap;
         add_mass(score, A.cap, hg * HT, s_lse2, n_pairs - PF * kAttThreads, [=](int i, int* sb, int* slot, float* z) {
           const int ii = i + PF * kAttThreads;
