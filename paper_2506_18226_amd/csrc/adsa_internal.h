@@ -13,11 +13,6 @@ namespace adsa {
 
 constexpr int kWave = 64;
 constexpr int kSelThreads = 256;       // select / compact-plan workgroup
-#ifndef ADSA_ATT_THREADS
-#define ADSA_ATT_THREADS 256
-#endif
-constexpr int kAttThreads = ADSA_ATT_THREADS;   // attend workgroup: its waves share one token chunk
-constexpr int kAttWaves = kAttThreads / kWave;
 constexpr int kMoveThreads = 256;
 
 // Attend launch plan: a workgroup handles (sequence, head group, token chunk).
@@ -28,6 +23,7 @@ struct AttendPlan {
   int n_head_groups;    // ceil(n_heads / heads_per_group)
   int n_chunks;         // token chunks per sequence (grid.x); every sequence splits its own count evenly
   int chunk_max;        // upper bound of tokens in one chunk, + 1
+  int waves;            // waves per attend workgroup: 4, 8 or 16
 };
 
 // Rows of adsa_seq.score: one accumulator per head for ATTN_MASS (the rank of a slot is their sum),

@@ -129,6 +129,7 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float* acc, floa
 template <typename Get>
 __device__ __forceinline__ void add_mass(float* score, int cap, int row0, const float* s_lse2, int total, Get get) {
   constexpr int B = 4;
+  const int kAttThreads = blockDim.x;
   for (int i0 = threadIdx.x; i0 < total; i0 += kAttThreads * B) {
     float* ptr[B];
     float inc[B], old[B];
@@ -150,13 +151,14 @@ __device__ __forceinline__ void add_mass(float* score, int cap, int row0, const 
   }
 }
 
-template <int EB, int D, int HT, int U>
-__global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
+template <int EB, int D, int HT, int U, int NW>
+__global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
+  constexpr int kAttThreads = NW * kWave, kAttWaves = NW;   // waves of the workgroup share one token chunk
   constexpr int EPL = Elems<EB>::N;                 // elements per lane
   constexpr int LPR = D / EPL;                      // lanes per row
   constexpr int RPW = kWave / LPR;                  // rows per wave-load
   constexpr int TT = RPW / HT;                      // tokens per wave-load
-  constexpr int PF = kAttThreads >= 256 ? 4 : 1024 / kAttThreads;   // score read-modify-writes a thread starts early
+  constexpr int PF = 1024 / kAttThreads;            // score read-modify-writes a thread starts early
   extern __shared__ float s_logit[];                // logits tile [HT][chunk_max]
   __shared__ float s_pm[kAttWaves * TT][HT], s_pl[kAttWaves * TT][HT];   // partial (m, l) per lane group
   __shared__ float s_pacc[kAttWaves * TT][HT][D];                          // partial accumulators
@@ -462,20 +464,25 @@ __global__ __launch_bounds__(kAttThreads) void k_attend(AttendArgs A) {
   if (hg == 0 && tid == 0 && A.advance) sq.step = sq.step + 1;
 }
 
-template <int EB, int D, int HT>
-hipError_t launch_attend_t(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
+template <int EB, int D, int HT, int NW>
+hipError_t launch_attend_w(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
-#ifndef ADSA_ATT_U
-#define ADSA_ATT_U 4
-#endif
-  constexpr int U = ADSA_ATT_U;
+  constexpr int U = 4;      // row pairs in flight per lane; 8 was measured slower (register pressure)
   const size_t lds = (size_t)HT * plan.chunk_max * sizeof(float);
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U>), grid, dim3(kAttThreads), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
+    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U, NW>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
   else
-    hipLaunchKernelGGL((k_attend<EB, D, HT, U>), grid, dim3(kAttThreads), lds, st, A);
+    hipLaunchKernelGGL((k_attend<EB, D, HT, U, NW>), grid, dim3(NW * kWave), lds, st, A);
   return hipGetLastError();
+}
+
+template <int EB, int D, int HT>
+hipError_t launch_attend_t(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
+                           hipEvent_t ev_start, hipEvent_t ev_stop) {
+  if (plan.waves == 16) return launch_attend_w<EB, D, HT, 16>(A, plan, n_seq, st, ev_start, ev_stop);
+  if (plan.waves == 8) return launch_attend_w<EB, D, HT, 8>(A, plan, n_seq, st, ev_start, ev_stop);
+  return launch_attend_w<EB, D, HT, 4>(A, plan, n_seq, st, ev_start, ev_stop);
 }
 
 __global__ void k_zero_words(uint32_t* p, size_t n) {
@@ -493,11 +500,14 @@ AttendPlan make_attend_plan(const adsa_params& p) {
   a.head_major = p.kv_slot_stride < p.kv_head_stride;
   a.heads_per_group = a.head_major ? 1 : rpw;
   a.n_head_groups = (p.n_heads + a.heads_per_group - 1) / a.heads_per_group;
-  // one chunk when (sequence, head group) pairs alone put >= 2 workgroups on each of the 256 CUs;
-  // else split the list until ~3 per CU, but never below 32 tokens per chunk
+  // One workgroup per (sequence, head group) whenever there are enough of them to keep ~16 MB of
+  // loads in flight chip-wide: 4 waves each from 512 pairs up, 8 or 16 waves for fewer (HBM is shared,
+  // so a CU holding two workgroups is no slower per byte).  Only tiny batches split the list, until
+  // ~768 workgroups, never below 32 tokens per chunk.
   const long long pairs = (long long)p.n_seq * a.n_head_groups;
+  a.waves = pairs >= 512 ? 4 : pairs >= 256 ? 8 : pairs >= 96 ? 16 : 4;
   int nc = 1;
-  if (pairs < 512) {
+  if (pairs < 96) {
     nc = (int)((768 + pairs - 1) / pairs);
     int max_by_len = p.sel_cap / 32;
     if (max_by_len < 1) max_by_len = 1;
