@@ -13,6 +13,9 @@ static int keep_largest_of(int mode) {
   return mode == ORC_SCORE_ATTN_MASS || mode == ORC_SCORE_EXT_LARGEST;
 }
 
+/* query heads per cache head (grouped-query attention); 0 means 1 */
+static int32_t q_per_kv(const orc_cfg* c) { return c->q_per_kv > 1 ? c->q_per_kv : 1; }
+
 int32_t orc_budget(const orc_cfg* c, int32_t s) {
   if (c->budget_den > 0) {
     int64_t L = (int64_t)c->grid_origin + s;
@@ -131,16 +134,17 @@ int orc_select(const orc_cfg* c, int32_t n_res, const int32_t* pos, float* score
 /* Eq. 5 gathers K_select, V_select; then scaled dot-product attention per head. */
 int orc_attend(const orc_cfg* c, const float* K, const float* V, const float* q,
                const int32_t* sel_idx, int32_t sel_cnt, double* out, double* lse, double* probs) {
-  int32_t h = c->n_heads, D = c->head_dim;
+  int32_t h = c->n_heads, D = c->head_dim, G = q_per_kv(c);
   double scale = c->softmax_scale != 0.0 ? c->softmax_scale : 1.0 / sqrt((double)D);
   if (sel_cnt <= 0) return -1;
   double* z = (double*)malloc(sizeof(double) * (size_t)sel_cnt);
   if (!z) return -1;
-  for (int32_t hh = 0; hh < h; ++hh) {
+  for (int32_t hh = 0; hh < h * G; ++hh) {               /* hh: query head; it reads cache head hh / G */
     const float* qh = q + (int64_t)hh * D;
+    const int32_t hk = hh / G;
     double m = -INFINITY;
     for (int32_t t = 0; t < sel_cnt; ++t) {
-      const float* kr = K + ((int64_t)sel_idx[t] * h + hh) * D;
+      const float* kr = K + ((int64_t)sel_idx[t] * h + hk) * D;
       double dot = 0.0;
       for (int32_t d = 0; d < D; ++d) dot += (double)qh[d] * (double)kr[d];
       z[t] = dot * scale;
@@ -152,7 +156,7 @@ int orc_attend(const orc_cfg* c, const float* K, const float* V, const float* q,
     for (int32_t t = 0; t < sel_cnt; ++t) {
       double p = exp(z[t] - m) / denom;
       if (probs) probs[(int64_t)hh * sel_cnt + t] = p;
-      const float* vr = V + ((int64_t)sel_idx[t] * h + hh) * D;
+      const float* vr = V + ((int64_t)sel_idx[t] * h + hk) * D;
       for (int32_t d = 0; d < D; ++d) out[(int64_t)hh * D + d] += p * (double)vr[d];
     }
     lse[hh] = m + log(denom);
@@ -175,7 +179,7 @@ int orc_accumulate(const orc_cfg* c, float* score, const int32_t* sel_idx, int32
                    const double* probs) {
   for (int32_t t = 0; t < sel_cnt; ++t) {
     double inc = 0.0;
-    for (int32_t hh = 0; hh < c->n_heads; ++hh) inc += probs[(int64_t)hh * sel_cnt + t];
+    for (int32_t hh = 0; hh < c->n_heads * q_per_kv(c); ++hh) inc += probs[(int64_t)hh * sel_cnt + t];
     score[sel_idx[t]] = (float)((double)score[sel_idx[t]] + inc);
   }
   return 0;
@@ -291,7 +295,7 @@ int orc_step(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score, i
   }
   int rc = orc_select(c, *n_res, pos, score, V, s, sel_idx, sel_cnt);
   if (rc) return rc;
-  double* probs = (double*)malloc(sizeof(double) * (size_t)c->n_heads * (size_t)(*sel_cnt + 1));
+  double* probs = (double*)malloc(sizeof(double) * (size_t)c->n_heads * (size_t)q_per_kv(c) * (size_t)(*sel_cnt + 1));
   if (!probs) return -1;
   rc = orc_attend(c, K, V, q, sel_idx, *sel_cnt, out, lse, probs);
   if (!rc && c->score_mode == ORC_SCORE_ATTN_MASS)

@@ -40,6 +40,9 @@
  *    rows (every later window needs them), and the top min(B,|rest|) of the
  *    rest by the same ranking; survivors move to the front in order.
  *  - Budget B counts global tokens only; B = floor((P+s)*num/den) if den > 0.
+ *  - Grouped-query attention (not in the paper, whose models have one query head per cache head):
+ *    the usual definition, query head j attends with cache head floor(j/G); the selection stays one
+ *    per sequence and ATTN_MASS sums the probabilities of all query heads.
  *  - evict_when_full (Section 4.2 as written): requires the 1-D window (win_recent_m > 0), for which
  *    a token that leaves the window never re-enters it, so evicting any candidate is safe.
  *
@@ -75,6 +78,8 @@ typedef struct {
   int32_t evict_when_full; /* 1: the paper's own cache policy (Section 4.2): when the cache holds `cap`
                               entries, evict the single most redundant candidate BEFORE inserting the
                               new token; 0: evict once per completed grid row */
+  int32_t q_per_kv;        /* G > 1: grouped-query attention, n_heads*G query heads, query head j reads
+                              cache head floor(j/G); 0 or 1: one query head per cache head */
   double  softmax_scale;   /* 0 => 1/sqrt(head_dim) */
 } orc_cfg;
 
@@ -98,8 +103,8 @@ int32_t orc_budget(const orc_cfg* c, int32_t s);
 int orc_select(const orc_cfg* c, int32_t n_res, const int32_t* pos, float* score, const float* V,
                int32_t s, int32_t* sel_idx, int32_t* sel_cnt);
 
-/* Eq. 5 + softmax attention over the listed slots, per head.
-   out double [h][D], lse double [h], probs double [h][sel_cnt] (may be NULL). */
+/* Eq. 5 + softmax attention over the listed slots, per query head (hq = n_heads * max(q_per_kv, 1)
+   of them; q float [hq][D]).  out double [hq][D], lse double [hq], probs double [hq][sel_cnt] (may be NULL). */
 int orc_attend(const orc_cfg* c, const float* K, const float* V, const float* q,
                const int32_t* sel_idx, int32_t sel_cnt, double* out, double* lse, double* probs);
 
@@ -107,7 +112,7 @@ int orc_attend(const orc_cfg* c, const float* K, const float* V, const float* q,
 int orc_dense(const orc_cfg* c, const float* K, const float* V, const float* q, int32_t n,
               double* out, double* lse);
 
-/* ATTN_MASS update from probs [h][sel_cnt]. */
+/* ATTN_MASS update from probs [hq][sel_cnt]: every query head's probability counts. */
 int orc_accumulate(const orc_cfg* c, float* score, const int32_t* sel_idx, int32_t sel_cnt,
                    const double* probs);
 

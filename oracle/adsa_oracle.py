@@ -36,7 +36,7 @@ class OracleCfg(C.Structure):
         ("grid_origin", C.c_int32), ("n_keep_prefix", C.c_int32),
         ("budget", C.c_int32), ("budget_num", C.c_int32), ("budget_den", C.c_int32),
         ("score_mode", C.c_int32), ("cap", C.c_int32),
-        ("win_recent_m", C.c_int32), ("evict_when_full", C.c_int32),
+        ("win_recent_m", C.c_int32), ("evict_when_full", C.c_int32), ("q_per_kv", C.c_int32),
         ("softmax_scale", C.c_double),
     ]
 
@@ -115,7 +115,7 @@ def select(cfg: OracleCfg, pos: np.ndarray, score: np.ndarray, V, s: int):
 def attend(cfg: OracleCfg, K, V, q, sel_idx, want_probs: bool = False):
     K, V, q = _f32(K), _f32(V), _f32(q)
     sel_idx = _i32(sel_idx)
-    h, D = cfg.n_heads, cfg.head_dim
+    h, D = cfg.n_heads * max(cfg.q_per_kv, 1), cfg.head_dim
     out = np.empty((h, D), dtype=np.float64)
     lse = np.empty(h, dtype=np.float64)
     probs = np.empty((h, sel_idx.size), dtype=np.float64) if want_probs else None
@@ -127,7 +127,7 @@ def attend(cfg: OracleCfg, K, V, q, sel_idx, want_probs: bool = False):
 
 def dense(cfg: OracleCfg, K, V, q, n: int):
     K, V, q = _f32(K), _f32(V), _f32(q)
-    h, D = cfg.n_heads, cfg.head_dim
+    h, D = cfg.n_heads * max(cfg.q_per_kv, 1), cfg.head_dim
     out = np.empty((h, D), dtype=np.float64)
     lse = np.empty(h, dtype=np.float64)
     _chk(_load().orc_dense(C.byref(cfg), _p(K, C.c_float), _p(V, C.c_float), _p(q, C.c_float),
@@ -193,7 +193,7 @@ def compact(cfg: OracleCfg, st: CacheState, s: int):
 def step(cfg: OracleCfg, st: CacheState, s: int, q, k_new, v_new):
     """One decode step on `st` (mutated).  Returns a dict of the step's outputs."""
     q, k_new, v_new = _f32(q), _f32(k_new), _f32(v_new)
-    h, D = cfg.n_heads, cfg.head_dim
+    h, D = cfg.n_heads * max(cfg.q_per_kv, 1), cfg.head_dim
     out = np.empty((h, D), dtype=np.float64)
     lse = np.empty(h, dtype=np.float64)
     sel = np.empty(cfg.cap + 1, dtype=np.int32)
@@ -216,7 +216,7 @@ def step(cfg: OracleCfg, st: CacheState, s: int, q, k_new, v_new):
 
 def make_cfg(*, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, grid_origin,
              n_keep_prefix=None, budget=0, budget_num=0, budget_den=0, score_mode=0, cap=0,
-             softmax_scale=0.0, win_recent_m=0, evict_when_full=0) -> OracleCfg:
+             softmax_scale=0.0, win_recent_m=0, evict_when_full=0, q_per_kv=0) -> OracleCfg:
     """Fill an OracleCfg; n_keep_prefix defaults to grid_origin, cap to the no-overflow bound."""
     if n_keep_prefix is None:
         n_keep_prefix = grid_origin
@@ -225,4 +225,4 @@ def make_cfg(*, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius
         cap = max(grid_origin, n_keep_prefix) + bmax + (win_rows_back + 1) * grid_w
     return OracleCfg(n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, grid_origin,
                      n_keep_prefix, budget, budget_num, budget_den, score_mode, cap, win_recent_m,
-                     evict_when_full, softmax_scale)
+                     evict_when_full, q_per_kv, softmax_scale)

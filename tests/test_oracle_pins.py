@@ -514,3 +514,70 @@ def test_streaming_cache_reproduces_the_tables_cache_lengths():
             longest = max(longest, st.n_res, res["sel_idx"].size)
         assert st.n_res == cap and longest == cap
         assert f"{100.0 * (1 - cap / (W * W)):.1f}" == pct
+
+
+# ----------------------------------------------------------------------------- grouped-query attention
+def test_grouped_query_attend_matches_torch_gqa_and_expanded_multi_head():
+    """Query head j reads cache head floor(j/G): identical to torch's grouped-query SDPA (a library
+    definition) and to the multi-head oracle on a cache whose heads are repeated G times."""
+    rng = np.random.default_rng(17)
+    h, G, D, n = 3, 4, 16, 50
+    cfg = tiny_cfg(n_heads=h, head_dim=D, q_per_kv=G)
+    K = rng.standard_normal((n, h, D)).astype(np.float32)
+    V = rng.standard_normal((n, h, D)).astype(np.float32)
+    q = rng.standard_normal((h * G, D)).astype(np.float32)
+    sel = np.sort(rng.choice(n, 21, replace=False)).astype(np.int32)
+    out, lse, probs = oracle.attend(cfg, K, V, q, sel, want_probs=True)
+    assert out.shape == (h * G, D) and probs.shape == (h * G, sel.size)
+    qt = torch.from_numpy(q.astype(np.float64))[None, :, None, :]                      # 1,hq,1,D
+    Kt = torch.from_numpy(K[sel].astype(np.float64)).permute(1, 0, 2)[None]            # 1,h,n,D
+    Vt = torch.from_numpy(V[sel].astype(np.float64)).permute(1, 0, 2)[None]
+    want = torch.nn.functional.scaled_dot_product_attention(qt, Kt, Vt, enable_gqa=True)[0, :, 0, :].numpy()
+    assert np.allclose(out, want, atol=1e-12)
+    # the multi-head oracle on the expanded cache (np.repeat: head j of the copy = head j // G)
+    cfg_mha = tiny_cfg(n_heads=h * G, head_dim=D)
+    out2, lse2, probs2 = oracle.attend(cfg_mha, np.repeat(K, G, axis=1), np.repeat(V, G, axis=1), q, sel,
+                                       want_probs=True)
+    assert np.array_equal(out, out2) and np.array_equal(lse, lse2) and np.array_equal(probs, probs2)
+    # the wrong mapping (j % G) is a different function: the pin would catch it
+    wrong = tiny_cfg(n_heads=h * G, head_dim=D)
+    out3, _ = oracle.attend(wrong, np.tile(K, (1, G, 1)), np.tile(V, (1, G, 1)), q, sel)
+    assert not np.allclose(out, out3, atol=1e-6)
+    # G = 0 and G = 1 are the multi-head case
+    for g1 in (0, 1):
+        c1 = tiny_cfg(n_heads=h, head_dim=D, q_per_kv=g1)
+        o1, l1 = oracle.attend(c1, K, V, q[:h], sel)
+        o0, l0 = _sdpa(q[:h], K[sel], V[sel])
+        assert np.allclose(o1, o0, atol=1e-12) and np.allclose(l1, l0, atol=1e-12)
+
+
+def test_grouped_query_mass_counts_every_query_head():
+    """ATTN_MASS under grouped queries: each step hands out exactly one unit of probability per QUERY
+    head, and a whole trajectory equals the multi-head trajectory on the expanded cache."""
+    wl = WL.get_workload("tiny")
+    G, P = 3, wl.prefix_len
+    cfg = oracle_cfg_gqa(wl, G)
+    cfg_mha = oracle_cfg_gqa(wl, 1, n_heads=wl.n_heads * G)
+    rng = np.random.default_rng(23)
+    q, k, v = WL.gen_tokens(wl, 0, 0, prefix_len=P)
+    L = k.shape[0]
+    qg = WL.round_to_bf16(rng.standard_normal((L, wl.n_heads * G, wl.head_dim)).astype(np.float32))
+    st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+    st2 = oracle.CacheState.from_prefix(cfg_mha, np.repeat(k[:P], G, axis=1), np.repeat(v[:P], G, axis=1))
+    for s in range(0, 2 * wl.grid_w + 3):
+        p = P + s - 1
+        before = st.score[:st.n_res].astype(np.float64).sum()
+        r = oracle.step(cfg, st, s, qg[p], k[p], v[p])
+        r2 = oracle.step(cfg_mha, st2, s, qg[p], np.repeat(k[p], G, axis=0), np.repeat(v[p], G, axis=0))
+        assert np.array_equal(r["sel_idx"], r2["sel_idx"]) and np.array_equal(r["out"], r2["out"])
+        assert np.array_equal(st.score[:st.n_res], st2.score[:st2.n_res]) and st.n_res == st2.n_res
+        if not r["compacted"]:
+            after = st.score[:st.n_res].astype(np.float64).sum()
+            assert abs(after - before - wl.n_heads * G) < 1e-4
+
+
+def oracle_cfg_gqa(wl, G, n_heads=None):
+    return oracle.make_cfg(
+        n_heads=wl.n_heads if n_heads is None else n_heads, head_dim=wl.head_dim, grid_h=wl.grid_h,
+        grid_w=wl.grid_w, win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
+        grid_origin=wl.prefix_len, budget=wl.budget, score_mode=WL.SCORE_ATTN_MASS, q_per_kv=G)
