@@ -99,7 +99,7 @@ typedef enum {
 /* [host] Launch-wide parameters (Section 4.1's n, m, K and the problem shape). */
 typedef struct adsa_params {
   int32_t n_seq;               /* sequences in this launch (>= 1) */
-  int32_t n_heads;             /* query heads == key/value heads */
+  int32_t n_heads;             /* key/value (cache) heads; the query has n_heads * max(q_per_kv, 1) heads */
   int32_t head_dim;            /* 64 or 128 */
   int32_t grid_h, grid_w;      /* image-token grid H x W, raster order */
   int32_t win_rows_back;       /* R: rows above the query's row that belong to the local window */
@@ -119,7 +119,10 @@ typedef struct adsa_params {
   int32_t win_recent_m;        /* > 0: the paper's own 1-D local region (Section 4.1), the m most recent image
                                   tokens incl. the query token, instead of the 2-D window (R, w ignored) */
   int32_t evict_policy;        /* adsa_evict_policy */
-  int32_t reserved;
+  int32_t q_per_kv;            /* G: query heads per cache head.  0 or 1: multi-head attention.  2..16:
+                                  grouped-query attention, query head j reads cache head floor(j/G); bf16 only,
+                                  and the logits of one list, (G + 1) * (sel_cap + 32) * 4 bytes, must fit
+                                  in about 100 KB of LDS, else ADSA_ERR_UNSUPPORTED */
 } adsa_params;
 
 /* Device array of n_seq entries: the ragged per-sequence state.  The kernels read AND update
@@ -176,14 +179,16 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
                 uint32_t flags, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Eq. 5 + attention: per sequence and head, softmax(q.K_sel^T * scale) V_sel over the slots
- * listed in sel_idx (gathered in place, never materialised), fp32 accumulation.
- *   q    dtype [n_seq][n_heads][head_dim]
- *   out  dtype [n_seq][n_heads][head_dim]
- *   lse  float [n_seq][n_heads]   natural-log sum-exp of the scaled logits
+ * Eq. 5 + attention: per sequence and query head, softmax(q.K_sel^T * scale) V_sel over the slots
+ * listed in sel_idx (gathered in place, never materialised), fp32 accumulation.  With
+ * hq = n_heads * max(q_per_kv, 1) query heads:
+ *   q    dtype [n_seq][hq][head_dim]
+ *   out  dtype [n_seq][hq][head_dim]
+ *   lse  float [n_seq][hq]   natural-log sum-exp of the scaled logits
  *   k_new, v_new  dtype [n_seq][n_heads][head_dim], only read with ADSA_FLAG_APPEND (else may be NULL)
  * For ADSA_SCORE_ATTN_MASS and unless ADSA_FLAG_NO_ACCUMULATE is set, score[slot] of every
- * attended slot gains, in row h of score[], the probability head h gave it.
+ * attended slot gains, in row h of score[], the probability the query head(s) of cache head h gave it
+ * (grouped queries: their sum in ascending head order).
  * ADSA_FLAG_APPEND (Section 4.2, new tokens go to the end of the cache): the row (k_new, v_new)
  * is written to the slot adsa_select(ADSA_FLAG_PLAN_APPEND) reserved (pending_slot >= 0), and that
  * slot is attended from k_new / v_new directly.

@@ -62,8 +62,9 @@ class LayerBatch:
             s["pending_slot"] = -1
         self.seqs = torch.zeros(n * B.SEQ_DTYPE.itemsize, dtype=torch.uint8, device=dev)
         if with_outputs:
-            self.out = torch.zeros((n, h, D), dtype=self.tdtype, device=dev)
-            self.lse = torch.zeros((n, h), dtype=torch.float32, device=dev)
+            hq = B.query_heads(p)
+            self.out = torch.zeros((n, hq, D), dtype=self.tdtype, device=dev)
+            self.lse = torch.zeros((n, hq), dtype=torch.float32, device=dev)
             self.sel_idx = torch.full((n, p.sel_cap), -1, dtype=torch.int32, device=dev)
             self.sel_cnt = torch.zeros(n, dtype=torch.int32, device=dev)
             self.keep_map = torch.full((n, cap), -3, dtype=torch.int32, device=dev)

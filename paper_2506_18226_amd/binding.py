@@ -38,7 +38,7 @@ class AdsaParams(C.Structure):
         ("cap", C.c_int32), ("sel_cap", C.c_int32),
         ("kv_slot_stride", C.c_int64), ("kv_head_stride", C.c_int64),
         ("softmax_scale", C.c_float), ("win_recent_m", C.c_int32), ("evict_policy", C.c_int32),
-        ("reserved", C.c_int32),
+        ("q_per_kv", C.c_int32),
     ]
 
 
@@ -133,7 +133,7 @@ def _check(rc: int, where: str) -> None:
 
 def make_params(*, n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, dtype,
                 score_mode, cap, sel_cap=None, sel_groups=1, layout="head_major", kv_slot_stride=None,
-                kv_head_stride=None, softmax_scale=0.0, win_recent_m=0, evict_policy=0) -> AdsaParams:
+                kv_head_stride=None, softmax_scale=0.0, win_recent_m=0, evict_policy=0, q_per_kv=0) -> AdsaParams:
     """Fill `adsa_params`.  layout "head_major" = [head][slot][D] (a head's rows are contiguous: the
     fast path), "slot_major" = [slot][head][D]; explicit strides override it."""
     if kv_head_stride is None:
@@ -142,12 +142,17 @@ def make_params(*, n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_
         kv_slot_stride = head_dim if layout == "head_major" else n_heads * head_dim
     return AdsaParams(n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, sel_groups,
                       dtype, score_mode, cap, cap if sel_cap is None else sel_cap,
-                      kv_slot_stride, kv_head_stride, softmax_scale, win_recent_m, evict_policy, 0)
+                      kv_slot_stride, kv_head_stride, softmax_scale, win_recent_m, evict_policy, q_per_kv)
 
 
 def score_rows(params: AdsaParams) -> int:
     """Rows of adsa_seq.score: one per head for ATTN_MASS, else one."""
     return params.n_heads if params.score_mode == SCORE_ATTN_MASS else 1
+
+
+def query_heads(params: AdsaParams) -> int:
+    """Heads of q / out / lse: n_heads cache heads times q_per_kv query heads each."""
+    return params.n_heads * max(params.q_per_kv, 1)
 
 
 def strerror(code: int) -> str:

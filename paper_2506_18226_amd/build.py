@@ -9,7 +9,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_DIR = os.path.join(_HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libadsa_hip.so")
-SOURCES = ["api.hip", "select_compact.hip", "attend.hip", "vcos.hip"]
+SOURCES = ["api.hip", "select_compact.hip", "attend.hip", "attend_gqa.hip", "vcos.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

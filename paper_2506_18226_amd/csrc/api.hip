@@ -35,6 +35,11 @@ int validate_params(const adsa_params* p) {
   if (p->win_recent_m < 0) return ADSA_ERR_SHAPE;
   if (p->evict_policy != ADSA_EVICT_ROW_END && p->evict_policy != ADSA_EVICT_WHEN_FULL) return ADSA_ERR_DTYPE;
   if (p->evict_policy == ADSA_EVICT_WHEN_FULL && p->win_recent_m == 0) return ADSA_ERR_UNSUPPORTED;
+  if (p->q_per_kv < 0 || p->q_per_kv > 16) return ADSA_ERR_SHAPE;
+  if (p->q_per_kv > 1) {       // grouped queries run on the bf16 matrix cores, logits of one list in LDS
+    if (p->dtype != ADSA_BF16) return ADSA_ERR_UNSUPPORTED;
+    if (gqa_lds_bytes(*p, make_attend_plan(*p).waves) > kGqaMaxLds) return ADSA_ERR_UNSUPPORTED;
+  }
   return ADSA_OK;
 }
 

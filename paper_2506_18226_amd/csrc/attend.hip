@@ -498,6 +498,15 @@ AttendPlan make_attend_plan(const adsa_params& p) {
   const int rpw = kWave / a.lanes_per_row;
   // [slot][head][D]: a wave-load takes rpw heads of one token; [head][slot][D]: rpw tokens of one head
   a.head_major = p.kv_slot_stride < p.kv_head_stride;
+  if (p.q_per_kv > 1) {      // grouped queries: one workgroup per (sequence, cache head), never split
+    a.heads_per_group = 1;
+    a.n_head_groups = p.n_heads;
+    const long long wgs = (long long)p.n_seq * p.n_heads;
+    a.waves = wgs >= 512 ? 4 : wgs >= 128 ? 8 : 16;
+    a.n_chunks = 1;
+    a.chunk_max = p.sel_cap + 1;
+    return a;
+  }
   a.heads_per_group = a.head_major ? 1 : rpw;
   a.n_head_groups = (p.n_heads + a.heads_per_group - 1) / a.heads_per_group;
   // One workgroup per (sequence, head group) whenever there are enough of them to keep ~16 MB of
@@ -561,6 +570,9 @@ hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq*
                          const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
                          void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
                          bool advance, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  if (p.q_per_kv > 1)
+    return launch_attend_gqa(p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, accumulate, append,
+                             advance, st, ev_start, ev_stop);
   AttendArgs A;
   A.seqs = seqs; A.q = (const char*)q; A.k_new = (const char*)k_new; A.v_new = (const char*)v_new;
   A.sel_idx = sel_idx; A.sel_cnt = sel_cnt; A.out = (char*)out; A.lse = lse;

@@ -51,6 +51,7 @@ class Workload:
     value_kind: str = "gauss"  # "tiny_sink" | "outlier2pct" | "lowrank8" | "gauss"
     value_scale: float = 1.0
     ragged: bool = False
+    q_per_kv: int = 1          # G: query heads per cache head (grouped-query attention when > 1)
     seed: int = field(default=0)
 
     @property
@@ -101,6 +102,11 @@ WORKLOADS: Dict[str, Workload] = {
     "ragged": _mk(4, name="ragged", n_seq=64, n_layers=1, n_heads=24, head_dim=64, dtype="bf16",
                   prefix_len=120, grid_h=32, grid_w=32, win_rows_back=1, win_col_radius=4,
                   budget=512, value_kind="gauss", ragged=True),
+    # grouped-query variant (not in the paper, whose models are multi-head): the attention shape of a
+    # 34B-class early-fusion token model, 64 query heads over 8 cache heads of 128, on the XXL image grid
+    "gqa": _mk(5, name="gqa", n_seq=32, n_layers=48, n_heads=8, head_dim=128, dtype="bf16",
+               prefix_len=120, grid_h=32, grid_w=32, win_rows_back=1, win_col_radius=4,
+               budget=512, value_kind="lowrank8", q_per_kv=8),
 }
 
 
@@ -131,7 +137,7 @@ def quantise(wl: Workload, x: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------- streams
-_PURPOSE = {"qkv": 1, "struct": 2, "state": 3, "ragged": 4, "score": 5}
+_PURPOSE = {"qkv": 1, "struct": 2, "state": 3, "ragged": 4, "score": 5, "gq": 6}
 
 
 def _rng(wl: Workload, layer: int, seq: int, purpose: str) -> np.random.Generator:
@@ -158,7 +164,9 @@ def seq_geometry(wl: Workload, seq: int) -> Tuple[int, int, int]:
 
 def gen_tokens(wl: Workload, layer: int, seq: int, prefix_len: int | None = None
                ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """q, k, v for every position of one (layer, sequence): arrays [L][h][D], float32.
+    """q, k, v for every position of one (layer, sequence): arrays [L][h][D], float32
+    (q is [L][h*G][D] for a grouped-query workload, drawn from a stream of its own with the
+    same recipe; query head j shares the low-rank basis of cache head j // G).
 
     Row p holds the post-RoPE query, key and value of the token at absolute
     position p (prefix tokens first, then image tokens in raster order).  Values
@@ -191,6 +199,15 @@ def gen_tokens(wl: Workload, layer: int, seq: int, prefix_len: int | None = None
             gs = _rng(wl, layer, seq, "struct")
             mask = gs.random(L) < 0.02
             k[mask] *= np.float32(3.0)
+    G = wl.q_per_kv
+    if G > 1:
+        gq = _rng(wl, layer, seq, "gq")
+        if kind == "lowrank8":
+            A = gq.standard_normal((L, h, G, rank), dtype=np.float32)
+            q = (np.einsum("lhgr,hdr->lhgd", A, M) / np.float32(np.sqrt(rank))).reshape(L, h * G, D)
+            q += np.float32(0.1) * gq.standard_normal((L, h * G, D), dtype=np.float32)
+        else:
+            q = gq.standard_normal((L, h * G, D), dtype=np.float32) * np.float32(wl.value_scale)
     return quantise(wl, q), quantise(wl, k), quantise(wl, v)
 
 
@@ -269,6 +286,11 @@ def gen_tokens_device(wl: Workload, layer: int, device, prefix_len: int | None =
         k = torch.einsum("nlhr,nhdr->nlhd", U, M) / rank ** 0.5 + 0.1 * randn(n, L, h, D)
         q = torch.einsum("nlhr,nhdr->nlhd", A, M) / rank ** 0.5 + 0.1 * randn(n, L, h, D)
         v = randn(n, L, h, D)
+        if wl.q_per_kv > 1:
+            G = wl.q_per_kv
+            A = randn(n, L, h, G, rank)
+            q = (torch.einsum("nlhgr,nhdr->nlhgd", A, M) / rank ** 0.5).reshape(n, L, h * G, D)
+            q = q + 0.1 * randn(n, L, h * G, D)
     else:
         q = randn(n, L, h, D) * wl.value_scale
         k = randn(n, L, h, D) * wl.value_scale
@@ -278,4 +300,6 @@ def gen_tokens_device(wl: Workload, layer: int, device, prefix_len: int | None =
         elif kind == "outlier2pct":
             mask = torch.rand(n, L, generator=g, device=device) < 0.02
             k[mask] *= 3.0
+        if wl.q_per_kv > 1:
+            q = randn(n, L, h * wl.q_per_kv, D) * wl.value_scale
     return q.to(tdt), k.to(tdt), v.to(tdt)

@@ -18,7 +18,7 @@ def oracle_cfg(wl, *, P=None, budget=None, score_mode=None, cap=0, n_keep_prefix
         n_keep_prefix=n_keep_prefix,
         budget=(wl.budget if budget is None else budget) if not use_frac else 0,
         budget_num=wl.budget_num if use_frac else 0, budget_den=wl.budget_den if use_frac else 0,
-        score_mode=wl.score_mode if score_mode is None else score_mode, cap=cap)
+        score_mode=wl.score_mode if score_mode is None else score_mode, cap=cap, q_per_kv=wl.q_per_kv)
 
 
 def replay(wl, cfg, layer, seq, stop_before, snapshots=()):

@@ -29,7 +29,7 @@ def params_for(wl, n_seq, cap, score_mode=None, sel_cap=None, layout="head_major
                          grid_w=wl.grid_w, win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
                          dtype=B.F32 if wl.dtype == "f32" else B.BF16,
                          score_mode=wl.score_mode if score_mode is None else score_mode,
-                         cap=cap, sel_cap=sel_cap, layout=layout)
+                         cap=cap, sel_cap=sel_cap, layout=layout, q_per_kv=wl.q_per_kv)
 
 
 LAYOUTS = ["head_major", "slot_major"]
