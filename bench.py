@@ -45,7 +45,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the whole trajectory)")
     ap.add_argument("--warmup", type=int, default=32, help="untimed decode steps before the timed region")
-    ap.add_argument("--workload", default="xxl", choices=["tiny", "xl", "xxl", "long"])
+    ap.add_argument("--workload", default="xxl", choices=["tiny", "xl", "xxl", "long", "gqa"])
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline-pass", action="store_true")
@@ -79,13 +79,14 @@ class Job:
             self.layer_params = B.make_params(
                 n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w, win_rows_back=0,
                 win_col_radius=0, dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=B.SCORE_VCOS,
-                cap=cap, sel_cap=cap, win_recent_m=2 * wl.grid_w + 1, evict_policy=B.EVICT_WHEN_FULL)
+                cap=cap, sel_cap=cap, win_recent_m=2 * wl.grid_w + 1, evict_policy=B.EVICT_WHEN_FULL,
+                q_per_kv=wl.q_per_kv)
         else:
             self.layer_params = B.make_params(
                 n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w,
                 win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
                 dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=wl.score_mode,
-                cap=wl.cap(), sel_cap=wl.sel_cap())
+                cap=wl.cap(), sel_cap=wl.sel_cap(), q_per_kv=wl.q_per_kv)
         mb = self.mb = ModelBatch(self.layer_params, n_layers, device)
         self.q, self.kn, self.vn = [], [], []
         S = self.n_steps_total
@@ -101,6 +102,7 @@ class Job:
         mb.pos[:, :P] = torch.arange(P, dtype=torch.int32, device=device)[None, :]
         self.sel_cnt_log = torch.zeros((S, n_layers * n), dtype=torch.int32, device=device)
         self.row_bytes = n * h * D * mb.K.element_size()
+        self.q_row_bytes = self.row_bytes * wl.q_per_kv
         self.reset()
 
     def reset(self):
@@ -131,7 +133,8 @@ class Job:
         vb = [t.data_ptr() for t in self.vn]
         cnt0 = self.sel_cnt_log.data_ptr()
         seq_sz, sel_row = B.SEQ_DTYPE.itemsize, lp.sel_cap * 4
-        out_row, lse_row = n * lp.n_heads * lp.head_dim * mb.out.element_size(), n * lp.n_heads * 4
+        hq = B.query_heads(lp)
+        out_row, lse_row = n * hq * lp.head_dim * mb.out.element_size(), n * hq * 4
         for s in range(s_begin, s_end):
             row_end = s >= 1 and (s - 1) % W == W - 1
             cnt_s = cnt0 + s * L * n * 4
@@ -142,9 +145,9 @@ class Job:
                 row_end = False
             B.adsa_select(tp, seqs0, sel0, cnt_s, None, B.FLAG_PLAN_APPEND, stream)
             flags = B.FLAG_APPEND | (0 if row_end else B.FLAG_ADVANCE)
-            off = s * self.row_bytes
+            off, q_off = s * self.row_bytes, s * self.q_row_bytes
             for l in range(L):
-                B.adsa_attend(lp, seqs0 + l * n * seq_sz, qb[l] + off, sel0 + l * n * sel_row, cnt_s + l * n * 4,
+                B.adsa_attend(lp, seqs0 + l * n * seq_sz, qb[l] + q_off, sel0 + l * n * sel_row, cnt_s + l * n * 4,
                               out0 + l * out_row, lse0 + l * lse_row, mb.layer_workspace, flags,
                               kb[l] + off, vb[l] + off, stream)
             if row_end:
@@ -162,7 +165,7 @@ def cpu_baseline(wl, n_layers, seconds):
     cfg = oracle.make_cfg(n_heads=wl.n_heads, head_dim=wl.head_dim, grid_h=wl.grid_h, grid_w=wl.grid_w,
                           win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius, grid_origin=P,
                           budget=wl.budget if wl.budget_den == 0 else 0, budget_num=wl.budget_num,
-                          budget_den=wl.budget_den, score_mode=wl.score_mode, cap=wl.cap())
+                          budget_den=wl.budget_den, score_mode=wl.score_mode, cap=wl.cap(), q_per_kv=wl.q_per_kv)
     done, spent = 0, 0.0
     seq = 0
     while spent < seconds and seq < wl.n_seq:
@@ -241,7 +244,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {
-            "workload": f"{wl.name}: {n_layers} layers x {wl.n_seq} sequences, {wl.n_heads} heads x {wl.head_dim}, "
+            "workload": f"{wl.name}: {n_layers} layers x {wl.n_seq} sequences, {wl.n_heads} heads x {wl.head_dim}"
+                        + (f" with {wl.q_per_kv} query heads each" if wl.q_per_kv > 1 else "") + f", "
                         f"{wl.dtype}, prefix {wl.prefix_len} + {wl.grid_h}x{wl.grid_w} grid, window R={wl.win_rows_back} "
                         f"w={wl.win_col_radius}, budget "
                         + (f"{wl.budget}" if wl.budget_den == 0 else f"{wl.budget_num}/{wl.budget_den} of context")
@@ -273,7 +277,7 @@ def main():
         achieved = att_bytes / (att_ms * 1e-3) / 1e9
         ratio = measured_traffic_ratio(wl.name)
         result["roofline"] = {
-            "kernel": "k_attend", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "kernel": "k_attend" if wl.q_per_kv == 1 else "k_attend_gqa", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": None if ratio is None else ratio * att_bytes / max(1, n_launch),
             "traffic_source": None if ratio is None else
@@ -281,6 +285,10 @@ def main():
             "launches": int(n_launch), "avg_launch_us": 1e3 * att_ms / max(1, n_launch),
             "algorithmic_bytes_per_launch": att_bytes / max(1, n_launch),
         }
+        if wl.q_per_kv > 1:        # the contraction runs on the matrix cores: 4 flops per (query head, token, column)
+            flops = int(cnt2[s0:S].sum()) * 4 * wl.n_heads * wl.q_per_kv * wl.head_dim
+            result["roofline"]["mfma_tflops"] = flops / (att_ms * 1e-3) / 1e12
+            result["roofline"]["mfma_frac_of_bf16_peak"] = flops / (att_ms * 1e-3) / 2.5e15
         if args.paper_cache:       # fixed-capacity cache: resident = what the sequences hold at the end
             n_end = [int(x) for x in job.mb.read_seqs()["n_res"]]
             dense = (wl.prefix_len + wl.n_image_tokens) * wl.n_seq * n_layers * tau

@@ -503,6 +503,7 @@ AttendPlan make_attend_plan(const adsa_params& p) {
     a.n_head_groups = p.n_heads;
     const long long wgs = (long long)p.n_seq * p.n_heads;
     a.waves = wgs >= 512 ? 4 : wgs >= 128 ? 8 : 16;
+    while (a.waves > 4 && gqa_lds_bytes(p, a.waves) > kGqaMaxLds) a.waves /= 2;
     a.n_chunks = 1;
     a.chunk_max = p.sel_cap + 1;
     return a;

@@ -13,6 +13,8 @@
 //            a lane loads the same D/16 columns of 4 tokens and transposes the 4 x D/16 block in
 //            registers (the contraction runs over tokens).  P is split into two bf16 halves
 //            (hi + lo) so that the product carries ~16 mantissa bits of the probabilities.
+//    Both passes are software-pipelined (the next stage's rows are in flight while the current one is
+//    multiplied) and the first V rows are requested before the barrier between the passes.
 //    The waves' partial outputs are added in wave order through LDS (deterministic), the workgroup
 //    writes out / lse for its G query heads and adds the probabilities of all G queries, summed in
 //    ascending head order, to its OWN cache head's row of score[]: no workgroup talks to another.
@@ -81,7 +83,7 @@ struct GqaArgs {
   const int32_t* sel_cnt;
   char* out;
   float* lse;
-  int n_heads, G, sel_cap, lg_stride, cap;
+  int n_heads, G, sel_cap, lg_stride, cap, stage_b;
   int accumulate, append, advance;
   long long slot_stride_b, head_stride_b;
   float scale_log2;
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   constexpr int LT = 16 / RPL;              // wave-loads per 16-token tile
   constexpr int NC = D / 16;                // 16-wide chunks of the q.k contraction
   constexpr int EV = D / 16;                // V columns a lane holds per token
-  constexpr int UT = D == 64 ? 4 : 2;       // tiles in flight per wave
+  constexpr int UT = (D == 64 ? 4 : 2) / (NW == 16 ? 2 : 1);   // tiles per pipeline stage (two stages in flight)
   constexpr int PF = (1024 / T) > 0 ? (1024 / T) : 1;
   extern __shared__ __align__(16) char smem[];
   __shared__ float s_wm[NW][16], s_wl[NW][16], s_lse2[16];
@@ -108,7 +110,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   const int G = A.G, lgs = A.lg_stride, HQ = A.n_heads * G;
   float* const s_logit = reinterpret_cast<float*>(smem);                 // [G][lgs]
   int* const s_slot = reinterpret_cast<int*>(s_logit + (size_t)G * lgs); // [lgs]
-  char* const s_stage = reinterpret_cast<char*>(s_slot + lgs);           // [NW][16][ROWB], later [G][D] floats
+  char* const s_stage = reinterpret_cast<char*>(s_slot + lgs);           // [NW][stage_b]: K tile [16][ROWB], later partial out [G][D]
 
   adsa_seq& sq = A.seqs[b];
   const int cnt = min(A.sel_cnt[b], A.sel_cap);
@@ -165,56 +167,90 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
     pf_old[k] = (A.accumulate && t < len) ? score[pf_slot[k]] : 0.0f;
   }
 
-  // ---------------- pass 1: logits
-  float m_lane = -INFINITY;
-  {
-    char* const stage = s_stage + wave * 16 * ROWB;
-    const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
-    for (int tile0 = wave * UT; tile0 < n_tiles; tile0 += NW * UT) {
-      uint4 kr[UT][LT];
+  // every wave takes an even, contiguous share of the list's 16-token tiles and walks it UT tiles at
+  // a time, the loads of the next stage in flight while the current one is multiplied
+  const int tb = (int)(((long long)n_tiles * wave) / NW), te = (int)(((long long)n_tiles * (wave + 1)) / NW);
+  const int stage_b = A.stage_b;                     // bytes of LDS each wave owns
+  char* const stage = s_stage + wave * stage_b;
+  const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
+
+  auto load_k = [&](uint4 (&buf)[UT][LT], int tile0) {
 #pragma unroll
-      for (int ut = 0; ut < UT; ++ut) {
+    for (int ut = 0; ut < UT; ++ut) {
+      if (tile0 + ut < te) {                         // wave-uniform
 #pragma unroll
         for (int u = 0; u < LT; ++u) {
-          const int t = min((tile0 + ut) * 16 + u * RPL + ld_row, padded - 1);
-          const int slot = s_slot[t];
+          const int slot = s_slot[(tile0 + ut) * 16 + u * RPL + ld_row];
           const char* p = (slot == new_slot) ? kn : k_base + (long long)slot * A.slot_stride_b;
           const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + ld_piece * 16));
-          kr[ut][u] = make_uint4(v.x, v.y, v.z, v.w);
-        }
-      }
-#pragma unroll
-      for (int ut = 0; ut < UT; ++ut) {
-        const int tile = tile0 + ut;
-        if (tile < n_tiles) {                          // wave-uniform
-          wave_lds_sync();                             // the previous tile's operand reads are issued
-#pragma unroll
-          for (int u = 0; u < LT; ++u)
-            *reinterpret_cast<uint4*>(stage + (u * RPL + ld_row) * ROWB + ld_piece * 16) = kr[ut][u];
-          wave_lds_sync();
-          const char* rowp = stage + r * ROWB + kg * (D / 2);   // token r of the tile, this lane's columns
-          f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-          for (int c2 = 0; c2 < NC / 2; ++c2) {
-            const uint4 x = *reinterpret_cast<const uint4*>(rowp + c2 * 16);
-            acc = mfma_bf16(as_bf16x4(x.x, x.y), qb[2 * c2], acc);
-            acc = mfma_bf16(as_bf16x4(x.z, x.w), qb[2 * c2 + 1], acc);
-          }
-          // acc[i] = q[g = r] . K[token tile*16 + 4*kg + i]
-          const int t0 = tile * 16 + 4 * kg;
-          float4 z;
-          z.x = (t0 + 0 < len) ? acc[0] * A.scale_log2 : -INFINITY;
-          z.y = (t0 + 1 < len) ? acc[1] * A.scale_log2 : -INFINITY;
-          z.z = (t0 + 2 < len) ? acc[2] * A.scale_log2 : -INFINITY;
-          z.w = (t0 + 3 < len) ? acc[3] * A.scale_log2 : -INFINITY;
-          if (r < G) {
-            *reinterpret_cast<float4*>(s_logit + (size_t)r * lgs + t0) = z;
-            m_lane = fmaxf(m_lane, fmaxf(fmaxf(z.x, z.y), fmaxf(z.z, z.w)));
-          }
+          buf[ut][u] = make_uint4(v.x, v.y, v.z, v.w);
         }
       }
     }
+  };
+  float m_lane = -INFINITY;
+  auto mul_k = [&](const uint4 (&buf)[UT][LT], int tile0) {
+#pragma unroll
+    for (int ut = 0; ut < UT; ++ut) {
+      const int tile = tile0 + ut;
+      if (tile < te) {
+        wave_lds_sync();                             // the previous tile's operand reads are issued
+#pragma unroll
+        for (int u = 0; u < LT; ++u)
+          *reinterpret_cast<uint4*>(stage + (u * RPL + ld_row) * ROWB + ld_piece * 16) = buf[ut][u];
+        wave_lds_sync();
+        const char* rowp = stage + r * ROWB + kg * (D / 2);   // token r of the tile, this lane's columns
+        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int c2 = 0; c2 < NC / 2; ++c2) {
+          const uint4 x = *reinterpret_cast<const uint4*>(rowp + c2 * 16);
+          acc = mfma_bf16(as_bf16x4(x.x, x.y), qb[2 * c2], acc);
+          acc = mfma_bf16(as_bf16x4(x.z, x.w), qb[2 * c2 + 1], acc);
+        }
+        // acc[i] = q[g = r] . K[token tile*16 + 4*kg + i]
+        const int t0 = tile * 16 + 4 * kg;
+        float4 z;
+        z.x = (t0 + 0 < len) ? acc[0] * A.scale_log2 : -INFINITY;
+        z.y = (t0 + 1 < len) ? acc[1] * A.scale_log2 : -INFINITY;
+        z.z = (t0 + 2 < len) ? acc[2] * A.scale_log2 : -INFINITY;
+        z.w = (t0 + 3 < len) ? acc[3] * A.scale_log2 : -INFINITY;
+        if (r < G) {
+          *reinterpret_cast<float4*>(s_logit + (size_t)r * lgs + t0) = z;
+          m_lane = fmaxf(m_lane, fmaxf(fmaxf(z.x, z.y), fmaxf(z.z, z.w)));
+        }
+      }
+    }
+  };
+  typedef uint32_t VTile[UT][4][VLoad<EV * 2>::W];
+  auto load_v = [&](VTile& buf, int tile0) {
+#pragma unroll
+    for (int ut = 0; ut < UT; ++ut) {
+      if (tile0 + ut < te) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int slot = s_slot[(tile0 + ut) * 16 + 4 * kg + i];
+          const char* p = (slot == new_slot) ? vn : v_base + (long long)slot * A.slot_stride_b;
+          VLoad<EV * 2>::load(p + r * (EV * 2), buf[ut][i]);
+        }
+      }
+    }
+  };
+
+  // ---------------- pass 1: logits
+  {
+    uint4 ka[UT][LT], kb[UT][LT];
+    if (tb < te) load_k(ka, tb);
+    for (int t0 = tb; t0 < te; t0 += 2 * UT) {
+      if (t0 + UT < te) load_k(kb, t0 + UT);
+      mul_k(ka, t0);
+      if (t0 + UT < te) {
+        if (t0 + 2 * UT < te) load_k(ka, t0 + 2 * UT);
+        mul_k(kb, t0 + UT);
+      }
+    }
   }
+  VTile va, vb;
+  if (tb < te) load_v(va, tb);                        // the first V rows travel while the maxima are merged
   m_lane = fmaxf(m_lane, __shfl_xor(m_lane, 16, kWave));
   m_lane = fmaxf(m_lane, __shfl_xor(m_lane, 32, kWave));
   if (lane < 16) s_wm[wave][lane] = m_lane;
@@ -228,80 +264,72 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
 #pragma unroll
   for (int j = 0; j < EV; ++j) acc[j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
   float l_lane = 0.0f;
-  {
-    const float* lrow = s_logit + (size_t)min(r, G - 1) * lgs + 4 * kg;
-    for (int tile0 = wave * UT; tile0 < n_tiles; tile0 += NW * UT) {
-      uint32_t vr[UT][4][VLoad<EV * 2>::W];
+  const float* const lrow = s_logit + (size_t)min(r, G - 1) * lgs + 4 * kg;
+  auto mul_v = [&](const VTile& buf, int tile0) {
 #pragma unroll
-      for (int ut = 0; ut < UT; ++ut) {
+    for (int ut = 0; ut < UT; ++ut) {
+      const int tile = tile0 + ut;
+      if (tile < te) {
+        const float4 z = *reinterpret_cast<const float4*>(lrow + tile * 16);
+        float p[4];
+        p[0] = fast_exp2(z.x - Mg); p[1] = fast_exp2(z.y - Mg);
+        p[2] = fast_exp2(z.z - Mg); p[3] = fast_exp2(z.w - Mg);
+        uint32_t hi[4], lo[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int t = min((tile0 + ut) * 16 + 4 * kg + i, padded - 1);
-          const int slot = s_slot[t];
-          const char* p = (slot == new_slot) ? vn : v_base + (long long)slot * A.slot_stride_b;
-          VLoad<EV * 2>::load(p + r * (EV * 2), vr[ut][i]);
+          if (r >= G) p[i] = 0.0f;
+          l_lane += p[i];
+          hi[i] = __float_as_uint(p[i]) & 0xFFFF0000u;
+          lo[i] = __float_as_uint(p[i] - __uint_as_float(hi[i])) >> 16;   // exact difference, truncated
+        }
+        const s16x4 a_hi = as_bf16x4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
+        const s16x4 a_lo = as_bf16x4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+#pragma unroll
+        for (int w2 = 0; w2 < VLoad<EV * 2>::W; ++w2) {
+          const uint32_t r0 = buf[ut][0][w2], r1 = buf[ut][1][w2], r2 = buf[ut][2][w2], r3 = buf[ut][3][w2];
+          // columns 2*w2 (low halves) and 2*w2+1 (high halves) of the 4 tokens
+          const s16x4 b_even = as_bf16x4((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
+          const s16x4 b_odd = as_bf16x4((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
+          acc[2 * w2] = mfma_bf16(a_hi, b_even, acc[2 * w2]);
+          acc[2 * w2] = mfma_bf16(a_lo, b_even, acc[2 * w2]);
+          acc[2 * w2 + 1] = mfma_bf16(a_hi, b_odd, acc[2 * w2 + 1]);
+          acc[2 * w2 + 1] = mfma_bf16(a_lo, b_odd, acc[2 * w2 + 1]);
         }
       }
-#pragma unroll
-      for (int ut = 0; ut < UT; ++ut) {
-        const int tile = tile0 + ut;
-        if (tile < n_tiles) {
-          const float4 z = *reinterpret_cast<const float4*>(lrow + tile * 16);
-          float p[4];
-          p[0] = fast_exp2(z.x - Mg); p[1] = fast_exp2(z.y - Mg);
-          p[2] = fast_exp2(z.z - Mg); p[3] = fast_exp2(z.w - Mg);
-          uint32_t hi[4], lo[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            if (r >= G) p[i] = 0.0f;
-            l_lane += p[i];
-            hi[i] = __float_as_uint(p[i]) & 0xFFFF0000u;
-            lo[i] = __float_as_uint(p[i] - __uint_as_float(hi[i])) >> 16;   // exact difference, truncated
-          }
-          const s16x4 a_hi = as_bf16x4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
-          const s16x4 a_lo = as_bf16x4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
-#pragma unroll
-          for (int w2 = 0; w2 < VLoad<EV * 2>::W; ++w2) {
-            const uint32_t r0 = vr[ut][0][w2], r1 = vr[ut][1][w2], r2 = vr[ut][2][w2], r3 = vr[ut][3][w2];
-            // columns 2*w2 (low halves) and 2*w2+1 (high halves) of the 4 tokens
-            const s16x4 b_even = as_bf16x4((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
-            const s16x4 b_odd = as_bf16x4((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
-            acc[2 * w2] = mfma_bf16(a_hi, b_even, acc[2 * w2]);
-            acc[2 * w2] = mfma_bf16(a_lo, b_even, acc[2 * w2]);
-            acc[2 * w2 + 1] = mfma_bf16(a_hi, b_odd, acc[2 * w2 + 1]);
-            acc[2 * w2 + 1] = mfma_bf16(a_lo, b_odd, acc[2 * w2 + 1]);
-          }
-        }
-      }
+    }
+  };
+  for (int t0 = tb; t0 < te; t0 += 2 * UT) {
+    if (t0 + UT < te) load_v(vb, t0 + UT);
+    mul_v(va, t0);
+    if (t0 + UT < te) {
+      if (t0 + 2 * UT < te) load_v(va, t0 + 2 * UT);
+      mul_v(vb, t0 + UT);
     }
   }
   l_lane += __shfl_xor(l_lane, 16, kWave);
   l_lane += __shfl_xor(l_lane, 32, kWave);
   if (lane < 16) s_wl[wave][lane] = l_lane;
 
-  // acc[j][i] = partial out[g = 4*kg + i][d = EV*r + j]: add the waves' partials in wave order
-  float* const s_part = reinterpret_cast<float*>(s_stage);
-#pragma unroll 1
-  for (int w = 0; w < NW; ++w) {
-    if (wave == w) {
+  // acc[j][i] = this wave's partial out[g = 4*kg + i][d = EV*r + j]: one slab per wave, summed in wave order below
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int g = 4 * kg + i;
-        if (g < G) {
-          float* dst = s_part + (size_t)g * D + EV * r;
+  for (int i = 0; i < 4; ++i) {
+    const int g = 4 * kg + i;
+    if (g < G) {
+      float* dst = reinterpret_cast<float*>(s_stage + wave * stage_b) + (size_t)g * D + EV * r;
 #pragma unroll
-          for (int j = 0; j < EV; ++j) dst[j] = (w == 0 ? 0.0f : dst[j]) + acc[j][i];
-        }
-      }
+      for (int j = 0; j < EV; ++j) dst[j] = acc[j][i];
     }
-    __syncthreads();
   }
+  __syncthreads();
   for (int o = tid; o < G * D; o += T) {
     const int g = o / D, d = o - g * D;
     float L = 0.0f, M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < NW; ++w) { L += s_wl[w][g]; M = fmaxf(M, s_wm[w][g]); }
-    out[o] = (uint16_t)f32_to_bf16_rne(s_part[o] / L);
+    float a = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) a += reinterpret_cast<const float*>(s_stage + w * stage_b)[o];
+    out[o] = (uint16_t)f32_to_bf16_rne(a / L);
     if (d == 0) {
       const float lse2 = M + __log2f(L);
       lse[g] = lse2 * kLn2;
@@ -361,11 +389,15 @@ hipError_t launch_gqa_d(const GqaArgs& A, int waves, int n_seq, size_t lds, hipS
 
 int gqa_logit_stride(const adsa_params& p) { return (p.sel_cap + 15) / 16 * 16 + 16; }
 
+// LDS each wave owns: a staged K tile [16][D*2+16 bytes], reused for its partial output [G][D] floats
+static size_t gqa_stage_bytes(const adsa_params& p) {
+  const size_t tile = (size_t)16 * (p.head_dim * 2 + 16), part = (size_t)p.q_per_kv * p.head_dim * sizeof(float);
+  return tile > part ? tile : part;
+}
+
 size_t gqa_lds_bytes(const adsa_params& p, int waves) {
   const size_t lgs = (size_t)gqa_logit_stride(p);
-  const size_t stage = (size_t)waves * 16 * (p.head_dim * 2 + 16);
-  const size_t part = (size_t)16 * p.head_dim * sizeof(float);
-  return ((size_t)p.q_per_kv + 1) * lgs * sizeof(float) + (stage > part ? stage : part);
+  return ((size_t)p.q_per_kv + 1) * lgs * sizeof(float) + (size_t)waves * gqa_stage_bytes(p);
 }
 
 hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
@@ -377,7 +409,7 @@ hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_
   A.seqs = seqs; A.q = (const char*)q; A.k_new = (const char*)k_new; A.v_new = (const char*)v_new;
   A.sel_idx = sel_idx; A.sel_cnt = sel_cnt; A.out = (char*)out; A.lse = lse;
   A.n_heads = p.n_heads; A.G = p.q_per_kv; A.sel_cap = p.sel_cap; A.lg_stride = gqa_logit_stride(p);
-  A.cap = p.cap;
+  A.cap = p.cap; A.stage_b = (int)gqa_stage_bytes(p);
   A.accumulate = accumulate ? 1 : 0; A.append = append ? 1 : 0; A.advance = advance ? 1 : 0;
   A.slot_stride_b = (long long)p.kv_slot_stride * 2;
   A.head_stride_b = (long long)p.kv_head_stride * 2;
