@@ -502,7 +502,7 @@ AttendPlan make_attend_plan(const adsa_params& p) {
     a.heads_per_group = 1;
     a.n_head_groups = p.n_heads;
     const long long wgs = (long long)p.n_seq * p.n_heads;
-    a.waves = wgs >= 512 ? 4 : wgs >= 128 ? 8 : 16;
+    a.waves = wgs >= 512 ? 4 : 8;
     while (a.waves > 4 && gqa_lds_bytes(p, a.waves) > kGqaMaxLds) a.waves /= 2;
     a.n_chunks = 1;
     a.chunk_max = p.sel_cap + 1;

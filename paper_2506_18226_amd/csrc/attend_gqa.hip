@@ -3,21 +3,26 @@
 // meets G queries, so the two products are small dense contractions and run on the matrix cores
 // (v_mfma_f32_16x16x16_bf16, fp32 accumulation); the kernel is still bound by the HBM stream.
 //
-//  k_attend_gqa<D, NW> : grid (cache head, sequence), NW waves.  Two passes over the list:
-//    pass 1  S[t][g] = K[t] . q[g]   per 16-token tile: rows are fetched with coalesced 16-byte
-//            loads, staged through a wave-private LDS tile (the MFMA operand layout wants lane%16 =
-//            token, a global load in that shape would touch 16 rows per quarter wave), multiplied
-//            with the G (<= 16) query rows held in registers, scaled to log2 units and kept in LDS
-//            as the logits [G][list]; per-query maxima are merged over lanes and waves.
-//    pass 2  out[g][:] = sum_t 2^(S - max) V[t]   V rows come straight from HBM in operand layout:
-//            a lane loads the same D/16 columns of 4 tokens and transposes the 4 x D/16 block in
-//            registers (the contraction runs over tokens).  P is split into two bf16 halves
-//            (hi + lo) so that the product carries ~16 mantissa bits of the probabilities.
-//    Both passes are software-pipelined (the next stage's rows are in flight while the current one is
-//    multiplied) and the first V rows are requested before the barrier between the passes.
-//    The waves' partial outputs are added in wave order through LDS (deterministic), the workgroup
-//    writes out / lse for its G query heads and adds the probabilities of all G queries, summed in
-//    ascending head order, to its OWN cache head's row of score[]: no workgroup talks to another.
+//  k_attend_gqa<D, NW> : grid (cache head, sequence), NW waves.  The list is cut into 16-token tiles;
+//  the waves of a workgroup take tiles from a shared LDS counter (the memory system serves waves
+//  unevenly, a fixed split leaves the slow ones as a tail) and each runs its own online softmax:
+//    S[t][g] = K[t] . q[g]   K rows are fetched with coalesced 16-byte loads and staged through a
+//            wave-private LDS tile (the MFMA operand layout wants lane%16 = token; a global load in
+//            that shape would touch 16 rows per quarter wave), then multiplied with the G (<= 16)
+//            query rows held in registers.  The product comes out with lane%16 = query and 4
+//            consecutive tokens per lane: exactly the operand layout of the next product, so the
+//            probabilities never leave the registers.  The scaled logits (log2 units) are also kept
+//            in LDS, [G][list], for the score update.
+//    out[g][:] += 2^(S - m[g]) V[t]   V rows come straight from HBM in operand layout: a lane loads the
+//            same D/16 columns of 4 tokens and transposes the 4 x D/16 block in registers (the
+//            contraction runs over tokens).  P is split into two bf16 halves (hi + lo) so that the
+//            product carries ~16 mantissa bits of the probabilities.  When a query's running maximum
+//            m[g] grows, the accumulators are rescaled (factors fetched across lanes).
+//    K and V of the next tiles are in flight while the current ones are multiplied.
+//    At the end the waves' (m, l, partial out) are merged through LDS in wave order (deterministic
+//    for a given tile assignment), the workgroup writes out / lse for its G query heads and adds the
+//    probabilities of all G queries, summed in ascending head order, to its OWN cache head's row of
+//    score[]: no workgroup talks to another.
 #include <hip/hip_ext.h>
 
 #include "adsa_internal.h"
@@ -98,10 +103,11 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   constexpr int LT = 16 / RPL;              // wave-loads per 16-token tile
   constexpr int NC = D / 16;                // 16-wide chunks of the q.k contraction
   constexpr int EV = D / 16;                // V columns a lane holds per token
-  constexpr int UT = (D == 64 ? 4 : 2) / (NW == 16 ? 2 : 1);   // tiles per pipeline stage (two stages in flight)
-  constexpr int PF = (1024 / T) > 0 ? (1024 / T) : 1;
+  constexpr int UT = D == 64 ? 2 : 1;       // 16-token tiles per pipeline stage (two stages in flight)
+  constexpr int VW = VLoad<EV * 2>::W;      // dwords of V a lane loads per token
   extern __shared__ __align__(16) char smem[];
   __shared__ float s_wm[NW][16], s_wl[NW][16], s_lse2[16];
+  __shared__ int s_next;                    // next unclaimed pipeline stage of the list
 
   const int hk = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -112,8 +118,10 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   int* const s_slot = reinterpret_cast<int*>(s_logit + (size_t)G * lgs); // [lgs]
   char* const s_stage = reinterpret_cast<char*>(s_slot + lgs);           // [NW][stage_b]: K tile [16][ROWB], later partial out [G][D]
 
+  // One round trip brings everything the first K loads depend on: the sequence record, the count, q,
+  // and the whole slot list (its address and extent do not depend on the count).
   adsa_seq& sq = A.seqs[b];
-  const int cnt = min(A.sel_cnt[b], A.sel_cap);
+  const int cnt_raw = A.sel_cnt[b];
   char* const k_base = reinterpret_cast<char*>(sq.k) + (long long)hk * A.head_stride_b;
   char* const v_base = reinterpret_cast<char*>(sq.v) + (long long)hk * A.head_stride_b;
   float* const score = sq.score + (size_t)hk * A.cap;
@@ -121,23 +129,10 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
   uint16_t* const out = reinterpret_cast<uint16_t*>(A.out) + ((size_t)b * HQ + (size_t)hk * G) * D;
   float* const lse = A.lse + (size_t)b * HQ + (size_t)hk * G;
-
-  if (cnt <= 0) {                                    // inactive or rejected sequence: zero-filled rows
-    for (int o = tid; o < G * D; o += T) {
-      out[o] = 0;
-      if (o % D == 0) lse[o / D] = 0.0f;
-    }
-    return;
-  }
-  const int len = cnt;
-  const int n_tiles = (len + 15) / 16, padded = n_tiles * 16;
-  const int new_slot = (A.append && pending >= 0 && pending < A.cap) ? pending : -1;
-  const char* const kn = A.k_new + ((size_t)b * A.n_heads + hk) * D * 2;
-  const char* const vn = A.v_new + ((size_t)b * A.n_heads + hk) * D * 2;
-
-  // slots of the list, clamped into the cache; the ragged tail repeats the last token's slot
-  for (int t = tid; t < padded; t += T) s_slot[t] = min(max(idx[min(t, len - 1)], 0), A.cap - 1);
-
+  // slots of the list, clamped into the cache (entries past the count are never used: readers clamp
+  // their list position to the last token)
+  for (int t = tid; t < A.sel_cap; t += T) s_slot[t] = min(max(idx[t], 0), A.cap - 1);
+  if (tid == 0) s_next = 0;
   // q as the B operand of pass 1: lane (g = r, kg) holds columns [D/4*kg, D/4*(kg+1)) of query g
   s16x4 qb[NC];
   {
@@ -150,143 +145,112 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
       qb[2 * c2 + 1] = as_bf16x4(x.z, x.w);
     }
   }
-  if (new_slot >= 0 && tid < D / 8) {                // Section 4.2 append: this cache head's rows of the new token
-    const long long off = (long long)new_slot * A.slot_stride_b + tid * 16;
-    *reinterpret_cast<uint4*>(k_base + off) = *reinterpret_cast<const uint4*>(kn + tid * 16);
-    *reinterpret_cast<uint4*>(v_base + off) = *reinterpret_cast<const uint4*>(vn + tid * 16);
+  const int cnt = min(cnt_raw, A.sel_cap);
+  if (cnt <= 0) {                                    // inactive or rejected sequence: zero-filled rows
+    for (int o = tid; o < G * D; o += T) {
+      out[o] = 0;
+      if (o % D == 0) lse[o / D] = 0.0f;
+    }
+    return;
   }
+  const int len = cnt;
+  const int n_tiles = (len + 15) / 16;
+  const int new_slot = (A.append && pending >= 0 && pending < A.cap) ? pending : -1;
+  const char* const kn = A.k_new + ((size_t)b * A.n_heads + hk) * D * 2;
+  const char* const vn = A.v_new + ((size_t)b * A.n_heads + hk) * D * 2;
   __syncthreads();
 
-  // the first PF score words this thread will update at the end: start the reads now
-  int pf_slot[PF];
-  float pf_old[PF];
-#pragma unroll
-  for (int k = 0; k < PF; ++k) {
-    const int t = tid + k * T;
-    pf_slot[k] = s_slot[min(t, padded - 1)];
-    pf_old[k] = (A.accumulate && t < len) ? score[pf_slot[k]] : 0.0f;
-  }
-
-  // every wave takes an even, contiguous share of the list's 16-token tiles and walks it UT tiles at
-  // a time, the loads of the next stage in flight while the current one is multiplied
-  const int tb = (int)(((long long)n_tiles * wave) / NW), te = (int)(((long long)n_tiles * (wave + 1)) / NW);
   const int stage_b = A.stage_b;                     // bytes of LDS each wave owns
   char* const stage = s_stage + wave * stage_b;
   const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
+  struct Stage { uint4 k[UT][LT]; uint32_t v[UT][4][VW]; };
 
-  auto load_k = [&](uint4 (&buf)[UT][LT], int tile0) {
+  auto grab = [&]() -> int {                         // claim the next stage (UT tiles) of the list
+    int v = 0;
+    if (lane == 0) v = atomicAdd(&s_next, 1);
+    return __builtin_amdgcn_readfirstlane(v);
+  };
+  auto load = [&](Stage& st, int sid) {
 #pragma unroll
     for (int ut = 0; ut < UT; ++ut) {
-      if (tile0 + ut < te) {                         // wave-uniform
+      const int tile = sid * UT + ut;
+      if (tile < n_tiles) {                          // wave-uniform
 #pragma unroll
         for (int u = 0; u < LT; ++u) {
-          const int slot = s_slot[(tile0 + ut) * 16 + u * RPL + ld_row];
+          const int slot = s_slot[min(tile * 16 + u * RPL + ld_row, len - 1)];
           const char* p = (slot == new_slot) ? kn : k_base + (long long)slot * A.slot_stride_b;
           const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + ld_piece * 16));
-          buf[ut][u] = make_uint4(v.x, v.y, v.z, v.w);
+          st.k[ut][u] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int slot = s_slot[min(tile * 16 + 4 * kg + i, len - 1)];
+          const char* p = (slot == new_slot) ? vn : v_base + (long long)slot * A.slot_stride_b;
+          VLoad<EV * 2>::load(p + r * (EV * 2), st.v[ut][i]);
         }
       }
     }
   };
-  float m_lane = -INFINITY;
-  auto mul_k = [&](const uint4 (&buf)[UT][LT], int tile0) {
+
+  float m_run = -INFINITY, l_lane = 0.0f;            // online softmax of query g = r (l: this lane's tokens only)
+  f32x4 acc[EV];                                     // acc[j][i] = partial out[g = 4*kg + i][d = EV*r + j]
+#pragma unroll
+  for (int j = 0; j < EV; ++j) acc[j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+  auto mul = [&](const Stage& st, int sid) {
 #pragma unroll
     for (int ut = 0; ut < UT; ++ut) {
-      const int tile = tile0 + ut;
-      if (tile < te) {
+      const int tile = sid * UT + ut;
+      if (tile < n_tiles) {
         wave_lds_sync();                             // the previous tile's operand reads are issued
 #pragma unroll
         for (int u = 0; u < LT; ++u)
-          *reinterpret_cast<uint4*>(stage + (u * RPL + ld_row) * ROWB + ld_piece * 16) = buf[ut][u];
+          *reinterpret_cast<uint4*>(stage + (u * RPL + ld_row) * ROWB + ld_piece * 16) = st.k[ut][u];
         wave_lds_sync();
         const char* rowp = stage + r * ROWB + kg * (D / 2);   // token r of the tile, this lane's columns
-        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int c2 = 0; c2 < NC / 2; ++c2) {
           const uint4 x = *reinterpret_cast<const uint4*>(rowp + c2 * 16);
-          acc = mfma_bf16(as_bf16x4(x.x, x.y), qb[2 * c2], acc);
-          acc = mfma_bf16(as_bf16x4(x.z, x.w), qb[2 * c2 + 1], acc);
+          s4 = mfma_bf16(as_bf16x4(x.x, x.y), qb[2 * c2], s4);
+          s4 = mfma_bf16(as_bf16x4(x.z, x.w), qb[2 * c2 + 1], s4);
         }
-        // acc[i] = q[g = r] . K[token tile*16 + 4*kg + i]
+        // s4[i] = q[g = r] . K[token tile*16 + 4*kg + i]
         const int t0 = tile * 16 + 4 * kg;
-        float4 z;
-        z.x = (t0 + 0 < len) ? acc[0] * A.scale_log2 : -INFINITY;
-        z.y = (t0 + 1 < len) ? acc[1] * A.scale_log2 : -INFINITY;
-        z.z = (t0 + 2 < len) ? acc[2] * A.scale_log2 : -INFINITY;
-        z.w = (t0 + 3 < len) ? acc[3] * A.scale_log2 : -INFINITY;
-        if (r < G) {
-          *reinterpret_cast<float4*>(s_logit + (size_t)r * lgs + t0) = z;
-          m_lane = fmaxf(m_lane, fmaxf(fmaxf(z.x, z.y), fmaxf(z.z, z.w)));
+        float z[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) z[i] = (t0 + i < len) ? s4[i] * A.scale_log2 : -INFINITY;
+        if (A.accumulate && r < G)
+          *reinterpret_cast<float4*>(s_logit + (size_t)r * lgs + t0) = make_float4(z[0], z[1], z[2], z[3]);
+        float tm = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+        tm = fmaxf(tm, __shfl_xor(tm, 16, kWave));
+        tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));   // maximum of query r over the tile (its first token is valid)
+        const float m_new = fmaxf(m_run, tm);
+        if (__any(m_new > m_run)) {                  // some query's maximum grew: rescale what was summed so far
+          const float c = fast_exp2(m_run - m_new);  // 0 for the first tile
+          l_lane *= c;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float ci = __shfl(c, 4 * kg + i, kWave);   // factor of query 4*kg + i
+#pragma unroll
+            for (int j = 0; j < EV; ++j) acc[j][i] *= ci;
+          }
+          m_run = m_new;
         }
-      }
-    }
-  };
-  typedef uint32_t VTile[UT][4][VLoad<EV * 2>::W];
-  auto load_v = [&](VTile& buf, int tile0) {
-#pragma unroll
-    for (int ut = 0; ut < UT; ++ut) {
-      if (tile0 + ut < te) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int slot = s_slot[(tile0 + ut) * 16 + 4 * kg + i];
-          const char* p = (slot == new_slot) ? vn : v_base + (long long)slot * A.slot_stride_b;
-          VLoad<EV * 2>::load(p + r * (EV * 2), buf[ut][i]);
-        }
-      }
-    }
-  };
-
-  // ---------------- pass 1: logits
-  {
-    uint4 ka[UT][LT], kb[UT][LT];
-    if (tb < te) load_k(ka, tb);
-    for (int t0 = tb; t0 < te; t0 += 2 * UT) {
-      if (t0 + UT < te) load_k(kb, t0 + UT);
-      mul_k(ka, t0);
-      if (t0 + UT < te) {
-        if (t0 + 2 * UT < te) load_k(ka, t0 + 2 * UT);
-        mul_k(kb, t0 + UT);
-      }
-    }
-  }
-  VTile va, vb;
-  if (tb < te) load_v(va, tb);                        // the first V rows travel while the maxima are merged
-  m_lane = fmaxf(m_lane, __shfl_xor(m_lane, 16, kWave));
-  m_lane = fmaxf(m_lane, __shfl_xor(m_lane, 32, kWave));
-  if (lane < 16) s_wm[wave][lane] = m_lane;
-  __syncthreads();
-
-  // ---------------- pass 2: probabilities x V
-  float Mg = -INFINITY;                               // maximum of query g = r
-#pragma unroll
-  for (int w = 0; w < NW; ++w) Mg = fmaxf(Mg, s_wm[w][r]);
-  f32x4 acc[EV];
-#pragma unroll
-  for (int j = 0; j < EV; ++j) acc[j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-  float l_lane = 0.0f;
-  const float* const lrow = s_logit + (size_t)min(r, G - 1) * lgs + 4 * kg;
-  auto mul_v = [&](const VTile& buf, int tile0) {
-#pragma unroll
-    for (int ut = 0; ut < UT; ++ut) {
-      const int tile = tile0 + ut;
-      if (tile < te) {
-        const float4 z = *reinterpret_cast<const float4*>(lrow + tile * 16);
-        float p[4];
-        p[0] = fast_exp2(z.x - Mg); p[1] = fast_exp2(z.y - Mg);
-        p[2] = fast_exp2(z.z - Mg); p[3] = fast_exp2(z.w - Mg);
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          if (r >= G) p[i] = 0.0f;
-          l_lane += p[i];
-          hi[i] = __float_as_uint(p[i]) & 0xFFFF0000u;
-          lo[i] = __float_as_uint(p[i] - __uint_as_float(hi[i])) >> 16;   // exact difference, truncated
+          float p = fast_exp2(z[i] - m_run);
+          if (r >= G) p = 0.0f;
+          l_lane += p;
+          hi[i] = __float_as_uint(p) & 0xFFFF0000u;
+          lo[i] = __float_as_uint(p - __uint_as_float(hi[i])) >> 16;     // exact difference, truncated
         }
         const s16x4 a_hi = as_bf16x4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
         const s16x4 a_lo = as_bf16x4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
 #pragma unroll
-        for (int w2 = 0; w2 < VLoad<EV * 2>::W; ++w2) {
-          const uint32_t r0 = buf[ut][0][w2], r1 = buf[ut][1][w2], r2 = buf[ut][2][w2], r3 = buf[ut][3][w2];
+        for (int w2 = 0; w2 < VW; ++w2) {
+          const uint32_t r0 = st.v[ut][0][w2], r1 = st.v[ut][1][w2], r2 = st.v[ut][2][w2], r3 = st.v[ut][3][w2];
           // columns 2*w2 (low halves) and 2*w2+1 (high halves) of the 4 tokens
           const s16x4 b_even = as_bf16x4((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
           const s16x4 b_odd = as_bf16x4((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
@@ -298,19 +262,27 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
       }
     }
   };
-  for (int t0 = tb; t0 < te; t0 += 2 * UT) {
-    if (t0 + UT < te) load_v(vb, t0 + UT);
-    mul_v(va, t0);
-    if (t0 + UT < te) {
-      if (t0 + 2 * UT < te) load_v(va, t0 + 2 * UT);
-      mul_v(vb, t0 + UT);
+
+  {
+    Stage sa, sb;
+    int ia = grab(), ib = grab();
+    load(sa, ia);
+    load(sb, ib);
+    // stage numbers are handed out in ascending order: once one is past the list, so are all later ones
+    while (ia * UT < n_tiles) {
+      mul(sa, ia);
+      ia = grab();
+      load(sa, ia);
+      if (ib * UT >= n_tiles) break;
+      mul(sb, ib);
+      ib = grab();
+      load(sb, ib);
     }
   }
   l_lane += __shfl_xor(l_lane, 16, kWave);
   l_lane += __shfl_xor(l_lane, 32, kWave);
-  if (lane < 16) s_wl[wave][lane] = l_lane;
-
-  // acc[j][i] = this wave's partial out[g = 4*kg + i][d = EV*r + j]: one slab per wave, summed in wave order below
+  if (lane < 16) { s_wm[wave][lane] = m_run; s_wl[wave][lane] = l_lane; }
+  // one slab of partial outputs per wave, merged below with the waves' softmax weights
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int g = 4 * kg + i;
@@ -321,39 +293,47 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
     }
   }
   __syncthreads();
+  // Softmax weights of the waves, per query: s_wm[w][g] becomes wave w's weight 2^(m_w - M).  No global
+  // store has been issued so far, so the two barriers here wait for LDS traffic only; every store of
+  // the kernel follows the last barrier and is acknowledged once, at the end.
+  if (tid < 16) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, s_wm[w][tid]);
+    float L = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float mw = s_wm[w][tid];
+      const float wgt = (mw == -INFINITY) ? 0.0f : fast_exp2(mw - M);      // a wave that saw no tile: weight 0
+      L = fmaf(s_wl[w][tid], wgt, L);
+      s_wm[w][tid] = wgt;
+    }
+    s_lse2[tid] = M + __log2f(L);
+    s_wl[0][tid] = 1.0f / L;
+  }
+  __syncthreads();
   for (int o = tid; o < G * D; o += T) {
     const int g = o / D, d = o - g * D;
-    float L = 0.0f, M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) { L += s_wl[w][g]; M = fmaxf(M, s_wm[w][g]); }
     float a = 0.0f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) a += reinterpret_cast<const float*>(s_stage + w * stage_b)[o];
-    out[o] = (uint16_t)f32_to_bf16_rne(a / L);
-    if (d == 0) {
-      const float lse2 = M + __log2f(L);
-      lse[g] = lse2 * kLn2;
-      s_lse2[g] = lse2;
-    }
+    for (int w = 0; w < NW; ++w) a = fmaf(reinterpret_cast<const float*>(s_stage + w * stage_b)[o], s_wm[w][g], a);
+    out[o] = (uint16_t)f32_to_bf16_rne(a * s_wl[0][g]);
+    if (d == 0) lse[g] = s_lse2[g] * kLn2;
+  }
+  if (new_slot >= 0 && tid < D / 8) {                // Section 4.2 append: this cache head's rows of the new token
+    const long long off = (long long)new_slot * A.slot_stride_b + tid * 16;
+    *reinterpret_cast<uint4*>(k_base + off) = *reinterpret_cast<const uint4*>(kn + tid * 16);
+    *reinterpret_cast<uint4*>(v_base + off) = *reinterpret_cast<const uint4*>(vn + tid * 16);
   }
 
   // ---------------- attention mass of this cache head: sum over its G queries, ascending
+  // Each (cache head, slot) word is touched by exactly one thread of one workgroup per launch, so a
+  // no-return hardware add gives the same fp32 sum as a load + store, without waiting for the load.
   if (A.accumulate) {
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < PF; ++k) {
-      const int t = tid + k * T;
-      if (t < len) {
-        float inc = 0.0f;
-        for (int g = 0; g < G; ++g) inc += fast_exp2(s_logit[(size_t)g * lgs + t] - s_lse2[g]);
-        score[pf_slot[k]] = pf_old[k] + inc;
-      }
-    }
-    for (int t = tid + PF * T; t < len; t += T) {
+    for (int t = tid; t < len; t += T) {
       float inc = 0.0f;
       for (int g = 0; g < G; ++g) inc += fast_exp2(s_logit[(size_t)g * lgs + t] - s_lse2[g]);
-      float* sp = score + s_slot[t];
-      *sp = *sp + inc;
+      unsafeAtomicAdd(score + s_slot[t], inc);
     }
   }
   if (hk == 0 && tid == 0 && A.advance) sq.step = sq.step + 1;     // no other workgroup reads step
@@ -380,7 +360,6 @@ hipError_t launch_gqa_w(const GqaArgs& A, int n_seq, size_t lds, hipStream_t st,
 template <int D>
 hipError_t launch_gqa_d(const GqaArgs& A, int waves, int n_seq, size_t lds, hipStream_t st, hipEvent_t e0,
                         hipEvent_t e1) {
-  if (waves == 16) return launch_gqa_w<D, 16>(A, n_seq, lds, st, e0, e1);
   if (waves == 8) return launch_gqa_w<D, 8>(A, n_seq, lds, st, e0, e1);
   return launch_gqa_w<D, 4>(A, n_seq, lds, st, e0, e1);
 }
