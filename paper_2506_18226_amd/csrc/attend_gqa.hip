@@ -342,7 +342,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
 template <int D, int NW>
 hipError_t launch_gqa_w(const GqaArgs& A, int n_seq, size_t lds, hipStream_t st, hipEvent_t ev_start,
                         hipEvent_t ev_stop) {
-  static size_t lds_allowed = 48 * 1024;       // raise the per-launch LDS limit once per kernel and size
+  static size_t lds_allowed = 64 * 1024;       // above the default limit: raise it once per kernel and size
   if (lds > lds_allowed) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<D, NW>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
