@@ -65,6 +65,7 @@ def test_workspace_size_is_positive_and_monotone(lib):
     (dict(kv_slot_stride=64), -2), (dict(softmax_scale=-1.0), -2),
     (dict(score_mode=B.SCORE_VCOS, n_heads=128, head_dim=128), -8),
     (dict(win_recent_m=-1), -2), (dict(evict_policy=5), -3), (dict(evict_policy=B.EVICT_WHEN_FULL), -8),
+    (dict(q_per_kv=-1), -2), (dict(q_per_kv=17), -2), (dict(q_per_kv=4, dtype=B.F32), -8),
 ])
 def test_bad_parameters_are_rejected_before_any_launch(lib, kw, code):
     p = good(**kw)
@@ -75,6 +76,16 @@ def test_bad_parameters_are_rejected_before_any_launch(lib, kw, code):
     rc = lib.adsa_step(C.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None)
     assert rc == code
     assert len(B.strerror(rc)) > 3
+
+
+def test_grouped_query_parameters(lib):
+    """q_per_kv 0 and 1 are the multi-head case; 2..16 need bf16 and a list whose logits fit in LDS."""
+    assert B.adsa_workspace_bytes(good(q_per_kv=0)) == B.adsa_workspace_bytes(good(q_per_kv=1)) > 0
+    assert B.adsa_workspace_bytes(good(q_per_kv=8, dtype=B.BF16)) > 0
+    assert B.query_heads(good(q_per_kv=8, dtype=B.BF16)) == 8 * good().n_heads
+    big = dict(dtype=B.BF16, cap=B.MAX_CAP, sel_cap=B.MAX_CAP, kv_slot_stride=None, kv_head_stride=None)
+    assert B.adsa_workspace_bytes(good(q_per_kv=2, **big)) > 0            # 3 x 8.2k x 4 B of logits: fits
+    assert B.adsa_workspace_bytes(good(q_per_kv=16, **big)) == 0          # 17 x 8.2k x 4 B: does not
 
 
 def test_null_alignment_and_workspace_errors(lib):
