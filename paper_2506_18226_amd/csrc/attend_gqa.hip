@@ -3,9 +3,10 @@
 // meets G queries, so the two products are small dense contractions and run on the matrix cores
 // (v_mfma_f32_16x16x16_bf16, fp32 accumulation); the kernel is still bound by the HBM stream.
 //
-//  k_attend_gqa<D, NW> : grid (cache head, sequence), NW waves.  The list is cut into 16-token tiles;
-//  the waves of a workgroup take tiles from a shared LDS counter (the memory system serves waves
-//  unevenly, a fixed split leaves the slow ones as a tail) and each runs its own online softmax:
+//  k_attend_gqa<D, NW> : grid (cache head, sequence), NW waves.  The list is cut into 16-token tiles,
+//  dealt round-robin to the waves of the workgroup (a fixed assignment: results are reproducible bit
+//  for bit; claiming tiles from a counter was measured no faster), and each wave runs its own online
+//  softmax:
 //    S[t][g] = K[t] . q[g]   K rows are fetched with coalesced 16-byte loads and staged through a
 //            wave-private LDS tile (the MFMA operand layout wants lane%16 = token; a global load in
 //            that shape would touch 16 rows per quarter wave), then multiplied with the G (<= 16)
@@ -19,8 +20,7 @@
 //            product carries ~16 mantissa bits of the probabilities.  When a query's running maximum
 //            m[g] grows, the accumulators are rescaled (factors fetched across lanes).
 //    K and V of the next tiles are in flight while the current ones are multiplied.
-//    At the end the waves' (m, l, partial out) are merged through LDS in wave order (deterministic
-//    for a given tile assignment), the workgroup writes out / lse for its G query heads and adds the
+//    At the end the waves' (m, l, partial out) are merged through LDS in wave order, the workgroup writes out / lse for its G query heads and adds the
 //    probabilities of all G queries, summed in ascending head order, to its OWN cache head's row of
 //    score[]: no workgroup talks to another.
 #include <hip/hip_ext.h>
@@ -107,7 +107,6 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   constexpr int VW = VLoad<EV * 2>::W;      // dwords of V a lane loads per token
   extern __shared__ __align__(16) char smem[];
   __shared__ float s_wm[NW][16], s_wl[NW][16], s_lse2[16];
-  __shared__ int s_next;                    // next unclaimed pipeline stage of the list
 
   const int hk = blockIdx.x, b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -132,7 +131,6 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   // slots of the list, clamped into the cache (entries past the count are never used: readers clamp
   // their list position to the last token)
   for (int t = tid; t < A.sel_cap; t += T) s_slot[t] = min(max(idx[t], 0), A.cap - 1);
-  if (tid == 0) s_next = 0;
   // q as the B operand of pass 1: lane (g = r, kg) holds columns [D/4*kg, D/4*(kg+1)) of query g
   s16x4 qb[NC];
   {
@@ -165,11 +163,6 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
   struct Stage { uint4 k[UT][LT]; uint32_t v[UT][4][VW]; };
 
-  auto grab = [&]() -> int {                         // claim the next stage (UT tiles) of the list
-    int v = 0;
-    if (lane == 0) v = atomicAdd(&s_next, 1);
-    return __builtin_amdgcn_readfirstlane(v);
-  };
   auto load = [&](Stage& st, int sid) {
 #pragma unroll
     for (int ut = 0; ut < UT; ++ut) {
@@ -265,17 +258,17 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
 
   {
     Stage sa, sb;
-    int ia = grab(), ib = grab();
+    // wave w takes stages w, w + NW, ...: a fixed assignment, so results are reproducible bit for bit
+    int ia = wave, ib = wave + NW;
     load(sa, ia);
     load(sb, ib);
-    // stage numbers are handed out in ascending order: once one is past the list, so are all later ones
     while (ia * UT < n_tiles) {
       mul(sa, ia);
-      ia = grab();
+      ia += 2 * NW;
       load(sa, ia);
       if (ib * UT >= n_tiles) break;
       mul(sb, ib);
-      ib = grab();
+      ib += 2 * NW;
       load(sb, ib);
     }
   }

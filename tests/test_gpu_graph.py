@@ -1,0 +1,85 @@
+"""A whole decode step captured once as a HIP graph and replayed for every step.
+
+Every decision that depends on the sequences' state (row end or not, what to evict, where the new
+token goes) is taken on the device, and the entry points only enqueue kernels (no allocation, no
+synchronisation, no memset node), so ONE captured adsa_step serves all steps of a trajectory: the
+caller refreshes q / k_new / v_new in place and replays.  Each replay is checked, bit for bit, against
+the same step run eagerly on a twin batch; the eager path itself is checked against the oracle in
+test_gpu_parity and test_gpu_gqa.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2506_18226_amd import binding as B
+from paper_2506_18226_amd import workloads as WL
+from paper_2506_18226_amd.batch import LayerBatch, to_device, to_host
+
+from common import oracle_cfg
+from test_gpu_parity import DEV, params_for, load_state, check_out
+
+pytestmark = pytest.mark.gpu
+
+
+def _twin_batches(wl, cfg, n_seq):
+    batches = []
+    toks = [WL.gen_tokens(wl, 0, b, prefix_len=cfg.grid_origin) for b in range(n_seq)]
+    for _ in range(3):
+        batch = LayerBatch(params_for(wl, n_seq, cfg.cap), DEV)
+        for b in range(n_seq):
+            q, k, v = toks[b]
+            st = oracle.CacheState.from_prefix(cfg, k[:cfg.grid_origin], v[:cfg.grid_origin])
+            load_state(batch, b, st, cfg, 0)
+        batch.upload_seqs()
+        batches.append(batch)
+    return batches, toks
+
+
+@pytest.mark.parametrize("over", [
+    dict(n_heads=4, head_dim=64, grid_h=5, grid_w=8, prefix_len=5, dtype="bf16"),
+    dict(n_heads=2, head_dim=128, grid_h=4, grid_w=8, prefix_len=7, dtype="bf16", q_per_kv=4),
+    dict(n_heads=3, head_dim=64, grid_h=4, grid_w=6, prefix_len=4, dtype="f32", score_mode=WL.SCORE_VCOS),
+])
+def test_one_captured_step_replayed_over_a_trajectory(over):
+    wl = WL.get_workload("tiny", n_seq=3, win_rows_back=1, win_col_radius=1, budget=6, value_kind="gauss",
+                         value_scale=0.5, **over)
+    cfg = oracle_cfg(wl)
+    n, P, S = wl.n_seq, cfg.grid_origin, wl.n_image_tokens
+    (eager, graphed, warm), toks = _twin_batches(wl, cfg, n)
+    qs, ks, vs = (np.stack([t[i] for t in toks], axis=1) for i in range(3))        # [L][n][heads][D]
+    qd, kd, vd = (to_device(x, eager.params.dtype, DEV) for x in (qs, ks, vs))
+    q_in, k_in, v_in = (torch.zeros_like(x[0]) for x in (qd, kd, vd))              # fixed addresses for the graph
+
+    # warm-up launch of every kernel outside the capture (first-use set-up of a kernel is not capturable work)
+    warm.step(qd[P - 1], kd[P - 1], vd[P - 1])
+    torch.cuda.synchronize()
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graphed.step(q_in, k_in, v_in)
+    torch.cuda.synchronize()
+    assert (graphed.read_seqs()["step"] == 0).all()                                  # capturing ran nothing
+
+    for s in range(S + 1):
+        p = P + s - 1
+        q_in.copy_(qd[p]); k_in.copy_(kd[p]); v_in.copy_(vd[p])
+        g.replay()
+        eager.step(qd[p], kd[p], vd[p])
+        torch.cuda.synchronize()
+        a, b = eager.read_seqs(), graphed.read_seqs()
+        tag = f"s={s}"
+        for f in ("n_res", "step", "status", "compacted", "pending_slot"):
+            assert np.array_equal(a[f], b[f]), (tag, f)
+        assert (a["status"] == 0).all() and (a["step"] == s + 1).all(), tag
+        assert torch.equal(eager.sel_cnt, graphed.sel_cnt), tag
+        for b_ in range(n):
+            c = int(eager.sel_cnt[b_])
+            assert torch.equal(eager.sel_idx[b_, :c], graphed.sel_idx[b_, :c]), tag
+        assert torch.equal(eager.out, graphed.out) and torch.equal(eager.lse, graphed.lse), tag
+        assert torch.equal(eager.K, graphed.K) and torch.equal(eager.V, graphed.V), tag
+        assert torch.equal(eager.pos, graphed.pos) and torch.equal(eager.score, graphed.score), tag
+    out = to_host(graphed.out)
+    assert np.isfinite(out).all()
+    final = graphed.read_seqs()
+    assert (final["n_res"] <= cfg.cap).all() and (final["step"] == S + 1).all()
