@@ -53,7 +53,7 @@ def parse_args():
     ap.add_argument("--paper-cache", action="store_true",
                     help="run the paper's own cache policy instead of the headline one: capacity = prefix + half the "
                          "image tokens, V-cosine ranking (Eq. 2-3), evict one when full, 1-D window, dense attention "
-                         "over everything resident (Section 4.2, Tables 1-2)")
+                         "over everything resident (Section 4.2, Tables 1-2); the incoming token takes the evicted slot")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (1 GiB read + 1 GiB written, 4 times): the "
                          "reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -79,7 +79,7 @@ class Job:
             self.layer_params = B.make_params(
                 n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w, win_rows_back=0,
                 win_col_radius=0, dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=B.SCORE_VCOS,
-                cap=cap, sel_cap=cap, win_recent_m=2 * wl.grid_w + 1, evict_policy=B.EVICT_WHEN_FULL,
+                cap=cap, sel_cap=cap, win_recent_m=2 * wl.grid_w + 1, evict_policy=B.EVICT_REUSE_SLOT,
                 q_per_kv=wl.q_per_kv)
         else:
             self.layer_params = B.make_params(
@@ -110,7 +110,7 @@ class Job:
         for s in mb.seqs_host:
             s["n_res"], s["step"], s["grid_origin"], s["n_keep_prefix"] = P, 0, P, P
             s["budget"], s["budget_num"], s["budget_den"] = wl.budget, wl.budget_num, wl.budget_den
-            s["status"], s["compacted"], s["pending_slot"] = 0, 0, -1
+            s["status"], s["compacted"], s["pending_slot"], s["hole"] = 0, 0, -1, 0
         mb.upload_seqs()
         mb.score.zero_()
         self.sel_cnt_log.zero_()
@@ -251,7 +251,8 @@ def main():
                         + (f"{wl.budget}" if wl.budget_den == 0 else f"{wl.budget_num}/{wl.budget_den} of context")
                         + (", ranking=accumulated attention mass, row-end eviction" if not args.paper_cache else
                            f"; PAPER CACHE POLICY: capacity {job.layer_params.cap}, V-cosine ranking, evict one when "
-                           f"full, 1-D window of {job.layer_params.win_recent_m}, attention over everything resident"),
+                           f"full (the incoming token takes its slot), 1-D window of {job.layer_params.win_recent_m}, "
+                           f"attention over everything resident"),
             "decode_steps_timed": [s0, S], "global_batch": wl.n_seq, "layers": n_layers,
             "setup_seconds": round(t_setup, 1),
         },

@@ -71,11 +71,16 @@ typedef enum {
 /* When the dynamic cache evicts (Section 4.2). */
 typedef enum {
   ADSA_EVICT_ROW_END = 0,      /* once per completed grid row: keep prefix + last R rows + top-B of the rest */
-  ADSA_EVICT_WHEN_FULL = 1     /* the paper's own rule: when n_res == cap and a token is about to be inserted,
+  ADSA_EVICT_WHEN_FULL = 1,    /* the paper's own rule: when n_res == cap and a token is about to be inserted,
                                   evict the ONE last-ranked candidate (most redundant) before the insertion;
                                   needs win_recent_m > 0 (a token that left a 1-D window is never local again).
                                   Attention then covers everything resident (Tables 1-2: context == KV cache):
-                                  the budget fields are ignored */
+                                  the budget fields are ignored.  The hole is closed: slots stay in position
+                                  order, at the price of moving every row behind the hole */
+  ADSA_EVICT_REUSE_SLOT = 2    /* the same rule and the same evicted token (among equal scores the newest
+                                  position goes), but nothing moves: the evicted slot is recorded in
+                                  adsa_seq.hole and the incoming token takes it.  From the first eviction on,
+                                  slot order is no longer position order (pos[] says who lives where) */
 } adsa_evict_policy;
 
 /* Device-side per-sequence status bits (adsa_seq.status). */
@@ -146,7 +151,10 @@ typedef struct adsa_seq {
   int32_t  compacted;          /* 1 if the last adsa_step/adsa_compact evicted+compacted this sequence */
   int32_t  pending_slot;       /* slot adsa_select(PLAN_APPEND) reserved for the query token, whose K/V rows
                                   the next adsa_attend(APPEND) fills; -1 if none.  Written by adsa_select */
-  int32_t  reserved[2];
+  int32_t  hole;               /* ADSA_EVICT_REUSE_SLOT: 1 + the slot the last eviction freed, 0 if none (start
+                                  with 0).  A freed slot still counts in n_res but is in no list; the next
+                                  adsa_select(PLAN_APPEND) gives it to the query token and clears hole */
+  int32_t  reserved;
 } adsa_seq;
 
 /* Bytes of device scratch the entry points need for these parameters (0 if they are invalid). */
@@ -206,7 +214,7 @@ int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void*
  * move K, V, pos and every score row to the front in place, order preserved, and set n_res, compacted.
  * Other sequences are untouched (compacted = 0, keep_map row untouched).  Like adsa_select it
  * may cover every layer's sequences in one call.  flags: ADSA_FLAG_ADVANCE.
- * With ADSA_EVICT_WHEN_FULL the call acts instead on the sequences whose cache is full
+ * With ADSA_EVICT_WHEN_FULL / ADSA_EVICT_REUSE_SLOT the call acts instead on the sequences whose cache is full
  * (n_res == cap, step >= 1), BEFORE the step's adsa_select: it removes the one candidate ranked
  * last for the incoming query's partition (ties: the highest slot goes) and closes the hole.
  */
@@ -219,7 +227,8 @@ int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map, uint32
  * token is appended at slot n_res (skipped when s == 0), the attended set is chosen and attended,
  * attention mass is accumulated (ATTN_MASS), sequences that closed a row are evicted+compacted,
  * and step += 1.  keep_map may be NULL only with ADSA_FLAG_NO_COMPACT.
- * With ADSA_EVICT_WHEN_FULL the order is the paper's: evict one if full, then append/select/attend.
+ * With ADSA_EVICT_WHEN_FULL / ADSA_EVICT_REUSE_SLOT the order is the paper's: evict one if full, then
+ * append/select/attend.
  */
 int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
               const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,

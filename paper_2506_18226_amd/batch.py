@@ -105,7 +105,7 @@ class LayerBatch:
         s["n_res"], s["step"], s["grid_origin"] = n, step, grid_origin
         s["n_keep_prefix"] = grid_origin if n_keep_prefix is None else n_keep_prefix
         s["budget"], s["budget_num"], s["budget_den"] = budget, budget_num, budget_den
-        s["status"], s["compacted"], s["pending_slot"] = 0, 0, -1
+        s["status"], s["compacted"], s["pending_slot"], s["hole"] = 0, 0, -1, 0
 
     # ---- device -> host, layout-independent views
     def k_host(self) -> np.ndarray:

@@ -19,7 +19,7 @@ SCORE_ATTN_MASS, SCORE_VCOS, SCORE_EXT_LARGEST, SCORE_EXT_SMALLEST = 0, 1, 2, 3
 FLAG_NO_COMPACT, FLAG_NO_ACCUMULATE, FLAG_PLAN_APPEND, FLAG_APPEND, FLAG_ADVANCE = 1, 2, 4, 8, 16
 SEQ_CACHE_FULL, SEQ_BAD_STATE, SEQ_SEL_OVERFLOW = 1, 2, 4
 MAX_CAP = 8192
-EVICT_ROW_END, EVICT_WHEN_FULL = 0, 1
+EVICT_ROW_END, EVICT_WHEN_FULL, EVICT_REUSE_SLOT = 0, 1, 2
 
 ERRORS = {0: "ADSA_OK", -1: "ADSA_ERR_NULL", -2: "ADSA_ERR_SHAPE", -3: "ADSA_ERR_DTYPE", -4: "ADSA_ERR_ALIGN",
           -5: "ADSA_ERR_CAPACITY", -6: "ADSA_ERR_WORKSPACE", -7: "ADSA_ERR_LAUNCH", -8: "ADSA_ERR_UNSUPPORTED"}
@@ -47,7 +47,7 @@ SEQ_DTYPE = np.dtype([
     ("k", np.uint64), ("v", np.uint64), ("pos", np.uint64), ("score", np.uint64),
     ("n_res", np.int32), ("step", np.int32), ("grid_origin", np.int32), ("n_keep_prefix", np.int32),
     ("budget", np.int32), ("budget_num", np.int32), ("budget_den", np.int32), ("status", np.int32),
-    ("compacted", np.int32), ("pending_slot", np.int32), ("reserved", np.int32, (2,)),
+    ("compacted", np.int32), ("pending_slot", np.int32), ("hole", np.int32), ("reserved", np.int32),
 ])
 assert SEQ_DTYPE.itemsize == 80
 

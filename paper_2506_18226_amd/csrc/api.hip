@@ -33,8 +33,8 @@ int validate_params(const adsa_params* p) {
   if (!slot_major && !head_major) return ADSA_ERR_SHAPE;
   if (!(p->softmax_scale >= 0.0f)) return ADSA_ERR_SHAPE;
   if (p->win_recent_m < 0) return ADSA_ERR_SHAPE;
-  if (p->evict_policy != ADSA_EVICT_ROW_END && p->evict_policy != ADSA_EVICT_WHEN_FULL) return ADSA_ERR_DTYPE;
-  if (p->evict_policy == ADSA_EVICT_WHEN_FULL && p->win_recent_m == 0) return ADSA_ERR_UNSUPPORTED;
+  if (p->evict_policy < ADSA_EVICT_ROW_END || p->evict_policy > ADSA_EVICT_REUSE_SLOT) return ADSA_ERR_DTYPE;
+  if (p->evict_policy != ADSA_EVICT_ROW_END && p->win_recent_m == 0) return ADSA_ERR_UNSUPPORTED;
   if (p->q_per_kv < 0 || p->q_per_kv > 16) return ADSA_ERR_SHAPE;
   if (p->q_per_kv > 1) {       // grouped queries run on the bf16 matrix cores, logits of one list in LDS
     if (p->dtype != ADSA_BF16) return ADSA_ERR_UNSUPPORTED;
@@ -130,8 +130,8 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
   if (rc) return rc;
   if (!seqs || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  // (with ADSA_EVICT_WHEN_FULL everything resident is attended: nothing to rank at selection time)
-  if (p->score_mode == ADSA_SCORE_VCOS && p->evict_policy != ADSA_EVICT_WHEN_FULL) {
+  // (with the evict-one-when-full policies everything resident is attended: nothing to rank at selection time)
+  if (p->score_mode == ADSA_SCORE_VCOS && p->evict_policy == ADSA_EVICT_ROW_END) {
     AttendPlan plan; Workspace w;
     rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
     if (rc) return rc;
@@ -197,7 +197,7 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
   char* ws = (char*)workspace;
   const bool vcos = p->score_mode == ADSA_SCORE_VCOS;
   const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS;
-  const bool streaming = p->evict_policy == ADSA_EVICT_WHEN_FULL;
+  const bool streaming = p->evict_policy != ADSA_EVICT_ROW_END;
   if (streaming && compact) {          // Section 4.2 as written: make room BEFORE the insertion
     if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
     if (launch_compact(*p, seqs, keep_map, ws, w, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;

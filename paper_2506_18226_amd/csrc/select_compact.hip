@@ -6,7 +6,9 @@
 //                    (Section 4.2: new tokens go to the end of the cache) that the attention
 //                    launch performs, so the ranking never waits for the token's K/V.
 //  k_compact_plan  : Section 4.2 in per-row form: keep flags (prefix, last R rows, top-B of the
-//                    rest), ballot/prefix-sum keep map, in-place move of pos[] and score[].
+//                    rest), ballot/prefix-sum keep map, in-place move of pos[] and score[]; or
+//                    Section 4.2 as written (evict the one most redundant candidate when full), closing
+//                    the hole in order or leaving it to the incoming token.
 //  k_compact_move  : in-place, order-preserving move of the surviving K and V rows.
 //
 // One workgroup of 256 threads owns one sequence in the first two kernels; everything it ranks
@@ -18,6 +20,7 @@ namespace adsa {
 namespace {
 
 constexpr uint8_t kFixed = 0;      // prefix / local / protected row: always kept
+constexpr uint8_t kSkip = 1;       // a freed slot (ADSA_EVICT_REUSE_SLOT): in no list
 constexpr uint8_t kCand = 2;       // competes for the budget
 
 // LDS of one ranking workgroup.  key[] and cls[] are sized by the launch's cap (dynamic LDS:
@@ -167,15 +170,21 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
     if (tid == 0) { sq.status = status_in | ADSA_SEQ_BAD_STATE; sel_cnt[b] = 0; sq.pending_slot = -1; }
     return;
   }
-  // Section 4.2: the query token goes to the end of the cache.  When the append itself happens
-  // later in this step (inside the attention launch), plan for it: slot n, always local, score 0.
-  int n_real = n;
+  // Section 4.2: the query token goes to the end of the cache (or, with ADSA_EVICT_REUSE_SLOT, into
+  // the slot the last eviction freed).  When the append itself happens later in this step (inside
+  // the attention launch), plan for it: that slot, always local, score 0.
+  const int hole = L.evict_policy == ADSA_EVICT_REUSE_SLOT ? sq.hole - 1 : -1;     // freed slot or -1
+  int slot_new = -1;
   if (plan_append && s >= 1) {
-    if (n + 1 > L.cap) {
-      if (tid == 0) { sq.status = status_in | ADSA_SEQ_CACHE_FULL; sel_cnt[b] = 0; sq.pending_slot = -1; }
-      return;
+    if (hole >= 0 && hole < n) slot_new = hole;
+    else {
+      if (n + 1 > L.cap) {
+        if (tid == 0) { sq.status = status_in | ADSA_SEQ_CACHE_FULL; sel_cnt[b] = 0; sq.pending_slot = -1; }
+        return;
+      }
+      slot_new = n;
+      n += 1;
     }
-    n += 1;
   }
 
   // ---- Eq. 1: partition, keys into LDS
@@ -183,10 +192,11 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   const bool largest = keep_largest_of(L.score_mode);
   uint32_t my_cand = 0;
   for (int i = tid; i < n; i += kSelThreads) {
-    const bool planned = i >= n_real;               // the slot the query token will occupy
-    const int c = planned ? 0 : select_class(cell, sq.pos[i]);
+    const bool planned = i == slot_new;             // the slot the query token will occupy
+    const bool freed = i == hole && !planned;       // evicted, not yet reused: nobody attends it
+    const int c = (planned || freed) ? 0 : select_class(cell, sq.pos[i]);
     if (c < 0) s_bad = 1;
-    cls[i] = c == 1 ? kCand : kFixed;
+    cls[i] = freed ? kSkip : c == 1 ? kCand : kFixed;
     key[i] = order_key(planned ? 0.0f : rank_value(sq.score, L.score_rows, L.cap, i), largest);
     my_cand += (c == 1);
   }
@@ -199,7 +209,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
 
   // ---- Eq. 4: threshold of the top-B candidates
   // the streaming policy attends everything resident (context == cache, Tables 1-2)
-  const uint32_t B = L.evict_policy == ADSA_EVICT_WHEN_FULL ? n_cand : (uint32_t)effective_budget(sq, s);
+  const uint32_t B = L.evict_policy != ADSA_EVICT_ROW_END ? n_cand : (uint32_t)effective_budget(sq, s);
   uint32_t T, need_eq;
   radix_threshold(sh, key, cls, n, n_cand, B < n_cand ? B : n_cand, &T, &need_eq);
 
@@ -209,9 +219,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   uint32_t a = 0, e = 0;
   for (int i = lo; i < hi; ++i) {
     const uint32_t k = key[i];
-    const bool cand = cls[i] == kCand;
-    a += (!cand) || (k > T);
-    e += cand && (k == T);
+    const uint8_t c = cls[i];
+    a += (c == kFixed) || (c == kCand && k > T);
+    e += c == kCand && (k == T);
   }
   uint32_t total;
   uint32_t ex = block_excl_scan(sh, a | (e << 16), &total);
@@ -219,24 +229,28 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   int32_t* out = sel_idx + (size_t)b * L.sel_cap;
   for (int i = lo; i < hi; ++i) {
     const uint32_t k = key[i];
-    const bool cand = cls[i] == kCand;
-    bool take = (!cand) || (k > T);
-    const bool eq = cand && (k == T);
+    const uint8_t c = cls[i];
+    bool take = (c == kFixed) || (c == kCand && k > T);
+    const bool eq = c == kCand && (k == T);
     const uint32_t dest = a_run + min(e_run, need_eq);
     if (eq) { take = e_run < need_eq; ++e_run; } else if (take) ++a_run;
     if (take && dest < (uint32_t)L.sel_cap) out[dest] = i;
   }
   const uint32_t cnt = (total & 0xFFFFu) + min(total >> 16, need_eq);
   const bool ok = cnt <= (uint32_t)L.sel_cap;
-  const bool reserve = ok && n > n_real;             // commit the planned append: the slot now exists
+  const bool reserve = ok && slot_new >= 0;          // commit the planned append: the slot now holds the query token
   if (reserve)
-    for (int r = tid; r < L.score_rows; r += kSelThreads) sq.score[(size_t)r * L.cap + n_real] = 0.0f;
+    for (int r = tid; r < L.score_rows; r += kSelThreads) sq.score[(size_t)r * L.cap + slot_new] = 0.0f;
   if (tid == 0) {
     if (!ok) { sq.status = status_in | ADSA_SEQ_SEL_OVERFLOW; sel_cnt[b] = 0; sq.pending_slot = -1; }
     else {
       sel_cnt[b] = (int32_t)cnt;
-      sq.pending_slot = reserve ? n_real : -1;
-      if (reserve) { sq.pos[n_real] = sq.grid_origin + s - 1; sq.n_res = n; }
+      sq.pending_slot = reserve ? slot_new : -1;
+      if (reserve) {
+        sq.pos[slot_new] = sq.grid_origin + s - 1;
+        sq.n_res = n;
+        if (slot_new == hole) sq.hole = 0;
+      }
     }
   }
 }
@@ -255,9 +269,11 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   const bool active = s >= 0 && sq.status == 0;
   // per-row policy: act when the query token closed a grid row; streaming policy (Section 4.2 as
   // written): act when the cache is full and a token is about to be inserted
-  const bool streaming = L.evict_policy == ADSA_EVICT_WHEN_FULL;
+  const bool streaming = L.evict_policy != ADSA_EVICT_ROW_END;
+  const bool reuse = L.evict_policy == ADSA_EVICT_REUSE_SLOT;
   const bool row_end = active && n >= 0 && n <= L.cap &&
-                       (streaming ? (s >= 1 && s <= L.grid_h * W && n == L.cap) : is_row_end(s, L.grid_h, W));
+                       (streaming ? (s >= 1 && s <= L.grid_h * W && n == L.cap && !(reuse && sq.hole != 0))
+                                  : is_row_end(s, L.grid_h, W));
   if (!row_end) {
     if (tid == 0) {
       plan[4 * b + 0] = 0; plan[4 * b + 1] = 0; plan[4 * b + 2] = 0; plan[4 * b + 3] = n;
@@ -277,6 +293,42 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   }
   uint32_t n_rest;
   block_excl_scan(sh, my_rest, &n_rest);
+  if (reuse) {
+    // Evict the candidate ranked last -- smallest key, among equals the newest position -- and leave
+    // everything where it is: the freed slot goes to the incoming token.
+    unsigned long long best = ~0ull;                  // (key, ~pos): the minimum is the victim
+    int best_i = -1;
+    for (int i = tid; i < n; i += kSelThreads) {
+      if (cls[i] != kCand) continue;
+      const unsigned long long v = ((unsigned long long)key[i] << 32) | (uint32_t)~(uint32_t)sq.pos[i];
+      if (v < best) { best = v; best_i = i; }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+      const unsigned long long o = __shfl_xor(best, d, kWave);
+      const int oi = __shfl_xor(best_i, d, kWave);
+      if (o < best) { best = o; best_i = oi; }
+    }
+    __shared__ unsigned long long s_best[kSelThreads / kWave];
+    __shared__ int s_best_i[kSelThreads / kWave];
+    if ((tid & (kWave - 1)) == 0) { s_best[tid / kWave] = best; s_best_i[tid / kWave] = best_i; }
+    __syncthreads();
+    int victim = -1;
+    unsigned long long vb = ~0ull;
+#pragma unroll
+    for (int w = 0; w < kSelThreads / kWave; ++w)
+      if (s_best_i[w] >= 0 && s_best[w] < vb) { vb = s_best[w]; victim = s_best_i[w]; }
+    int32_t* map = keep_map + (size_t)b * L.cap;
+    if (victim >= 0)
+      for (int i = tid; i < n; i += kSelThreads) map[i] = i == victim ? -1 : i;
+    if (tid == 0) {
+      plan[4 * b + 0] = n; plan[4 * b + 1] = n; plan[4 * b + 2] = 0; plan[4 * b + 3] = n;
+      sq.compacted = victim >= 0 ? 1 : 0;
+      if (victim >= 0) sq.hole = victim + 1;
+      if (advance_step) sq.step = s + 1;
+    }
+    return;
+  }
   uint32_t B = (uint32_t)effective_budget(sq, s);
   if (streaming) B = n_rest > 0 ? n_rest - 1 : 0;      // all candidates but the one ranked last
   uint32_t T, need_eq;
@@ -409,7 +461,7 @@ hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_ma
   hipLaunchKernelGGL(k_compact_plan, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, L, seqs,
                      keep_map, plan, advance_step ? 1 : 0);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || p.evict_policy == ADSA_EVICT_REUSE_SLOT) return e;     // slot reuse moves no row
   // one workgroup per 128-byte column slice of a head row (whole head row when it is narrower)
   const int head_bytes = p.head_dim * L.elem_bytes;
   const int slice_bytes = head_bytes < 128 ? head_bytes : 128;

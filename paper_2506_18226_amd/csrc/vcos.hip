@@ -5,9 +5,10 @@
 // u = sum_j v^_j over the candidates,  S_i = (v^_i . u - v^_i . v^_i) / (N - 1): two streaming
 // passes over the candidates' V rows instead of O(N^2 D) work.
 //
-//  k_vcos_norm_usum : grid (slot tile, sequence).  A wave per slot computes the inverse norm; then
-//                     the workgroup's threads each own 4 columns and add the tile's normalised
-//                     rows into a per-tile partial of u (deterministic order, no atomics).
+//  k_vcos_norm_usum : grid (slot tile, sequence).  A wave holds a slot's whole row in registers: inverse
+//                     norm by a wave reduction, then the normalised row is added to the wave's column
+//                     sums; the waves' sums are added in LDS into a per-tile partial of u
+//                     (deterministic order, no atomics, every row read once).
 //  k_vcos_score     : grid (slot tile, sequence).  Sums the tile partials of u into LDS, counts the
 //                     candidates, then a wave per slot takes the dot product and writes S_i into
 //                     score[slot] (non-candidate slots keep their score).
@@ -40,7 +41,7 @@ __device__ __forceinline__ float wave_sum(float x) {
 
 // candidate test for slot i of sequence sq (false for inactive sequences / non row-end compaction)
 __device__ __forceinline__ bool vcos_candidate(const VcosArgs& A, const QueryCell& c, int pos) {
-  if (A.for_compaction && A.evict_policy != ADSA_EVICT_WHEN_FULL) return evict_class(c, pos) == 1;
+  if (A.for_compaction && A.evict_policy == ADSA_EVICT_ROW_END) return evict_class(c, pos) == 1;
   return select_class(c, pos) == 1;     // also the streaming eviction: the incoming query's partition
 }
 
@@ -48,7 +49,8 @@ __device__ __forceinline__ bool vcos_active(const VcosArgs& A, const adsa_seq& s
   if (sq.step < 0 || sq.status != 0 || sq.n_res < 0 || sq.n_res > A.cap) return false;
   if (sq.step > A.grid_h * A.grid_w) return false;
   if (!A.for_compaction) return true;
-  if (A.evict_policy == ADSA_EVICT_WHEN_FULL) return sq.step >= 1 && sq.n_res == A.cap;
+  if (A.evict_policy == ADSA_EVICT_REUSE_SLOT && sq.hole != 0) return false;     // room was made already
+  if (A.evict_policy != ADSA_EVICT_ROW_END) return sq.step >= 1 && sq.n_res == A.cap;
   return is_row_end(sq.step, A.grid_h, A.grid_w);
 }
 
@@ -62,8 +64,12 @@ __device__ __forceinline__ float4 load4(const VcosArgs& A, const char* vbase, in
                      __uint_as_float(r.y << 16), __uint_as_float(r.y & 0xFFFF0000u));
 }
 
+// GPL = column groups (of 4) per lane: a wave holds a whole concatenated V row in registers, so every
+// row is read from HBM once: norm by a wave reduction, then the normalised row goes into the wave's
+// running column sums.  The four waves' sums meet in LDS in wave order (deterministic).
+template <int GPL>
 __global__ __launch_bounds__(kVcThreads) void k_vcos_norm_usum(VcosArgs A) {
-  __shared__ float s_inv[kVcTile];
+  extern __shared__ float s_acc[];                     // [kVcWaves][groups*4]
   const int tile = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   const adsa_seq& sq = A.seqs_c[b];
@@ -74,31 +80,46 @@ __global__ __launch_bounds__(kVcThreads) void k_vcos_norm_usum(VcosArgs A) {
   const QueryCell cell = make_query_cell(sq, sq.step, A.grid_w, A.R, A.w, A.recent_m);
   const char* vbase = reinterpret_cast<const char*>(sq.v);
   const int groups = A.n_heads * A.head_dim / 4;
-  for (int i = s0 + wave; i < s1; i += kVcWaves) {
-    float inv = 0.0f;                                   // 0 marks "not a candidate"
-    if (vcos_candidate(A, cell, sq.pos[i])) {
+  float4 acc[GPL];
+#pragma unroll
+  for (int k = 0; k < GPL; ++k) acc[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int i = s0 + wave; i < s1; i += kVcWaves) {       // ascending slots per wave: fixed summation order
+    float inv = 0.0f;                                     // 0 marks "not a candidate"
+    if (vcos_candidate(A, cell, sq.pos[i])) {             // wave-uniform
+      float4 x[GPL];
       float ss = 0.0f;
-      for (int g = lane; g < groups; g += kWave) {
-        const float4 x = load4(A, vbase, i, g);
-        ss = fmaf(x.x, x.x, ss); ss = fmaf(x.y, x.y, ss); ss = fmaf(x.z, x.z, ss); ss = fmaf(x.w, x.w, ss);
+#pragma unroll
+      for (int k = 0; k < GPL; ++k) {
+        const int g = lane + k * kWave;
+        x[k] = g < groups ? load4(A, vbase, i, g) : make_float4(0.f, 0.f, 0.f, 0.f);
+        ss = fmaf(x[k].x, x[k].x, ss); ss = fmaf(x[k].y, x[k].y, ss);
+        ss = fmaf(x[k].z, x[k].z, ss); ss = fmaf(x[k].w, x[k].w, ss);
       }
       ss = wave_sum(ss);
       inv = 1.0f / fmaxf(sqrtf(ss), 1e-8f);
+#pragma unroll
+      for (int k = 0; k < GPL; ++k) {
+        acc[k].x = fmaf(x[k].x, inv, acc[k].x); acc[k].y = fmaf(x[k].y, inv, acc[k].y);
+        acc[k].z = fmaf(x[k].z, inv, acc[k].z); acc[k].w = fmaf(x[k].w, inv, acc[k].w);
+      }
     }
-    if (lane == 0) { s_inv[i - s0] = inv; A.inv_norm[(size_t)b * A.cap + i] = inv; }
+    if (lane == 0) A.inv_norm[(size_t)b * A.cap + i] = inv;
+  }
+#pragma unroll
+  for (int k = 0; k < GPL; ++k) {
+    const int g = lane + k * kWave;
+    if (g < groups) reinterpret_cast<float4*>(s_acc + (size_t)wave * groups * 4)[g] = acc[k];
   }
   __syncthreads();
   float* up = A.u_part + ((size_t)b * A.n_tiles + tile) * (size_t)(groups * 4);
   for (int g = tid; g < groups; g += kVcThreads) {
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int i = s0; i < s1; ++i) {
-      const float inv = s_inv[i - s0];
-      if (inv == 0.0f) continue;
-      const float4 x = load4(A, vbase, i, g);
-      acc.x = fmaf(x.x, inv, acc.x); acc.y = fmaf(x.y, inv, acc.y);
-      acc.z = fmaf(x.z, inv, acc.z); acc.w = fmaf(x.w, inv, acc.w);
+    float4 t = reinterpret_cast<const float4*>(s_acc)[g];
+#pragma unroll
+    for (int w = 1; w < kVcWaves; ++w) {
+      const float4 o = reinterpret_cast<const float4*>(s_acc + (size_t)w * groups * 4)[g];
+      t.x += o.x; t.y += o.y; t.z += o.z; t.w += o.w;
     }
-    reinterpret_cast<float4*>(up)[g] = acc;
+    reinterpret_cast<float4*>(up)[g] = t;
   }
 }
 
@@ -168,7 +189,22 @@ hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction
   A.slot_stride_b = (long long)p.kv_slot_stride * A.elem_bytes;
   A.head_stride_b = (long long)p.kv_head_stride * A.elem_bytes;
   dim3 grid(A.n_tiles, p.n_seq);
-  hipLaunchKernelGGL(k_vcos_norm_usum, grid, dim3(kVcThreads), 0, st, A);
+  const int gpl = (dim / 4 + kWave - 1) / kWave;          // column groups per lane: 1..32
+  const size_t lds1 = sizeof(float) * (size_t)dim * kVcWaves;
+  if (gpl <= 4) hipLaunchKernelGGL(k_vcos_norm_usum<4>, grid, dim3(kVcThreads), lds1, st, A);
+  else if (gpl <= 6) hipLaunchKernelGGL(k_vcos_norm_usum<6>, grid, dim3(kVcThreads), lds1, st, A);
+  else if (gpl <= 8) hipLaunchKernelGGL(k_vcos_norm_usum<8>, grid, dim3(kVcThreads), lds1, st, A);
+  else if (gpl <= 16) hipLaunchKernelGGL(k_vcos_norm_usum<16>, grid, dim3(kVcThreads), lds1, st, A);
+  else {
+    static bool raised = false;                           // 64..128 KB of LDS: above the default limit
+    if (!raised) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_vcos_norm_usum<32>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) * kVcMaxDim * kVcWaves)) != hipSuccess)
+        return hipErrorInvalidValue;
+      raised = true;
+    }
+    hipLaunchKernelGGL(k_vcos_norm_usum<32>, grid, dim3(kVcThreads), lds1, st, A);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_vcos_score, grid, dim3(kVcThreads), sizeof(float) * (size_t)dim, st, A);

@@ -38,7 +38,7 @@ def test_struct_mirrors_match_the_header():
     assert C.sizeof(B.AdsaParams) == 12 * 4 + 2 * 8 + 4 + 3 * 4
     assert B.SEQ_DTYPE.itemsize == 80
     assert B.SEQ_DTYPE.fields["n_res"][1] == 32 and B.SEQ_DTYPE.fields["status"][1] == 60
-    assert B.SEQ_DTYPE.fields["pending_slot"][1] == 68
+    assert B.SEQ_DTYPE.fields["pending_slot"][1] == 68 and B.SEQ_DTYPE.fields["hole"][1] == 72
 
 
 def good(**kw):
@@ -65,7 +65,7 @@ def test_workspace_size_is_positive_and_monotone(lib):
     (dict(kv_slot_stride=64), -2), (dict(softmax_scale=-1.0), -2),
     (dict(score_mode=B.SCORE_VCOS, n_heads=128, head_dim=128), -8),
     (dict(win_recent_m=-1), -2), (dict(evict_policy=5), -3), (dict(evict_policy=B.EVICT_WHEN_FULL), -8),
-    (dict(q_per_kv=-1), -2), (dict(q_per_kv=17), -2), (dict(q_per_kv=4, dtype=B.F32), -8),
+    (dict(evict_policy=B.EVICT_REUSE_SLOT), -8), (dict(q_per_kv=-1), -2), (dict(q_per_kv=17), -2), (dict(q_per_kv=4, dtype=B.F32), -8),
 ])
 def test_bad_parameters_are_rejected_before_any_launch(lib, kw, code):
     p = good(**kw)
