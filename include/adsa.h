@@ -97,6 +97,10 @@ typedef enum {
                                        local); its K/V rows arrive with adsa_attend(ADSA_FLAG_APPEND).
                                        Once per decode step */
 #define ADSA_FLAG_APPEND        8u  /* adsa_attend: write (k_new, v_new) into pending_slot while attending */
+#define ADSA_FLAG_NEW_F32      32u  /* adsa_attend / adsa_step with a bf16 cache: k_new and v_new are fp32
+                                       [n_seq][n_heads][head_dim]; each value is rounded to the nearest bf16
+                                       (ties to even) once, as it enters the cache, and the launch attends the
+                                       rounded row.  No effect with an fp32 cache */
 #define ADSA_FLAG_ADVANCE      16u  /* adsa_attend / adsa_compact: step += 1 for every active sequence when
                                        the call is done; give it to the LAST call of a decode step only
                                        (adsa_compact tests the row end on the step before the increment) */
@@ -200,7 +204,7 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
  * ADSA_FLAG_APPEND (Section 4.2, new tokens go to the end of the cache): the row (k_new, v_new)
  * is written to the slot adsa_select(ADSA_FLAG_PLAN_APPEND) reserved (pending_slot >= 0), and that
  * slot is attended from k_new / v_new directly.
- * flags: ADSA_FLAG_NO_ACCUMULATE, ADSA_FLAG_APPEND, ADSA_FLAG_ADVANCE.
+ * flags: ADSA_FLAG_NO_ACCUMULATE, ADSA_FLAG_APPEND, ADSA_FLAG_NEW_F32, ADSA_FLAG_ADVANCE.
  */
 int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
                 const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt, void* out,

@@ -16,7 +16,7 @@ from . import build as _build
 
 F32, BF16 = 0, 1
 SCORE_ATTN_MASS, SCORE_VCOS, SCORE_EXT_LARGEST, SCORE_EXT_SMALLEST = 0, 1, 2, 3
-FLAG_NO_COMPACT, FLAG_NO_ACCUMULATE, FLAG_PLAN_APPEND, FLAG_APPEND, FLAG_ADVANCE = 1, 2, 4, 8, 16
+FLAG_NO_COMPACT, FLAG_NO_ACCUMULATE, FLAG_PLAN_APPEND, FLAG_APPEND, FLAG_ADVANCE, FLAG_NEW_F32 = 1, 2, 4, 8, 16, 32
 SEQ_CACHE_FULL, SEQ_BAD_STATE, SEQ_SEL_OVERFLOW = 1, 2, 4
 MAX_CAP = 8192
 EVICT_ROW_END, EVICT_WHEN_FULL, EVICT_REUSE_SLOT = 0, 1, 2

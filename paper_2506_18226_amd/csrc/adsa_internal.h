@@ -59,7 +59,7 @@ int vcos_tiles(int cap);
 hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
                          const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
                          void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
-                         bool advance, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
+                         bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
 // grouped-query path (q_per_kv >= 2): matrix-core kernel, one workgroup per (sequence, cache head)
 constexpr size_t kGqaMaxLds = 128 * 1024;     // dynamic LDS one workgroup may ask for
 int gqa_logit_stride(const adsa_params& p);
@@ -67,7 +67,7 @@ size_t gqa_lds_bytes(const adsa_params& p, int waves);
 hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
                              const void* k_new, const void* v_new, const int32_t* sel_idx,
                              const int32_t* sel_cnt, void* out, float* lse, bool accumulate, bool append,
-                             bool advance, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
+                             bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_map, char* ws,
                           const Workspace& w, bool advance_step, hipStream_t st);
 

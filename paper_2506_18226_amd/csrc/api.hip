@@ -72,7 +72,7 @@ hipEvent_t prof_event() {
 hipError_t timed_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
                         const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
                         void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
-                        bool advance, hipStream_t st) {
+                        bool advance, bool new_f32, hipStream_t st) {
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (g_prof.on) {
     e0 = prof_event();
@@ -80,7 +80,7 @@ hipError_t timed_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* 
     if (!e0 || !e1) e0 = e1 = nullptr;
   }
   return launch_attend(p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, ws, w, accumulate, append,
-                       advance, st, e0, e1);
+                       advance, new_f32 && p.dtype == ADSA_BF16, st, e0, e1);
 }
 
 }  // namespace
@@ -158,7 +158,7 @@ int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void*
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS && !(flags & ADSA_FLAG_NO_ACCUMULATE);
   if (timed_attend(*p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, (char*)workspace, w, accumulate,
-                   append, (flags & ADSA_FLAG_ADVANCE) != 0, st) != hipSuccess)
+                   append, (flags & ADSA_FLAG_ADVANCE) != 0, (flags & ADSA_FLAG_NEW_F32) != 0, st) != hipSuccess)
     return ADSA_ERR_LAUNCH;
   return ADSA_OK;
 }
@@ -205,7 +205,7 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
   if (vcos && !streaming && launch_vcos(*p, seqs, false, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
   if (launch_select(*p, seqs, sel_idx, sel_cnt, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
   if (timed_attend(*p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, ws, w, accumulate, true,
-                   !compact || streaming, st) != hipSuccess)
+                   !compact || streaming, (flags & ADSA_FLAG_NEW_F32) != 0, st) != hipSuccess)
     return ADSA_ERR_LAUNCH;
   if (compact && !streaming) {
     if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;

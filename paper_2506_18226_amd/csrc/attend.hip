@@ -74,6 +74,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// 8 consecutive fp32 values -> 8 bf16 (round to nearest even) in one 16-byte vector
+__device__ __forceinline__ uint4 pack8_bf16(const float* f) {
+  const float4 a = reinterpret_cast<const float4*>(f)[0], b = reinterpret_cast<const float4*>(f)[1];
+  return make_uint4(f32_to_bf16_rne(a.x) | (f32_to_bf16_rne(a.y) << 16), f32_to_bf16_rne(a.z) | (f32_to_bf16_rne(a.w) << 16),
+                    f32_to_bf16_rne(b.x) | (f32_to_bf16_rne(b.y) << 16), f32_to_bf16_rne(b.z) | (f32_to_bf16_rne(b.w) << 16));
+}
+
 // Data handed from one workgroup to another inside a launch (chunk partials, logits) is written
 // and read with device-scope relaxed atomics: they go through to the level where all XCDs agree,
 // so no L2 write-back / invalidate (a device-scope fence) is needed.  Order is kept by the issue
@@ -108,6 +115,7 @@ struct AttendArgs {
   int32_t* counters;    // [n_seq][n_hg]                 arrival counters, zero between launches
   int n_heads, n_hg, sel_cap, lg_stride, chunk_max, cap;
   int accumulate, append, advance;     // advance: step += 1 at the end
+  int new_f32;                         // k_new / v_new are fp32 although the cache is bf16: round as they enter
   long long slot_stride_b, head_stride_b;
   float scale_log2;     // softmax scale * log2(e)
 };
@@ -247,12 +255,22 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
   const long long lane_off = (long long)head_c * A.head_stride_b + dl * 16;
   char* kb = k_base + lane_off;
   char* vb = v_base + lane_off;
-  const char* kn = A.k_new + row_off;
-  const char* vn = A.v_new + row_off;
+  // the new token's row as this launch attends it; fp32 rows of a bf16 cache are rounded once, here, and
+  // every lane keeps its 16-byte piece of the rounded row in registers
+  const bool cvt = EB == 2 && A.new_f32 && new_slot >= 0;
+  const char* kn = cvt ? kb : A.k_new + row_off;     // (cvt: any valid row; the loaded value is replaced)
+  const char* vn = cvt ? vb : A.v_new + row_off;
+  uint4 nk = make_uint4(0u, 0u, 0u, 0u), nv = nk;
+  if (cvt) {
+    const size_t off32 = ((size_t)b * A.n_heads + head_c) * D * 4 + dl * 32;
+    nk = pack8_bf16(reinterpret_cast<const float*>(A.k_new + off32));
+    nv = pack8_bf16(reinterpret_cast<const float*>(A.v_new + off32));
+  }
   if (new_slot >= 0 && chunk == n_chunks - 1 && wave == 0 && ts == 0 && head_ok) {
     const long long off = (long long)new_slot * A.slot_stride_b;     // this group's rows of the new token
-    *reinterpret_cast<uint4*>(kb + off) = *reinterpret_cast<const uint4*>(kn);
-    *reinterpret_cast<uint4*>(vb + off) = *reinterpret_cast<const uint4*>(vn);
+    if (!cvt) { nk = *reinterpret_cast<const uint4*>(kn); nv = *reinterpret_cast<const uint4*>(vn); }
+    *reinterpret_cast<uint4*>(kb + off) = nk;
+    *reinterpret_cast<uint4*>(vb + off) = nv;
   }
 
   float m = -INFINITY, l = 0.0f, acc[EPL];
@@ -272,6 +290,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
       const bool is_new = slot == new_slot;         // the query token itself: read it from k_new / v_new
       kr[u] = load_stream16(is_new ? kn : kb + off);
       vr[u] = load_stream16(is_new ? vn : vb + off);
+      if (cvt && is_new) { kr[u] = nk; vr[u] = nv; }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -467,7 +486,9 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
 template <int EB, int D, int HT, int NW>
 hipError_t launch_attend_w(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
-  constexpr int U = 4;      // row pairs in flight per lane; 8 was measured slower (register pressure)
+  // row pairs in flight per lane; 8 was measured slower (register pressure).  A 16-wave workgroup has
+  // 128 registers per lane: 2 pairs fit without spilling, and its 1024 lanes keep enough in flight
+  constexpr int U = NW == 16 ? 2 : 4;
   const size_t lds = (size_t)HT * plan.chunk_max * sizeof(float);
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)
@@ -570,10 +591,10 @@ hipError_t launch_workspace_init(char* ws, const Workspace& w, hipStream_t st) {
 hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
                          const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
                          void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
-                         bool advance, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                         bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (p.q_per_kv > 1)
     return launch_attend_gqa(p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, accumulate, append,
-                             advance, st, ev_start, ev_stop);
+                             advance, new_f32, st, ev_start, ev_stop);
   AttendArgs A;
   A.seqs = seqs; A.q = (const char*)q; A.k_new = (const char*)k_new; A.v_new = (const char*)v_new;
   A.sel_idx = sel_idx; A.sel_cnt = sel_cnt; A.out = (char*)out; A.lse = lse;
@@ -584,6 +605,7 @@ hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq*
   A.n_heads = p.n_heads; A.n_hg = plan.n_head_groups; A.sel_cap = p.sel_cap; A.lg_stride = w.lg_stride;
   A.chunk_max = plan.chunk_max; A.cap = p.cap;
   A.accumulate = accumulate ? 1 : 0; A.append = append ? 1 : 0; A.advance = advance ? 1 : 0;
+  A.new_f32 = (new_f32 && append) ? 1 : 0;
   const int eb = elem_bytes(p);
   A.slot_stride_b = (long long)p.kv_slot_stride * eb;
   A.head_stride_b = (long long)p.kv_head_stride * eb;

@@ -63,6 +63,11 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// n consecutive fp32 values (n = 4 or 8) -> bf16, round to nearest even, packed two per dword
+__device__ __forceinline__ void pack_bf16(const float* f, int n, uint32_t* w) {
+  for (int i = 0; i < n / 2; ++i) w[i] = f32_to_bf16_rne(f[2 * i]) | (f32_to_bf16_rne(f[2 * i + 1]) << 16);
+}
+
 template <int BYTES> struct VLoad;
 template <> struct VLoad<8> {
   static constexpr int W = 2;
@@ -90,6 +95,7 @@ struct GqaArgs {
   float* lse;
   int n_heads, G, sel_cap, lg_stride, cap, stage_b;
   int accumulate, append, advance;
+  int new_f32;          // k_new / v_new are fp32 although the cache is bf16: round as they enter
   long long slot_stride_b, head_stride_b;
   float scale_log2;
 };
@@ -154,13 +160,31 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   const int len = cnt;
   const int n_tiles = (len + 15) / 16;
   const int new_slot = (A.append && pending >= 0 && pending < A.cap) ? pending : -1;
-  const char* const kn = A.k_new + ((size_t)b * A.n_heads + hk) * D * 2;
-  const char* const vn = A.v_new + ((size_t)b * A.n_heads + hk) * D * 2;
+  // the new token's row as this launch attends it; fp32 rows are rounded once, here: every lane keeps
+  // the pieces of the rounded row it would load (K: 16 bytes at ld_piece, V: its EV columns)
+  const bool cvt = A.new_f32 && new_slot >= 0;
+  const size_t new_row = ((size_t)b * A.n_heads + hk) * D;
+  const char* const kn = cvt ? k_base : A.k_new + new_row * 2;     // (cvt: any valid row; the value is replaced)
+  const char* const vn = cvt ? v_base : A.v_new + new_row * 2;
+  const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
+  uint32_t nk[4] = {0u, 0u, 0u, 0u}, nv[VW];
+#pragma unroll
+  for (int i = 0; i < VW; ++i) nv[i] = 0u;
+  if (cvt) {
+    const float* k32 = reinterpret_cast<const float*>(A.k_new) + new_row;
+    const float* v32 = reinterpret_cast<const float*>(A.v_new) + new_row;
+    float t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = k32[ld_piece * 8 + i];
+    pack_bf16(t, 8, nk);
+#pragma unroll
+    for (int i = 0; i < EV; ++i) t[i] = v32[r * EV + i];
+    pack_bf16(t, EV, nv);
+  }
   __syncthreads();
 
   const int stage_b = A.stage_b;                     // bytes of LDS each wave owns
   char* const stage = s_stage + wave * stage_b;
-  const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
   struct Stage { uint4 k[UT][LT]; uint32_t v[UT][4][VW]; };
 
   auto load = [&](Stage& st, int sid) {
@@ -173,13 +197,17 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
           const int slot = s_slot[min(tile * 16 + u * RPL + ld_row, len - 1)];
           const char* p = (slot == new_slot) ? kn : k_base + (long long)slot * A.slot_stride_b;
           const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + ld_piece * 16));
-          st.k[ut][u] = make_uint4(v.x, v.y, v.z, v.w);
+          st.k[ut][u] = (cvt && slot == new_slot) ? make_uint4(nk[0], nk[1], nk[2], nk[3]) : make_uint4(v.x, v.y, v.z, v.w);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int slot = s_slot[min(tile * 16 + 4 * kg + i, len - 1)];
           const char* p = (slot == new_slot) ? vn : v_base + (long long)slot * A.slot_stride_b;
           VLoad<EV * 2>::load(p + r * (EV * 2), st.v[ut][i]);
+          if (cvt && slot == new_slot) {
+#pragma unroll
+            for (int w2 = 0; w2 < VW; ++w2) st.v[ut][i][w2] = nv[w2];
+          }
         }
       }
     }
@@ -315,8 +343,21 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   }
   if (new_slot >= 0 && tid < D / 8) {                // Section 4.2 append: this cache head's rows of the new token
     const long long off = (long long)new_slot * A.slot_stride_b + tid * 16;
-    *reinterpret_cast<uint4*>(k_base + off) = *reinterpret_cast<const uint4*>(kn + tid * 16);
-    *reinterpret_cast<uint4*>(v_base + off) = *reinterpret_cast<const uint4*>(vn + tid * 16);
+    if (cvt) {
+      float t[8];
+      uint32_t w[4];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = reinterpret_cast<const float*>(A.k_new)[new_row + tid * 8 + i];
+      pack_bf16(t, 8, w);
+      *reinterpret_cast<uint4*>(k_base + off) = make_uint4(w[0], w[1], w[2], w[3]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = reinterpret_cast<const float*>(A.v_new)[new_row + tid * 8 + i];
+      pack_bf16(t, 8, w);
+      *reinterpret_cast<uint4*>(v_base + off) = make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+      *reinterpret_cast<uint4*>(k_base + off) = *reinterpret_cast<const uint4*>(kn + tid * 16);
+      *reinterpret_cast<uint4*>(v_base + off) = *reinterpret_cast<const uint4*>(vn + tid * 16);
+    }
   }
 
   // ---------------- attention mass of this cache head: sum over its G queries, ascending
@@ -375,7 +416,7 @@ size_t gqa_lds_bytes(const adsa_params& p, int waves) {
 hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
                              const void* k_new, const void* v_new, const int32_t* sel_idx,
                              const int32_t* sel_cnt, void* out, float* lse, bool accumulate, bool append,
-                             bool advance, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                             bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (p.dtype != ADSA_BF16 || p.q_per_kv < 2 || p.q_per_kv > 16) return hipErrorInvalidValue;
   GqaArgs A;
   A.seqs = seqs; A.q = (const char*)q; A.k_new = (const char*)k_new; A.v_new = (const char*)v_new;
@@ -383,6 +424,7 @@ hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_
   A.n_heads = p.n_heads; A.G = p.q_per_kv; A.sel_cap = p.sel_cap; A.lg_stride = gqa_logit_stride(p);
   A.cap = p.cap; A.stage_b = (int)gqa_stage_bytes(p);
   A.accumulate = accumulate ? 1 : 0; A.append = append ? 1 : 0; A.advance = advance ? 1 : 0;
+  A.new_f32 = (new_f32 && append) ? 1 : 0;
   A.slot_stride_b = (long long)p.kv_slot_stride * 2;
   A.head_stride_b = (long long)p.kv_head_stride * 2;
   const float scale = p.softmax_scale != 0.0f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);

@@ -793,6 +793,49 @@ def test_streaming_cache_slot_reuse_free_running(mode, layout):
     assert n_evictions >= 21
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("G", [1, 4])
+def test_append_rounds_fp32_rows_into_a_bf16_cache(G, layout):
+    """ADSA_FLAG_NEW_F32: k_new / v_new arrive as fp32, the cache is bf16.  The rows must enter the cache
+    rounded to nearest-even (compared bit for bit with the host rounding the oracle's inputs use) and the
+    step must equal the oracle's step on the rounded rows."""
+    over = dict(n_heads=4, head_dim=64, grid_h=6, grid_w=8, prefix_len=5, win_rows_back=1, win_col_radius=1,
+                dtype="bf16", q_per_kv=G)
+    wl = WL.get_workload("xl", n_seq=1, budget=6, budget_num=0, budget_den=0, **over)
+    cfg = oracle_cfg(wl, budget=6)
+    steps = [1, 7, 8, 9, 20, 48]
+    q, k, v, _, snaps = replay(wl, cfg, 0, 0, max(steps), snapshots=set(steps))
+    P = cfg.grid_origin
+    rng = np.random.default_rng(77)
+    # unrounded fp32 rows for the new tokens (values with low mantissa bits set, incl. exact ties of the rounding)
+    k32 = rng.standard_normal((len(steps), wl.n_heads, wl.head_dim)).astype(np.float32)
+    v32 = rng.standard_normal((len(steps), wl.n_heads, wl.head_dim)).astype(np.float32)
+    k32[:, 0, :4] = np.array([1.00390625, 1.01171875, -1.00390625, 3.0e-39], np.float32)   # ties to even, a subnormal
+    params = params_for(wl, len(steps), cfg.cap, layout=layout)
+    batch = LayerBatch(params, DEV)
+    for b, s in enumerate(steps):
+        load_state(batch, b, snaps[s], cfg, s)
+    batch.upload_seqs()
+    pp = [P + s - 1 for s in steps]
+    qd = to_device(np.stack([q[p] for p in pp]), params.dtype, DEV)
+    kd, vd = torch.from_numpy(k32).to(DEV), torch.from_numpy(v32).to(DEV)
+    batch.step(qd, kd, vd, flags=B.FLAG_NEW_F32)
+    torch.cuda.synchronize()
+    seqs = batch.read_seqs()
+    out, lse = to_host(batch.out), batch.lse.cpu().numpy()
+    Kd, Vd = batch.k_host(), batch.v_host()
+    kr, vr = WL.round_to_bf16(k32), WL.round_to_bf16(v32)
+    for b, s in enumerate(steps):
+        st = snaps[s].copy()
+        ref = oracle.step(cfg, st, s, q[pp[b]], kr[b], vr[b])
+        tag = f"G={G} s={s}"
+        n = st.n_res
+        assert seqs["status"][b] == 0 and seqs["n_res"][b] == n, tag
+        assert np.array_equal(Kd[b, :n], st.K[:n]) and np.array_equal(Vd[b, :n], st.V[:n]), tag   # rounded rows, bit for bit
+        check_out(wl, out[b], ref["out"], tag)
+        assert np.abs(lse[b] - ref["lse"]).max() <= lse_tol(wl), tag
+
+
 # ----------------------------------------------------------------------------- per-head attended sets
 def test_per_head_selection_is_one_single_head_sequence_per_head():
     """The paper does not say whether heads share one attended set.  Per-head sets need no extra
