@@ -169,7 +169,14 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
   constexpr int PF = 1024 / kAttThreads;            // score read-modify-writes a thread starts early
   extern __shared__ float s_logit[];                // logits tile [HT][chunk_max]
   __shared__ float s_pm[kAttWaves * TT][HT], s_pl[kAttWaves * TT][HT];   // partial (m, l) per lane group
-  __shared__ float s_pacc[kAttWaves * TT][HT][D];                          // partial accumulators
+  // Merge layout.  One head per workgroup: all threads share the merge, thread t = (column t / S, split t % S)
+  // adds every S-th partial of its column and the S splits meet by shuffles; rows are padded so that the
+  // 64 lanes of a wave hit 64 different banks.  Several heads: one thread per output element.
+  constexpr int NPART = kAttWaves * TT;
+  constexpr int S = kAttThreads / D;
+  constexpr bool kSplitMerge = HT == 1 && S >= 2 && S <= kWave && NPART % S == 0;
+  constexpr int STR = kSplitMerge ? D + kWave / S : D;
+  __shared__ float s_pacc[NPART * HT * STR];                                // partial accumulators [lane group][head][STR]
   __shared__ float s_lse2[HT];
   __shared__ int s_ticket;
 
@@ -339,55 +346,92 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
     const int pi = wave * TT + ts;
     if (dl == 0) { s_pm[pi][hs] = m; s_pl[pi][hs] = l; }
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) s_pacc[pi][hs][dl * EPL + e] = acc[e];
+    for (int e = 0; e < EPL; ++e) s_pacc[(pi * HT + hs) * STR + dl * EPL + e] = acc[e];
   }
   __syncthreads();
   float lse2_h[HT];                                 // log2-domain log-sum-exp of this chunk, per head
-  float M_mine = -INFINITY, L_mine = 1.0f;
-  const int o_sb = (tid / D) % HT;                 // head of the output element this thread reduces first
-#pragma unroll
-  for (int sb = 0; sb < HT; ++sb) {
+  if constexpr (kSplitMerge) {
+    constexpr int PPS = NP / S;                     // partials each thread adds
+    const int d = tid / S, qv = tid - d * S;
     float M = -INFINITY;
 #pragma unroll
-    for (int pi = 0; pi < NP; ++pi) M = fmaxf(M, s_pm[pi][sb]);
-    float L = 0.0f;
+    for (int pi = 0; pi < NP; ++pi) M = fmaxf(M, s_pm[pi][0]);
+    float L = 0.0f, a = 0.0f;
 #pragma unroll
-    for (int pi = 0; pi < NP; ++pi) {
-      const float mp = s_pm[pi][sb];
-      L = fmaf(s_pl[pi][sb], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - M), L);   // empty partial: weight 0
+    for (int k = 0; k < PPS; ++k) {
+      const int pi = k * S + qv;
+      const float mp = s_pm[pi][0];
+      const float wgt = (mp == -INFINITY) ? 0.0f : fast_exp2(mp - M);      // empty partial: weight 0
+      L = fmaf(s_pl[pi][0], wgt, L);
+      a = fmaf(s_pacc[pi * STR + d], wgt, a);
     }
-    lse2_h[sb] = M + __log2f(L);
-    if (sb == o_sb) { M_mine = M; L_mine = L; }
-  }
-  for (int o = tid; o < heads_here * D; o += kAttThreads) {
-    const int sb = o / D, d = o - sb * D;
-    float Mo = M_mine, Lo = L_mine;
-    if (o >= kAttThreads) {                         // second pass (HT*D > 256): redo this head's scalars
-      Mo = -INFINITY;
-      for (int pi = 0; pi < NP; ++pi) Mo = fmaxf(Mo, s_pm[pi][sb]);
-      Lo = 0.0f;
-      for (int pi = 0; pi < NP; ++pi) {
-        const float mp = s_pm[pi][sb];
-        Lo = fmaf(s_pl[pi][sb], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - Mo), Lo);
+#pragma unroll
+    for (int x = 1; x < S; x <<= 1) {               // the S splits of a column sit in adjacent lanes
+      L += __shfl_xor(L, x, kWave);
+      a += __shfl_xor(a, x, kWave);
+    }
+    lse2_h[0] = M + __log2f(L);
+    if (qv == 0) {
+      const int hd = hg;
+      if (direct) {
+        const float val = a / L;
+        const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
+        if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
+        else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
+        if (d == 0) A.lse[(size_t)b * A.n_heads + hd] = lse2_h[0] * kLn2;
+      } else {
+        const size_t pidx = ((size_t)b * A.n_heads + hd) * n_chunks + chunk;
+        st_dev(A.part_acc + pidx * D + d, a);
+        if (d == 0) st_dev2(A.part_ml + pidx * 2, M, L);
       }
     }
-    float a = 0.0f;
-#pragma unroll
-    for (int pi = 0; pi < NP; ++pi) {
-      const float mp = s_pm[pi][sb];
-      a = fmaf(s_pacc[pi][sb][d], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - Mo), a);
+  } else {
+    float M_mine = -INFINITY, L_mine = 1.0f;
+    const int o_sb = (tid / D) % HT;                 // head of the output element this thread reduces first
+  #pragma unroll
+    for (int sb = 0; sb < HT; ++sb) {
+      float M = -INFINITY;
+  #pragma unroll
+      for (int pi = 0; pi < NP; ++pi) M = fmaxf(M, s_pm[pi][sb]);
+      float L = 0.0f;
+  #pragma unroll
+      for (int pi = 0; pi < NP; ++pi) {
+        const float mp = s_pm[pi][sb];
+        L = fmaf(s_pl[pi][sb], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - M), L);   // empty partial: weight 0
+      }
+      lse2_h[sb] = M + __log2f(L);
+      if (sb == o_sb) { M_mine = M; L_mine = L; }
     }
-    const int hd = hg * HT + sb;
-    if (direct) {
-      const float val = a / Lo;
-      const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
-      if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
-      else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
-      if (d == 0) A.lse[(size_t)b * A.n_heads + hd] = (Mo + __log2f(Lo)) * kLn2;
-    } else {
-      const size_t pidx = ((size_t)b * A.n_heads + hd) * n_chunks + chunk;
-      st_dev(A.part_acc + pidx * D + d, a);
-      if (d == 0) st_dev2(A.part_ml + pidx * 2, Mo, Lo);
+    for (int o = tid; o < heads_here * D; o += kAttThreads) {
+      const int sb = o / D, d = o - sb * D;
+      float Mo = M_mine, Lo = L_mine;
+      if (o >= kAttThreads) {                         // second pass (HT*D > 256): redo this head's scalars
+        Mo = -INFINITY;
+        for (int pi = 0; pi < NP; ++pi) Mo = fmaxf(Mo, s_pm[pi][sb]);
+        Lo = 0.0f;
+        for (int pi = 0; pi < NP; ++pi) {
+          const float mp = s_pm[pi][sb];
+          Lo = fmaf(s_pl[pi][sb], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - Mo), Lo);
+        }
+      }
+      float a = 0.0f;
+  #pragma unroll
+      for (int pi = 0; pi < NP; ++pi) {
+        const float mp = s_pm[pi][sb];
+        a = fmaf(s_pacc[(pi * HT + sb) * STR + d], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - Mo), a);
+      }
+      const int hd = hg * HT + sb;
+      if (direct) {
+        const float val = a / Lo;
+        const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
+        if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
+        else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
+        if (d == 0) A.lse[(size_t)b * A.n_heads + hd] = (Mo + __log2f(Lo)) * kLn2;
+      } else {
+        const size_t pidx = ((size_t)b * A.n_heads + hd) * n_chunks + chunk;
+        st_dev(A.part_acc + pidx * D + d, a);
+        if (d == 0) st_dev2(A.part_ml + pidx * 2, Mo, Lo);
+      }
     }
   }
 
