@@ -54,6 +54,9 @@ def parse_args():
                     help="run the paper's own cache policy instead of the headline one: capacity = prefix + half the "
                          "image tokens, V-cosine ranking (Eq. 2-3), evict one when full, 1-D window, dense attention "
                          "over everything resident (Section 4.2, Tables 1-2); the incoming token takes the evicted slot")
+    ap.add_argument("--two-pass-vcos", action="store_true",
+                    help="with --paper-cache: rank with two passes over V per step (ADSA_SCORE_VCOS) instead of the numbers "
+                         "the attention launch leaves behind (ADSA_SCORE_VCOS_FUSED)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (1 GiB read + 1 GiB written, 4 times): the "
                          "reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -64,7 +67,7 @@ class Job:
     """All device state of the benchmark: every layer's caches as one layer-major batch,
     step-major inputs, and the per-step launch sequence."""
 
-    def __init__(self, wl, n_layers, device, paper_cache=False):
+    def __init__(self, wl, n_layers, device, paper_cache=False, two_pass_vcos=False):
         import torch
         from paper_2506_18226_amd import binding as B
         from paper_2506_18226_amd import workloads as WL
@@ -78,7 +81,8 @@ class Job:
             cap = P + wl.n_image_tokens // 2
             self.layer_params = B.make_params(
                 n_seq=n, n_heads=h, head_dim=D, grid_h=wl.grid_h, grid_w=wl.grid_w, win_rows_back=0,
-                win_col_radius=0, dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=B.SCORE_VCOS,
+                win_col_radius=0, dtype=B.F32 if wl.dtype == "f32" else B.BF16,
+                score_mode=B.SCORE_VCOS if two_pass_vcos else B.SCORE_VCOS_FUSED,
                 cap=cap, sel_cap=cap, win_recent_m=2 * wl.grid_w + 1, evict_policy=B.EVICT_REUSE_SLOT,
                 q_per_kv=wl.q_per_kv)
         else:
@@ -113,6 +117,8 @@ class Job:
             s["status"], s["compacted"], s["pending_slot"], s["hole"] = 0, 0, -1, 0
         mb.upload_seqs()
         mb.score.zero_()
+        if mb.vcos_u is not None:
+            mb.vcos_u.zero_()
         self.sel_cnt_log.zero_()
         self.torch.cuda.synchronize()
 
@@ -213,7 +219,7 @@ def main():
     wl = WL.get_workload(args.workload)
     n_layers = args.layers if args.layers > 0 else wl.n_layers
     t_setup = time.perf_counter()
-    job = Job(wl, n_layers, device, paper_cache=args.paper_cache)
+    job = Job(wl, n_layers, device, paper_cache=args.paper_cache, two_pass_vcos=args.two_pass_vcos)
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
     S = job.n_steps_total
@@ -250,7 +256,9 @@ def main():
                         f"w={wl.win_col_radius}, budget "
                         + (f"{wl.budget}" if wl.budget_den == 0 else f"{wl.budget_num}/{wl.budget_den} of context")
                         + (", ranking=accumulated attention mass, row-end eviction" if not args.paper_cache else
-                           f"; PAPER CACHE POLICY: capacity {job.layer_params.cap}, V-cosine ranking, evict one when "
+                           f"; PAPER CACHE POLICY: capacity {job.layer_params.cap}, V-cosine ranking "
+                           + ("(two passes over V per step)" if args.two_pass_vcos else "(fused into the attention launch)") +
+                           f", evict one when "
                            f"full (the incoming token takes its slot), 1-D window of {job.layer_params.win_recent_m}, "
                            f"attention over everything resident"),
             "decode_steps_timed": [s0, S], "global_batch": wl.n_seq, "layers": n_layers,

@@ -21,10 +21,11 @@
  *
  * Cache layout.  Element (slot, head, d) of a sequence's K (same for V) lives
  * at  k + slot*kv_slot_stride + head*kv_head_stride + d  (strides in
- * elements).  [slot][head][D] (slot stride = n_heads*head_dim, head stride =
- * head_dim) makes a gathered token one contiguous burst and is the fast path;
- * [head][slot][D] is expressible too.  Base pointers must be 16-byte aligned
- * and both strides multiples of 16 bytes.
+ * elements).  [head][slot][D] (slot stride = head_dim, head stride >= cap*head_dim):
+ * a head's rows are contiguous, one workgroup streams one head -- the fast
+ * path; [slot][head][D] (slot stride = n_heads*head_dim, head stride =
+ * head_dim) is supported too.  Base pointers must be 16-byte aligned and both
+ * strides multiples of 16 bytes.
  *
  * Decode-step convention.  `step` = s = number of image tokens in the context
  * INCLUDING the query token; the query token is image token s-1, at grid cell
@@ -65,7 +66,17 @@ typedef enum {
   ADSA_SCORE_ATTN_MASS = 0,    /* accumulated softmax probability received so far; keep LARGEST */
   ADSA_SCORE_VCOS = 1,         /* mean pairwise cosine of V (Eq. 2-3) over the candidates; keep SMALLEST */
   ADSA_SCORE_EXT_LARGEST = 2,  /* caller-maintained score[]; keep largest */
-  ADSA_SCORE_EXT_SMALLEST = 3  /* caller-maintained score[]; keep smallest */
+  ADSA_SCORE_EXT_SMALLEST = 3, /* caller-maintained score[]; keep smallest */
+  ADSA_SCORE_VCOS_FUSED = 4    /* the same Eq. 2-3 ranking as ADSA_SCORE_VCOS for ADSA_EVICT_REUSE_SLOT, without
+                                  separate passes over V: the attention launch, which streams every resident
+                                  V row anyway, also takes each row's squared norm and its dot product with
+                                  the running sum u of the candidates' normalised V vectors (adsa_seq.vcos_u,
+                                  kept up to date by adsa_compact: minus the evicted row, plus the row that
+                                  leaves the local window next).  The next eviction ranks from those numbers.
+                                  Needs [head][slot][D] caches and q_per_kv <= 1.  Whenever the running state
+                                  does not belong to the step at hand (first use, a cache edited by the
+                                  caller) the call falls back to the two-pass computation, so results never
+                                  depend on it being warm */
 } adsa_score_mode;
 
 /* When the dynamic cache evicts (Section 4.2). */
@@ -134,7 +145,7 @@ typedef struct adsa_params {
                                   in about 100 KB of LDS, else ADSA_ERR_UNSUPPORTED */
 } adsa_params;
 
-/* Device array of n_seq entries: the ragged per-sequence state.  The kernels read AND update
+/* Device array of n_seq entries (96 bytes each): the ragged per-sequence state.  The kernels read AND update
    n_res, step, status, compacted, so one launch serves sequences at different positions. */
 typedef struct adsa_seq {
   void*    k;                  /* this sequence's K cache (dtype elements) */
@@ -143,7 +154,10 @@ typedef struct adsa_seq {
   float*   score;              /* [score_rows][cap] ranking score of each resident slot: the rank of slot i
                                   is the sum over rows (ascending, fp32) of score[row][i].
                                   ADSA_SCORE_ATTN_MASS: score_rows = n_heads, one accumulator per head
-                                  (each head's workgroup updates only its own row); else score_rows = 1 */
+                                  (each head's workgroup updates only its own row).
+                                  ADSA_SCORE_VCOS_FUSED: score_rows = 2*n_heads, rows 2h and 2h+1 hold head h's
+                                  share of |v|^2 and of v.u per slot (written by the attention launch; not a
+                                  rank by themselves).  Else score_rows = 1 */
   int32_t  n_res;              /* resident slots */
   int32_t  step;               /* s (see the decode-step convention above); < 0: inactive */
   int32_t  grid_origin;        /* P: absolute position of image token 0 (= prefix length) */
@@ -159,6 +173,11 @@ typedef struct adsa_seq {
                                   with 0).  A freed slot still counts in n_res but is in no list; the next
                                   adsa_select(PLAN_APPEND) gives it to the query token and clears hole */
   int32_t  reserved;
+  float*   vcos_u;             /* ADSA_SCORE_VCOS_FUSED: [n_heads*head_dim + 4] floats owned by the caller and
+                                  maintained by the library: the running sum u, then two step tags (as floats)
+                                  that say which step u and the score rows belong to.  Zero it when the cache
+                                  or `step` is changed by hand.  NULL otherwise */
+  int64_t  reserved2;
 } adsa_seq;
 
 /* Bytes of device scratch the entry points need for these parameters (0 if they are invalid). */

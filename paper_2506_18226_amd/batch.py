@@ -51,6 +51,9 @@ class LayerBatch:
         self.rows = B.score_rows(p)
         self.score = torch.zeros((n, self.rows, cap), dtype=torch.float32, device=dev)
         self.seqs_host = np.zeros(n, dtype=B.SEQ_DTYPE)
+        # running V-cosine state of the fused ranking: u [h*D] + 4 tag words per sequence
+        self.vcos_u = (torch.zeros((n, h * D + 4), dtype=torch.float32, device=dev)
+                       if p.score_mode == B.SCORE_VCOS_FUSED else None)
         elem = self.K.element_size()
         for b in range(n):
             s = self.seqs_host[b]
@@ -60,6 +63,8 @@ class LayerBatch:
             s["score"] = self.score.data_ptr() + b * self.rows * cap * 4
             s["step"] = -1
             s["pending_slot"] = -1
+            if self.vcos_u is not None:
+                s["vcos_u"] = self.vcos_u.data_ptr() + b * (h * D + 4) * 4
         self.seqs = torch.zeros(n * B.SEQ_DTYPE.itemsize, dtype=torch.uint8, device=dev)
         if with_outputs:
             hq = B.query_heads(p)
@@ -106,6 +111,8 @@ class LayerBatch:
         s["n_keep_prefix"] = grid_origin if n_keep_prefix is None else n_keep_prefix
         s["budget"], s["budget_num"], s["budget_den"] = budget, budget_num, budget_den
         s["status"], s["compacted"], s["pending_slot"], s["hole"] = 0, 0, -1, 0
+        if self.vcos_u is not None:
+            self.vcos_u[b].zero_()          # the cache was set by hand: the running state starts over
 
     # ---- device -> host, layout-independent views
     def k_host(self) -> np.ndarray:

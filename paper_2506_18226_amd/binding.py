@@ -15,7 +15,7 @@ import numpy as np
 from . import build as _build
 
 F32, BF16 = 0, 1
-SCORE_ATTN_MASS, SCORE_VCOS, SCORE_EXT_LARGEST, SCORE_EXT_SMALLEST = 0, 1, 2, 3
+SCORE_ATTN_MASS, SCORE_VCOS, SCORE_EXT_LARGEST, SCORE_EXT_SMALLEST, SCORE_VCOS_FUSED = 0, 1, 2, 3, 4
 FLAG_NO_COMPACT, FLAG_NO_ACCUMULATE, FLAG_PLAN_APPEND, FLAG_APPEND, FLAG_ADVANCE, FLAG_NEW_F32 = 1, 2, 4, 8, 16, 32
 SEQ_CACHE_FULL, SEQ_BAD_STATE, SEQ_SEL_OVERFLOW = 1, 2, 4
 MAX_CAP = 8192
@@ -42,14 +42,15 @@ class AdsaParams(C.Structure):
     ]
 
 
-# Mirror of `adsa_seq` (device struct array), 80 bytes per entry.
+# Mirror of `adsa_seq` (device struct array), 96 bytes per entry.
 SEQ_DTYPE = np.dtype([
     ("k", np.uint64), ("v", np.uint64), ("pos", np.uint64), ("score", np.uint64),
     ("n_res", np.int32), ("step", np.int32), ("grid_origin", np.int32), ("n_keep_prefix", np.int32),
     ("budget", np.int32), ("budget_num", np.int32), ("budget_den", np.int32), ("status", np.int32),
     ("compacted", np.int32), ("pending_slot", np.int32), ("hole", np.int32), ("reserved", np.int32),
+    ("vcos_u", np.uint64), ("reserved2", np.int64),
 ])
-assert SEQ_DTYPE.itemsize == 80
+assert SEQ_DTYPE.itemsize == 96
 
 
 class AdsaError(RuntimeError):
@@ -146,7 +147,9 @@ def make_params(*, n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_
 
 
 def score_rows(params: AdsaParams) -> int:
-    """Rows of adsa_seq.score: one per head for ATTN_MASS, else one."""
+    """Rows of adsa_seq.score: one per head for ATTN_MASS, two per head for VCOS_FUSED, else one."""
+    if params.score_mode == SCORE_VCOS_FUSED:
+        return 2 * params.n_heads
     return params.n_heads if params.score_mode == SCORE_ATTN_MASS else 1
 
 

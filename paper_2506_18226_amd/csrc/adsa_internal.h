@@ -28,7 +28,15 @@ struct AttendPlan {
 
 // Rows of adsa_seq.score: one accumulator per head for ATTN_MASS (the rank of a slot is their sum),
 // a single row otherwise.
-static inline int score_rows(const adsa_params& p) { return p.score_mode == ADSA_SCORE_ATTN_MASS ? p.n_heads : 1; }
+static inline int score_rows(const adsa_params& p) {
+  if (p.score_mode == ADSA_SCORE_VCOS_FUSED) return 2 * p.n_heads;    // per head: |v|^2 share, v.u share
+  return p.score_mode == ADSA_SCORE_ATTN_MASS ? p.n_heads : 1;
+}
+// Eq. 2-3 ranking in either form
+static inline bool is_vcos(const adsa_params& p) {
+  return p.score_mode == ADSA_SCORE_VCOS || p.score_mode == ADSA_SCORE_VCOS_FUSED;
+}
+constexpr int kVcosTags = 4;      // floats after u in adsa_seq.vcos_u: [0] 1 + step u belongs to, [1] 1 + step the score rows belong to
 
 // Workspace layout (byte offsets from a 256-byte aligned base).
 struct Workspace {
@@ -40,6 +48,8 @@ struct Workspace {
   size_t plan_off;         // int32 [n_seq][4]   compaction: old n_res, first moved slot, did, new n_res
   size_t vcos_off;         // float [n_seq][cap]   inverse V norms of the candidates (0 = not a candidate)
   size_t vcos_u_off;       // float [n_seq][ceil(cap/64)][n_heads*head_dim]   per-tile partial sums of v^
+  size_t vcos_s_off;       // float [n_seq][cap]   Eq. 3's S_i of the two-pass computation when score[] holds
+                           //                      the fused form's rows (ADSA_SCORE_VCOS_FUSED)
   size_t total;
   int lg_stride;           // sel_cap rounded up to a multiple of 4
 };
@@ -56,6 +66,10 @@ hipError_t launch_select(const adsa_params& p, adsa_seq* seqs, int32_t* sel_idx,
 hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction, char* ws,
                        const Workspace& w, hipStream_t st);
 int vcos_tiles(int cap);
+// ADSA_SCORE_VCOS_FUSED, after the eviction plan: u <- u - evicted row + the row that turns candidate next step
+// (or a fresh sum when u does not belong to this step)
+hipError_t launch_vcos_advance(const adsa_params& p, adsa_seq* seqs, hipStream_t st);
+size_t vcos_advance_lds_bytes(const adsa_params& p);
 hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
                          const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
                          void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,

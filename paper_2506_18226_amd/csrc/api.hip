@@ -12,14 +12,14 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 int validate_params(const adsa_params* p) {
   if (!p) return ADSA_ERR_NULL;
   if (p->dtype != ADSA_F32 && p->dtype != ADSA_BF16) return ADSA_ERR_DTYPE;
-  if (p->score_mode < ADSA_SCORE_ATTN_MASS || p->score_mode > ADSA_SCORE_EXT_SMALLEST) return ADSA_ERR_DTYPE;
+  if (p->score_mode < ADSA_SCORE_ATTN_MASS || p->score_mode > ADSA_SCORE_VCOS_FUSED) return ADSA_ERR_DTYPE;
   if (p->n_seq < 1 || p->n_seq > 65535) return ADSA_ERR_SHAPE;
   if (p->n_heads < 1 || p->n_heads > 256) return ADSA_ERR_SHAPE;
   if (p->head_dim != 64 && p->head_dim != 128) return ADSA_ERR_SHAPE;
   if (p->grid_h < 1 || p->grid_w < 1 || (long long)p->grid_h * p->grid_w > (1 << 24)) return ADSA_ERR_SHAPE;
   if (p->win_rows_back < 0 || p->win_col_radius < 0) return ADSA_ERR_SHAPE;
   if (p->sel_groups != 1) return ADSA_ERR_UNSUPPORTED;
-  if (p->score_mode == ADSA_SCORE_VCOS && (long long)p->n_heads * p->head_dim > 8192) return ADSA_ERR_UNSUPPORTED;
+  if (is_vcos(*p) && (long long)p->n_heads * p->head_dim > 8192) return ADSA_ERR_UNSUPPORTED;
   if (p->cap < 1 || p->cap > ADSA_MAX_CAP) return ADSA_ERR_CAPACITY;
   if (p->sel_cap < 1 || p->sel_cap > p->cap) return ADSA_ERR_CAPACITY;
   const long long eb = p->dtype == ADSA_F32 ? 4 : 2;
@@ -36,6 +36,12 @@ int validate_params(const adsa_params* p) {
   if (p->evict_policy < ADSA_EVICT_ROW_END || p->evict_policy > ADSA_EVICT_REUSE_SLOT) return ADSA_ERR_DTYPE;
   if (p->evict_policy != ADSA_EVICT_ROW_END && p->win_recent_m == 0) return ADSA_ERR_UNSUPPORTED;
   if (p->q_per_kv < 0 || p->q_per_kv > 16) return ADSA_ERR_SHAPE;
+  if (p->score_mode == ADSA_SCORE_VCOS_FUSED) {      // u lives in LDS four times; rows are per cache head
+    if (p->evict_policy != ADSA_EVICT_REUSE_SLOT || !head_major || p->kv_slot_stride >= p->kv_head_stride ||
+        p->q_per_kv > 1)
+      return ADSA_ERR_UNSUPPORTED;
+    if (vcos_advance_lds_bytes(*p) > 64 * 1024) return ADSA_ERR_UNSUPPORTED;
+  }
   if (p->q_per_kv > 1) {       // grouped queries run on the bf16 matrix cores, logits of one list in LDS
     if (p->dtype != ADSA_BF16) return ADSA_ERR_UNSUPPORTED;
     if (gqa_lds_bytes(*p, make_attend_plan(*p).waves) > kGqaMaxLds) return ADSA_ERR_UNSUPPORTED;
@@ -172,10 +178,11 @@ int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map, uint32
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
   if (rc) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  if (p->score_mode == ADSA_SCORE_VCOS &&
-      launch_vcos(*p, seqs, true, (char*)workspace, w, st) != hipSuccess)
+  if (is_vcos(*p) && launch_vcos(*p, seqs, true, (char*)workspace, w, st) != hipSuccess)
     return ADSA_ERR_LAUNCH;
   if (launch_compact(*p, seqs, keep_map, (char*)workspace, w, (flags & ADSA_FLAG_ADVANCE) != 0, st) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
+  if (p->score_mode == ADSA_SCORE_VCOS_FUSED && launch_vcos_advance(*p, seqs, st) != hipSuccess)
     return ADSA_ERR_LAUNCH;
   return ADSA_OK;
 }
@@ -195,12 +202,14 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
   if (rc) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char* ws = (char*)workspace;
-  const bool vcos = p->score_mode == ADSA_SCORE_VCOS;
+  const bool vcos = is_vcos(*p);
   const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS;
   const bool streaming = p->evict_policy != ADSA_EVICT_ROW_END;
   if (streaming && compact) {          // Section 4.2 as written: make room BEFORE the insertion
     if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
     if (launch_compact(*p, seqs, keep_map, ws, w, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+    if (p->score_mode == ADSA_SCORE_VCOS_FUSED && launch_vcos_advance(*p, seqs, st) != hipSuccess)
+      return ADSA_ERR_LAUNCH;
   }
   if (vcos && !streaming && launch_vcos(*p, seqs, false, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
   if (launch_select(*p, seqs, sel_idx, sel_cnt, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;

@@ -14,6 +14,9 @@
 //    heads' rows of score[]: no workgroup ever talks to another one.
 //    With several chunks, each writes a partial and the scaled logits to the workspace and the
 //    LAST one to arrive (an arrival counter, nothing waits) merges them and updates the scores.
+//    VF (ADSA_SCORE_VCOS_FUSED): every V row that streams through also yields its head's share of |v|^2
+//    and of v.u (u = running sum of the candidates' normalised V, Eq. 2-3), stored per (head, slot): the
+//    next eviction ranks from them instead of re-reading V.
 #include <hip/hip_ext.h>
 
 #include "adsa_internal.h"
@@ -116,6 +119,7 @@ struct AttendArgs {
   int n_heads, n_hg, sel_cap, lg_stride, chunk_max, cap;
   int accumulate, append, advance;     // advance: step += 1 at the end
   int new_f32;                         // k_new / v_new are fp32 although the cache is bf16: round as they enter
+  int head_dim, vcos_fused;
   long long slot_stride_b, head_stride_b;
   float scale_log2;     // softmax scale * log2(e)
 };
@@ -159,7 +163,21 @@ __device__ __forceinline__ void add_mass(float* score, int cap, int row0, const 
   }
 }
 
-template <int EB, int D, int HT, int U, int NW>
+// Last act of a launch on a sequence (one thread): VF marks the score rows as belonging to the next
+// step's eviction if u did (tag 1 + step, kept as floats behind u), then the step may advance.
+template <bool VF>
+__device__ __forceinline__ void finish_step(adsa_seq& sq, const AttendArgs& A) {
+  if constexpr (VF) {
+    if (sq.vcos_u) {
+      float* tags = sq.vcos_u + (size_t)A.n_heads * A.head_dim;
+      const float want = (float)(sq.step + 2);
+      tags[1] = tags[0] == want ? want : 0.0f;
+    }
+  }
+  if (A.advance) sq.step = sq.step + 1;
+}
+
+template <int EB, int D, int HT, int U, int NW, bool VF>
 __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
   constexpr int kAttThreads = NW * kWave, kAttWaves = NW;   // waves of the workgroup share one token chunk
   constexpr int EPL = Elems<EB>::N;                 // elements per lane
@@ -280,6 +298,18 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
     *reinterpret_cast<uint4*>(vb + off) = nv;
   }
 
+  // VF: this lane's columns of u for its head, and the two score rows of the head
+  float uf[EPL];
+  float* vrows = nullptr;
+  bool vf_on = false;
+  if constexpr (VF) {
+    const float* up = sq.vcos_u;
+    vf_on = up != nullptr && head_ok;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) uf[e] = vf_on ? up[(size_t)head_c * D + dl * EPL + e] : 0.0f;
+    vrows = score + (size_t)(2 * head_c) * A.cap;
+  }
+
   float m = -INFINITY, l = 0.0f, acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.0f;
@@ -333,6 +363,14 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
         l += pr;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] = fmaf(pr, vf[e], acc[e]);
+        if constexpr (VF) {                         // Eq. 2-3 bookkeeping of this row: |v_h|^2 and v_h . u_h
+          float dv = 0.0f, sv = 0.0f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) { dv = fmaf(vf[e], uf[e], dv); sv = fmaf(vf[e], vf[e], sv); }
+          dv = row_sum<LPR>(dv);
+          sv = row_sum<LPR>(sv);
+          if (dl == 0 && tl[u] < len) { s_logit[tl[u]] = sv; s_logit[A.chunk_max + tl[u]] = dv; }
+        }
       }
       m = m_new;
     }
@@ -435,6 +473,15 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
     }
   }
 
+  if constexpr (VF) {
+    // |v_h|^2 and v_h.u_h of this chunk's tokens, left in LDS by the loop (the barrier above ordered them)
+    if (vf_on)
+      for (int j = tid; j < len; j += kAttThreads) {
+        const int slot = min(max(idx[t_begin + j], 0), A.cap - 1);
+        vrows[slot] = s_logit[j];
+        vrows[A.cap + slot] = s_logit[A.chunk_max + j];
+      }
+  }
   if (direct) {
     // -------- per-head attention mass: score[head][slot] += p, from the logits still in LDS
     if (A.accumulate) {
@@ -462,7 +509,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
         });
       }
     }
-    if (hg == 0 && tid == 0 && A.advance) sq.step = sq.step + 1;   // no other workgroup reads step
+    if (hg == 0 && tid == 0) finish_step<VF>(sq, A);             // no other workgroup reads step
     return;
   }
 
@@ -524,27 +571,34 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
       *slot = min(max(idx[j], 0), cap - 1); *z = ld_dev(lg + (size_t)*sb * lgs + j);
     });
   }
-  if (hg == 0 && tid == 0 && A.advance) sq.step = sq.step + 1;
+  if (hg == 0 && tid == 0) finish_step<VF>(sq, A);
 }
 
-template <int EB, int D, int HT, int NW>
+template <int EB, int D, int HT, int NW, bool VF = false>
 hipError_t launch_attend_w(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
   // row pairs in flight per lane; 8 was measured slower (register pressure).  A 16-wave workgroup has
   // 128 registers per lane: 2 pairs fit without spilling, and its 1024 lanes keep enough in flight
   constexpr int U = NW == 16 ? 2 : 4;
-  const size_t lds = (size_t)HT * plan.chunk_max * sizeof(float);
+  const size_t lds = (size_t)(VF ? 2 : HT) * plan.chunk_max * sizeof(float);
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U, NW>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
+    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
   else
-    hipLaunchKernelGGL((k_attend<EB, D, HT, U, NW>), grid, dim3(NW * kWave), lds, st, A);
+    hipLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF>), grid, dim3(NW * kWave), lds, st, A);
   return hipGetLastError();
 }
 
 template <int EB, int D, int HT>
 hipError_t launch_attend_t(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
+  if constexpr (HT == 1) {
+    if (A.vcos_fused) {
+      if (plan.waves == 16) return launch_attend_w<EB, D, HT, 16, true>(A, plan, n_seq, st, ev_start, ev_stop);
+      if (plan.waves == 8) return launch_attend_w<EB, D, HT, 8, true>(A, plan, n_seq, st, ev_start, ev_stop);
+      return launch_attend_w<EB, D, HT, 4, true>(A, plan, n_seq, st, ev_start, ev_stop);
+    }
+  }
   if (plan.waves == 16) return launch_attend_w<EB, D, HT, 16>(A, plan, n_seq, st, ev_start, ev_stop);
   if (plan.waves == 8) return launch_attend_w<EB, D, HT, 8>(A, plan, n_seq, st, ev_start, ev_stop);
   return launch_attend_w<EB, D, HT, 4>(A, plan, n_seq, st, ev_start, ev_stop);
@@ -590,7 +644,8 @@ AttendPlan make_attend_plan(const adsa_params& p) {
     if (nc > kMaxChunks) nc = kMaxChunks;
   }
   // the logits tile [heads_per_group][chunk] must fit in LDS next to the merge buffers
-  while (nc < kMaxChunks && (size_t)a.heads_per_group * ((p.sel_cap + nc - 1) / nc + 1) * sizeof(float) > 40 * 1024) ++nc;
+  const int lds_rows = p.score_mode == ADSA_SCORE_VCOS_FUSED ? 2 : a.heads_per_group;    // floats of LDS per token
+  while (nc < kMaxChunks && (size_t)lds_rows * ((p.sel_cap + nc - 1) / nc + 1) * sizeof(float) > 40 * 1024) ++nc;
   a.n_chunks = nc;
   a.chunk_max = (p.sel_cap + nc - 1) / nc + 1;
   return a;
@@ -616,10 +671,13 @@ Workspace make_workspace(const adsa_params& p, const AttendPlan& plan) {
   off = align_up(off + sizeof(int32_t) * (size_t)p.n_seq * 4, 256);
   w.vcos_off = off;
   w.vcos_u_off = off;
-  if (p.score_mode == ADSA_SCORE_VCOS) {
+  w.vcos_s_off = off;
+  if (is_vcos(p)) {
     off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.cap, 256);
     w.vcos_u_off = off;
     off = align_up(off + sizeof(float) * (size_t)p.n_seq * vcos_tiles(p.cap) * p.n_heads * p.head_dim, 256);
+    w.vcos_s_off = off;
+    if (p.score_mode == ADSA_SCORE_VCOS_FUSED) off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.cap, 256);
   }
   w.total = off;
   return w;
@@ -650,6 +708,7 @@ hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq*
   A.chunk_max = plan.chunk_max; A.cap = p.cap;
   A.accumulate = accumulate ? 1 : 0; A.append = append ? 1 : 0; A.advance = advance ? 1 : 0;
   A.new_f32 = (new_f32 && append) ? 1 : 0;
+  A.head_dim = p.head_dim; A.vcos_fused = p.score_mode == ADSA_SCORE_VCOS_FUSED ? 1 : 0;
   const int eb = elem_bytes(p);
   A.slot_stride_b = (long long)p.kv_slot_stride * eb;
   A.head_stride_b = (long long)p.kv_head_stride * eb;

@@ -190,6 +190,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   // ---- Eq. 1: partition, keys into LDS
   const QueryCell cell = make_query_cell(sq, s, L.grid_w, L.R, L.w, L.recent_m);
   const bool largest = keep_largest_of(L.score_mode);
+  const bool ranked = L.evict_policy == ADSA_EVICT_ROW_END;
   uint32_t my_cand = 0;
   for (int i = tid; i < n; i += kSelThreads) {
     const bool planned = i == slot_new;             // the slot the query token will occupy
@@ -197,7 +198,8 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
     const int c = (planned || freed) ? 0 : select_class(cell, sq.pos[i]);
     if (c < 0) s_bad = 1;
     cls[i] = freed ? kSkip : c == 1 ? kCand : kFixed;
-    key[i] = order_key(planned ? 0.0f : rank_value(sq.score, L.score_rows, L.cap, i), largest);
+    // (evict-one-when-full policies attend every candidate: their rank is never looked at)
+    key[i] = order_key((planned || !ranked) ? 0.0f : rank_value(sq.score, L.score_rows, L.cap, i), largest);
     my_cand += (c == 1);
   }
   uint32_t n_cand;
@@ -258,7 +260,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
 // plan[b] = { old n_res, first slot that moves, did compact, new n_res }
 __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, adsa_seq* seqs,
                                                              int32_t* keep_map, int32_t* plan,
-                                                             int advance_step) {
+                                                             int advance_step, const float* vcos_s) {
   __shared__ RankShared sh;
   extern __shared__ uint32_t s_rank_dyn[];
   uint32_t* key = s_rank_dyn;                                  // [cap] keys, later the keep map
@@ -288,11 +290,37 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
     // streaming: the partition of the incoming query (its local region must survive)
     const int c = streaming ? (select_class(cell, sq.pos[i]) == 1 ? 1 : 0) : evict_class(cell, sq.pos[i]);
     cls[i] = c == 1 ? kCand : kFixed;
-    key[i] = order_key(rank_value(sq.score, L.score_rows, L.cap, i), largest);
+    key[i] = L.score_mode == ADSA_SCORE_VCOS_FUSED ? 0u      // (keys of the candidates follow once N is known)
+                                                   : order_key(rank_value(sq.score, L.score_rows, L.cap, i), largest);
     my_rest += (c == 1);
   }
   uint32_t n_rest;
   block_excl_scan(sh, my_rest, &n_rest);
+  if (L.score_mode == ADSA_SCORE_VCOS_FUSED) {
+    // Eq. 3 from what the last attention launch left per (head, slot): S_i = (v^_i.u - v^_i.v^_i)/(N-1) with
+    // |v_i|^2 and v_i.u summed over the heads' rows (ascending).  If those rows do not belong to this
+    // step, the two-pass computation has just written S_i to the workspace instead.
+    const float* tags = sq.vcos_u ? sq.vcos_u + (size_t)L.n_heads * L.head_dim : nullptr;
+    const bool rows_ok = tags && tags[1] == (float)(s + 1);
+    const float inv_nm1 = n_rest > 1 ? 1.0f / (float)(n_rest - 1) : 0.0f;
+    for (int i = tid; i < n; i += kSelThreads) {
+      if (cls[i] != kCand) continue;
+      float S;
+      if (rows_ok) {
+        float ss = 0.0f, dot = 0.0f;
+        for (int hh = 0; hh < L.n_heads; ++hh) {
+          ss += sq.score[(size_t)(2 * hh) * L.cap + i];
+          dot += sq.score[(size_t)(2 * hh + 1) * L.cap + i];
+        }
+        const float inv = 1.0f / fmaxf(sqrtf(ss), 1e-8f);
+        S = (dot * inv - ss * inv * inv) * inv_nm1;
+      } else {
+        S = vcos_s[(size_t)b * L.cap + i];
+      }
+      key[i] = order_key(S, false);
+    }
+    __syncthreads();
+  }
   if (reuse) {
     // Evict the candidate ranked last -- smallest key, among equals the newest position -- and leave
     // everything where it is: the freed slot goes to the incoming token.
@@ -458,8 +486,9 @@ hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_ma
                           const Workspace& w, bool advance_step, hipStream_t st) {
   int32_t* plan = reinterpret_cast<int32_t*>(ws + w.plan_off);
   LaunchShape L = shape_of(p);
+  const float* vcos_s = p.score_mode == ADSA_SCORE_VCOS_FUSED ? reinterpret_cast<const float*>(ws + w.vcos_s_off) : nullptr;
   hipLaunchKernelGGL(k_compact_plan, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, L, seqs,
-                     keep_map, plan, advance_step ? 1 : 0);
+                     keep_map, plan, advance_step ? 1 : 0, vcos_s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.evict_policy == ADSA_EVICT_REUSE_SLOT) return e;     // slot reuse moves no row
   // one workgroup per 128-byte column slice of a head row (whole head row when it is narrower)

@@ -28,6 +28,7 @@ struct VcosArgs {
   adsa_seq* seqs;
   float* inv_norm;      // [n_seq][cap]
   float* u_part;        // [n_seq][n_tiles][dim]
+  float* s_out;         // [n_seq][cap] where S_i goes when score[] holds the fused form's rows, else NULL
   int n_heads, head_dim, elem_bytes, cap, n_tiles;
   int grid_h, grid_w, R, w, for_compaction, recent_m, evict_policy;
   long long slot_stride_b, head_stride_b;
@@ -50,6 +51,8 @@ __device__ __forceinline__ bool vcos_active(const VcosArgs& A, const adsa_seq& s
   if (sq.step > A.grid_h * A.grid_w) return false;
   if (!A.for_compaction) return true;
   if (A.evict_policy == ADSA_EVICT_REUSE_SLOT && sq.hole != 0) return false;     // room was made already
+  if (A.s_out && sq.vcos_u && sq.vcos_u[A.n_heads * A.head_dim + 1] == (float)(sq.step + 1))
+    return false;                                       // the attention launch left this step's numbers
   if (A.evict_policy != ADSA_EVICT_ROW_END) return sq.step >= 1 && sq.n_res == A.cap;
   return is_row_end(sq.step, A.grid_h, A.grid_w);
 }
@@ -168,11 +171,118 @@ __global__ __launch_bounds__(kVcThreads) void k_vcos_score(VcosArgs A) {
     // remove the i == j term (1 for a normal row, 0 for a zero row) and average over the others
     const float self = ss * inv * inv;
     const float S = N > 1 ? (dot * inv - self) / (float)(N - 1) : 0.0f;
-    if (lane == 0) sq.score[i] = S;
+    if (lane == 0) {
+      if (A.s_out) A.s_out[(size_t)b * A.cap + i] = S;
+      else sq.score[i] = S;
+    }
   }
 }
 
+// ADSA_SCORE_VCOS_FUSED: bring u to the candidate set of the NEXT step, after this step's eviction plan and
+// before its attention launch (which takes every row's dot product with u).  One workgroup per sequence.
+// If u belongs to this step: subtract the evicted row, add the rows that turn from local to candidate
+// (normally the one token that leaves the 1-D window).  Otherwise: a fresh sum over the next step's
+// candidates.  Wave w handles slots w, w+4, ... in ascending order into its own LDS copy of u; the copies
+// are added in wave order, so the result does not depend on timing.
+struct AdvArgs {
+  adsa_seq* seqs;
+  int n_heads, head_dim, elem_bytes, cap, grid_h, grid_w, R, w, recent_m;
+  long long slot_stride_b, head_stride_b;
+};
+
+__global__ __launch_bounds__(kVcThreads) void k_vcos_advance(AdvArgs A) {
+  extern __shared__ float s_u[];                        // [kVcWaves][dim]
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  adsa_seq& sq = A.seqs[b];
+  float* U = sq.vcos_u;
+  if (sq.step < 0 || sq.status != 0 || U == nullptr) return;
+  const int s = sq.step, n = sq.n_res, dim = A.n_heads * A.head_dim, groups = dim / 4;
+  if (n < 0 || n > A.cap) return;
+  float* tags = U + dim;
+  if (s + 1 > A.grid_h * A.grid_w) {                    // no later step evicts
+    if (tid == 0) tags[0] = 0.0f;
+    return;
+  }
+  const bool incremental = tags[0] == (float)(s + 1);   // u is the sum over THIS step's candidates
+  const int victim = sq.hole - 1;                       // slot freed by this step's eviction, or -1
+  const QueryCell now = make_query_cell(sq, s, A.grid_w, A.R, A.w, A.recent_m);
+  const QueryCell next = make_query_cell(sq, s + 1, A.grid_w, A.R, A.w, A.recent_m);
+  for (int c = tid; c < dim; c += kVcThreads) {
+    s_u[c] = incremental ? U[c] : 0.0f;
+#pragma unroll
+    for (int w = 1; w < kVcWaves; ++w) s_u[(size_t)w * dim + c] = 0.0f;
+  }
+  __syncthreads();
+  // what happens to each slot: +1 joins u, -1 leaves it, 0 nothing (classified by all threads at once)
+  signed char* s_sign = reinterpret_cast<signed char*>(s_u + (size_t)kVcWaves * dim);   // [cap]
+  for (int i = tid; i < n; i += kVcThreads) {
+    const int pos = sq.pos[i];
+    const bool cand_next = select_class(next, pos) == 1;
+    int sign = 0;
+    if (incremental) {
+      const bool cand_now = select_class(now, pos) == 1;
+      if (i == victim) sign = cand_now ? -1 : 0;
+      else if (cand_next && !cand_now) sign = 1;
+    } else if (cand_next && i != victim) sign = 1;
+    s_sign[i] = (signed char)sign;
+  }
+  __syncthreads();
+  VcosArgs L;                                           // for load4()
+  L.head_dim = A.head_dim; L.elem_bytes = A.elem_bytes; L.slot_stride_b = A.slot_stride_b; L.head_stride_b = A.head_stride_b;
+  const char* vbase = reinterpret_cast<const char*>(sq.v);
+  float* mine = s_u + (size_t)wave * dim;
+  for (int base = 0; base < n; base += kWave) {         // wave w owns slots w, w+4, ...: ascending, fixed order
+    const int my = base + lane;
+    const int sg = (my < n && (my % kVcWaves) == wave) ? (int)s_sign[my] : 0;
+    unsigned long long todo = __ballot(sg != 0);
+    while (todo) {
+      const int src = __ffsll((long long)todo) - 1;
+      todo &= todo - 1;
+      const int i = base + src;
+      const float sign = (float)__shfl(sg, src, kWave);
+      float ss = 0.0f;
+      for (int g = lane; g < groups; g += kWave) {
+        const float4 x = load4(L, vbase, i, g);
+        ss = fmaf(x.x, x.x, ss); ss = fmaf(x.y, x.y, ss); ss = fmaf(x.z, x.z, ss); ss = fmaf(x.w, x.w, ss);
+      }
+      ss = wave_sum(ss);
+      const float f = sign / fmaxf(sqrtf(ss), 1e-8f);
+      for (int g = lane; g < groups; g += kWave) {
+        const float4 x = load4(L, vbase, i, g);
+        float4 t = reinterpret_cast<float4*>(mine)[g];
+        t.x = fmaf(x.x, f, t.x); t.y = fmaf(x.y, f, t.y); t.z = fmaf(x.z, f, t.z); t.w = fmaf(x.w, f, t.w);
+        reinterpret_cast<float4*>(mine)[g] = t;
+      }
+    }
+  }
+  __syncthreads();
+  for (int c = tid; c < dim; c += kVcThreads) {
+    float t = s_u[c];
+#pragma unroll
+    for (int w = 1; w < kVcWaves; ++w) t += s_u[(size_t)w * dim + c];
+    U[c] = t;
+  }
+  if (tid == 0) tags[0] = (float)(s + 2);               // u now belongs to step s + 1
+}
+
 }  // namespace
+
+// four copies of u and one byte per slot
+size_t vcos_advance_lds_bytes(const adsa_params& p) {
+  return sizeof(float) * (size_t)p.n_heads * p.head_dim * kVcWaves + (((size_t)p.cap + 15) / 16) * 16;
+}
+
+hipError_t launch_vcos_advance(const adsa_params& p, adsa_seq* seqs, hipStream_t st) {
+  const size_t lds = vcos_advance_lds_bytes(p);
+  if (lds > 64 * 1024) return hipErrorInvalidValue;
+  AdvArgs A;
+  A.seqs = seqs; A.n_heads = p.n_heads; A.head_dim = p.head_dim; A.elem_bytes = elem_bytes(p); A.cap = p.cap;
+  A.grid_h = p.grid_h; A.grid_w = p.grid_w; A.R = p.win_rows_back; A.w = p.win_col_radius; A.recent_m = p.win_recent_m;
+  A.slot_stride_b = (long long)p.kv_slot_stride * A.elem_bytes;
+  A.head_stride_b = (long long)p.kv_head_stride * A.elem_bytes;
+  hipLaunchKernelGGL(k_vcos_advance, dim3(p.n_seq), dim3(kVcThreads), lds, st, A);
+  return hipGetLastError();
+}
 
 hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction, char* ws,
                        const Workspace& w, hipStream_t st) {
@@ -182,6 +292,7 @@ hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction
   A.seqs_c = seqs; A.seqs = seqs;
   A.inv_norm = reinterpret_cast<float*>(ws + w.vcos_off);
   A.u_part = reinterpret_cast<float*>(ws + w.vcos_u_off);
+  A.s_out = p.score_mode == ADSA_SCORE_VCOS_FUSED ? reinterpret_cast<float*>(ws + w.vcos_s_off) : nullptr;
   A.n_heads = p.n_heads; A.head_dim = p.head_dim; A.elem_bytes = elem_bytes(p); A.cap = p.cap;
   A.n_tiles = (p.cap + kVcTile - 1) / kVcTile;
   A.grid_h = p.grid_h; A.grid_w = p.grid_w; A.R = p.win_rows_back; A.w = p.win_col_radius;

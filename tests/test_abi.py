@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_mirrors_match_the_header():
     assert C.sizeof(B.AdsaParams) == 12 * 4 + 2 * 8 + 4 + 3 * 4
-    assert B.SEQ_DTYPE.itemsize == 80
+    assert B.SEQ_DTYPE.itemsize == 96 and B.SEQ_DTYPE.fields["vcos_u"][1] == 80
     assert B.SEQ_DTYPE.fields["n_res"][1] == 32 and B.SEQ_DTYPE.fields["status"][1] == 60
     assert B.SEQ_DTYPE.fields["pending_slot"][1] == 68 and B.SEQ_DTYPE.fields["hole"][1] == 72
 

@@ -741,17 +741,21 @@ def test_streaming_cache_evict_one_when_full(mode, layout):
     assert n_evictions == 5
 
 
-@pytest.mark.parametrize("layout", LAYOUTS)
-@pytest.mark.parametrize("mode", [B.SCORE_VCOS, B.SCORE_ATTN_MASS])
+@pytest.mark.parametrize("mode,layout", [(B.SCORE_VCOS, "head_major"), (B.SCORE_VCOS, "slot_major"),
+                                         (B.SCORE_ATTN_MASS, "head_major"), (B.SCORE_ATTN_MASS, "slot_major"),
+                                         (B.SCORE_VCOS_FUSED, "head_major")])
 def test_streaming_cache_slot_reuse_free_running(mode, layout):
     """ADSA_EVICT_REUSE_SLOT: same rule and same victim as the order-preserving form, but the incoming
     token takes the evicted slot and nothing moves.  Free-running over a whole trajectory (59 evictions)
     against the free-running oracle: the caches must hold the same tokens -- compared by position, since
-    slot order differs -- with identical rows, and every step's output must match."""
+    slot order differs -- with identical rows, and every step's output must match.
+    ADSA_SCORE_VCOS_FUSED is the same ranking (oracle: VCOS) computed inside the attention launch from the
+    running sum u; its first eviction falls back to the two-pass form, all later ones use the fused numbers."""
+    omode = B.SCORE_VCOS if mode == B.SCORE_VCOS_FUSED else mode
     P, H, W, m, cap = 5, 8, 8, 6, 30
-    wl = WL.get_workload("xl", n_seq=1, n_heads=4, head_dim=64, grid_h=H, grid_w=W, prefix_len=P, score_mode=mode)
+    wl = WL.get_workload("xl", n_seq=1, n_heads=4, head_dim=64, grid_h=H, grid_w=W, prefix_len=P, score_mode=omode)
     cfg = oracle.make_cfg(n_heads=4, head_dim=64, grid_h=H, grid_w=W, win_rows_back=0, win_col_radius=0,
-                          grid_origin=P, budget=10 ** 6, score_mode=mode, cap=cap, win_recent_m=m, evict_when_full=1)
+                          grid_origin=P, budget=10 ** 6, score_mode=omode, cap=cap, win_recent_m=m, evict_when_full=1)
     q, k, v = WL.gen_tokens(wl, 0, 0, prefix_len=P)
     st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
     params = B.make_params(n_seq=1, n_heads=4, head_dim=64, grid_h=H, grid_w=W, win_rows_back=0,
@@ -790,6 +794,15 @@ def test_streaming_cache_slot_reuse_free_running(mode, layout):
         if ref["compacted"]:
             km = batch.keep_map.cpu().numpy()[0, :cap]
             assert (km < 0).sum() == 1 and np.array_equal(km[km >= 0], np.nonzero(km >= 0)[0]), tag
+        if mode == B.SCORE_VCOS_FUSED and s < H * W:
+            # the running state: tagged for the next step, and u = sum of the next step's candidates' unit V
+            state = batch.vcos_u.cpu().numpy()[0]
+            dim = 4 * 64
+            assert state[dim] == s + 2 and state[dim + 1] == s + 2, tag
+            cls = oracle.classify(cfg, st.pos[:n], s + 1)
+            rows = st.V[:n][cls == oracle.CANDIDATE].reshape(-1, dim).astype(np.float64)
+            want = (rows / np.maximum(np.linalg.norm(rows, axis=1, keepdims=True), 1e-8)).sum(axis=0) if len(rows) else np.zeros(dim)
+            assert np.allclose(state[:dim], want, atol=2e-5), tag
     assert n_evictions >= 21
 
 
