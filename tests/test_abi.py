@@ -88,6 +88,19 @@ def test_grouped_query_parameters(lib):
     assert B.adsa_workspace_bytes(good(q_per_kv=16, **big)) == 0          # 17 x 8.2k x 4 B: does not
 
 
+def test_fused_vcos_parameters(lib):
+    """ADSA_SCORE_VCOS_FUSED: slot-reuse policy, [head][slot][D] caches, one query head per cache head."""
+    ok = dict(score_mode=B.SCORE_VCOS_FUSED, evict_policy=B.EVICT_REUSE_SLOT, win_recent_m=9, layout="head_major")
+    assert B.adsa_workspace_bytes(good(**ok)) > 0
+    assert B.score_rows(good(**ok)) == 2 * good().n_heads
+    for bad in (dict(ok, layout="slot_major"), dict(ok, evict_policy=B.EVICT_WHEN_FULL),
+                dict(ok, evict_policy=B.EVICT_ROW_END, win_recent_m=0), dict(ok, q_per_kv=2),
+                dict(ok, n_heads=64, head_dim=64, cap=128)):          # 16 * h * D bytes of LDS do not fit
+        p = good(**bad)
+        assert B.adsa_workspace_bytes(p) == 0, bad
+        assert lib.adsa_compact(C.byref(p), 0x1000, 0x1000, 0, 0x1000, 1 << 30, None) == -8, bad
+
+
 def test_null_alignment_and_workspace_errors(lib):
     p = good()
     ok = 0x1000
