@@ -466,6 +466,11 @@ def vcos_close(gpu, ref):
     ("tiny", dict(n_heads=4, head_dim=64, grid_h=8, grid_w=8, prefix_len=6), 9, [0, 1, 9, 24, 25, 40, 63, 64]),
     ("xl", dict(n_seq=1, n_heads=20, grid_h=6, grid_w=12, prefix_len=17, budget_num=0, budget_den=0), 21, [13, 36, 37, 60, 72]),
     ("long", dict(n_seq=1, n_heads=3, grid_h=5, grid_w=16, prefix_len=9), 12, [17, 48, 64, 80]),
+    # wide concatenated V rows: 1792, 4096 and 8192 columns (7, 16 and 32 column groups per lane; the
+    # widest needs more LDS than a launch gets by default)
+    ("tiny", dict(n_heads=28, head_dim=64, grid_h=4, grid_w=6, prefix_len=3), 5, [7, 12, 13, 24]),
+    ("long", dict(n_seq=1, n_heads=32, head_dim=128, grid_h=4, grid_w=6, prefix_len=3), 5, [7, 12, 13, 24]),
+    ("long", dict(n_seq=1, n_heads=64, head_dim=128, grid_h=4, grid_w=6, prefix_len=3), 5, [12, 13, 24]),
 ])
 def test_vcos_step_teacher_forced(name, over, budget, steps, layout):
     """The paper's own ranking: mean pairwise V-cosine over the candidates (Eq. 2-3), keep the K
