@@ -376,12 +376,10 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
 template <int D, int NW>
 hipError_t launch_gqa_w(const GqaArgs& A, int n_seq, size_t lds, hipStream_t st, hipEvent_t ev_start,
                         hipEvent_t ev_stop) {
-  static size_t lds_allowed = 64 * 1024;       // above the default limit: raise it once per kernel and size
-  if (lds > lds_allowed) {
+  if (lds > 64 * 1024) {       // above the default per-launch limit (long lists only): ask for it, per device
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<D, NW>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    lds_allowed = lds;
   }
   dim3 grid(A.n_heads, n_seq);
   if (ev_start && ev_stop)

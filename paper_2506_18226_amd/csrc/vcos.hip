@@ -307,13 +307,11 @@ hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction
   else if (gpl <= 8) hipLaunchKernelGGL(k_vcos_norm_usum<8>, grid, dim3(kVcThreads), lds1, st, A);
   else if (gpl <= 16) hipLaunchKernelGGL(k_vcos_norm_usum<16>, grid, dim3(kVcThreads), lds1, st, A);
   else {
-    static bool raised = false;                           // 64..128 KB of LDS: above the default limit
-    if (!raised) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_vcos_norm_usum<32>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)(sizeof(float) * kVcMaxDim * kVcWaves)) != hipSuccess)
-        return hipErrorInvalidValue;
-      raised = true;
-    }
+    // 64..128 KB of LDS: above the default per-launch limit
+    if (lds1 > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_vcos_norm_usum<32>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1) != hipSuccess)
+      return hipErrorInvalidValue;
     hipLaunchKernelGGL(k_vcos_norm_usum<32>, grid, dim3(kVcThreads), lds1, st, A);
   }
   hipError_t e = hipGetLastError();
