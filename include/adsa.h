@@ -73,7 +73,8 @@ typedef enum {
                                   the running sum u of the candidates' normalised V vectors (adsa_seq.vcos_u,
                                   kept up to date by adsa_compact: minus the evicted row, plus the row that
                                   leaves the local window next).  The next eviction ranks from those numbers.
-                                  Needs [head][slot][D] caches and q_per_kv <= 1.  Whenever the running state
+                                  Needs [head][slot][D] caches, q_per_kv <= 1 and 16*n_heads*head_dim + cap
+                                  bytes of LDS <= 64 KB (else ADSA_ERR_UNSUPPORTED).  Whenever the running state
                                   does not belong to the step at hand (first use, a cache edited by the
                                   caller) the call falls back to the two-pass computation, so results never
                                   depend on it being warm */
@@ -150,7 +151,8 @@ typedef struct adsa_params {
 typedef struct adsa_seq {
   void*    k;                  /* this sequence's K cache (dtype elements) */
   void*    v;                  /* this sequence's V cache */
-  int32_t* pos;                /* [cap] absolute position of each resident slot, strictly ascending */
+  int32_t* pos;                /* [cap] absolute position of each resident slot, strictly ascending (under
+                                  ADSA_EVICT_REUSE_SLOT only until the first eviction; always distinct) */
   float*   score;              /* [score_rows][cap] ranking score of each resident slot: the rank of slot i
                                   is the sum over rows (ascending, fp32) of score[row][i].
                                   ADSA_SCORE_ATTN_MASS: score_rows = n_heads, one accumulator per head
