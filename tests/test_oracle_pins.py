@@ -18,6 +18,18 @@ from paper_2506_18226_amd import workloads as WL
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
+def table_context_lengths():
+    """(grid side, kept context, printed reduction) rows of tests/golden/tables_context_lengths.txt."""
+    rows = []
+    for line in open(os.path.join(GOLDEN, "tables_context_lengths.txt")):
+        if line.strip() and not line.startswith("#"):
+            side, full, kept, pct = line.split()
+            assert int(full) == int(side) ** 2
+            rows.append((int(side), int(kept), pct))
+    assert len(rows) == 5
+    return rows
+
+
 def tiny_cfg(**kw):
     base = dict(n_heads=2, head_dim=8, grid_h=3, grid_w=4, win_rows_back=1, win_col_radius=1,
                 grid_origin=2, budget=0)
@@ -323,8 +335,7 @@ def test_context_bookkeeping_reproduces_table_1_and_2_totals():
     (-33.3 %), 512 / 640 / 768 of 1024 (-50 / -37.5 / -25 %).  The paper's window is the most
     recent m tokens, so use w >= W-1; at the last decode step the attended count must hit the
     total exactly.  (The split into n, K, m is not given in the paper: only the sum is pinned.)"""
-    cases = [(24, 256, "55.6"), (24, 384, "33.3"), (32, 512, "50.0"), (32, 640, "37.5"), (32, 768, "25.0")]
-    for W, total, pct in cases:
+    for W, total, pct in table_context_lengths():
         n_prefix = W                                    # pin the first image row as the prefix
         cfg = oracle.make_cfg(n_heads=1, head_dim=4, grid_h=W, grid_w=W, win_rows_back=1,
                               win_col_radius=W - 1, grid_origin=0, n_keep_prefix=n_prefix,
@@ -500,7 +511,7 @@ def test_streaming_cache_reproduces_the_tables_cache_lengths():
     """Tables 1-2: KV cache = context = 384 / 256 of 576 and 768 / 640 / 512 of 1024 image tokens
     (-33.3, -55.6, -25, -37.5, -50 %).  The paper's cache 'initialises with only half the length':
     capacity is the only knob; run the policy (tiny head size) and read the final cache length."""
-    for W, cap, pct in [(24, 384, "33.3"), (24, 256, "55.6"), (32, 768, "25.0"), (32, 640, "37.5"), (32, 512, "50.0")]:
+    for W, cap, pct in table_context_lengths():
         cfg = oracle.make_cfg(n_heads=1, head_dim=2, grid_h=W, grid_w=W, win_rows_back=0, win_col_radius=0,
                               grid_origin=0, n_keep_prefix=8, budget=10 ** 6, score_mode=WL.SCORE_EXT_SMALLEST,
                               cap=cap, win_recent_m=W + 2, evict_when_full=1)
