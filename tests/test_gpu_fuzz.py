@@ -103,6 +103,97 @@ def test_random_geometry_teacher_forced(seed):
         TALLY["full"] += 1
 
 
+# ----------------------------------------------------------------------------- the paper's cache policy, free-running
+def draw_streaming_case(seed):
+    g = np.random.default_rng(5000 + seed)
+    H, W = int(g.integers(3, 8)), int(g.integers(3, 11))
+    P = int(g.integers(1, 12))
+    m = int(g.integers(2, 2 * W))
+    n_pin = int(g.integers(0, P + 1))                     # part of the prefix may be left unpinned (evictable)
+    cap = max(n_pin, 1) + m + int(g.integers(2, 12))      # room for pinned prefix + window + a few candidates
+    cap = max(cap, P + 1)                                 # the prefix itself must fit before decoding starts
+    dtype = "bf16" if g.random() < 0.6 else "f32"
+    D = int(g.choice([64, 128]))
+    h = int(g.integers(1, 7))
+    mode = int(g.choice([B.SCORE_VCOS, B.SCORE_ATTN_MASS, B.SCORE_VCOS_FUSED]))
+    policy = B.EVICT_REUSE_SLOT if (mode == B.SCORE_VCOS_FUSED or g.random() < 0.5) else B.EVICT_WHEN_FULL
+    layout = "head_major" if (mode == B.SCORE_VCOS_FUSED or g.random() < 0.5) else "slot_major"
+    kind = str(g.choice(["gauss", "outlier2pct", "lowrank8"]))
+    wl = WL.get_workload("tiny", n_seq=1, n_heads=h, head_dim=D, grid_h=H, grid_w=W, win_rows_back=0,
+                         win_col_radius=0, prefix_len=P, dtype=dtype, budget=0, value_kind=kind,
+                         value_scale=float(g.choice([0.25, 1.0])), seed=0xE000 + seed)
+    return wl, m, n_pin, cap, mode, policy, layout
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_streaming_cache_free_running(seed):
+    """Section 4.2 as written (evict the most redundant candidate when full), over random shapes, ranking
+    modes (two-pass V-cosine, V-cosine fused into attention, attention mass), both eviction forms and both
+    layouts: the GPU runs the whole trajectory on its own state, the oracle on its own; after every step
+    the two caches must hold the same tokens (compared by position) with identical rows, and the outputs
+    must agree.  A differing victim is accepted only where the oracle's scores of the two tie."""
+    wl, m, n_pin, cap, mode, policy, layout = draw_streaming_case(seed)
+    omode = B.SCORE_VCOS if mode == B.SCORE_VCOS_FUSED else mode
+    P, H, W = wl.prefix_len, wl.grid_h, wl.grid_w
+    cfg = oracle.make_cfg(n_heads=wl.n_heads, head_dim=wl.head_dim, grid_h=H, grid_w=W, win_rows_back=0,
+                          win_col_radius=0, grid_origin=P, n_keep_prefix=n_pin, budget=10 ** 6, score_mode=omode,
+                          cap=cap, win_recent_m=m, evict_when_full=1)
+    q, k, v = WL.gen_tokens(wl, 0, 0, prefix_len=P)
+    st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+    params = B.make_params(n_seq=1, n_heads=wl.n_heads, head_dim=wl.head_dim, grid_h=H, grid_w=W, win_rows_back=0,
+                           win_col_radius=0, dtype=B.F32 if wl.dtype == "f32" else B.BF16, score_mode=mode, cap=cap,
+                           layout=layout, win_recent_m=m, evict_policy=policy)
+    batch = LayerBatch(params, DEV)
+    load_state(batch, 0, st, cfg, 0)
+    batch.upload_seqs()
+    qd, kd, vd = (to_device(x, params.dtype, DEV) for x in (q, k, v))
+    tag0 = f"seed={seed} {H}x{W} P={P} pinned={n_pin} m={m} cap={cap} h={wl.n_heads} D={wl.head_dim} {wl.dtype} " \
+           f"{layout} mode={mode} policy={policy}"
+    evictions = 0
+    for s in range(0, H * W + 1):
+        p = P + s - 1
+        before = st.copy()
+        batch.step(qd[p:p + 1], kd[p:p + 1], vd[p:p + 1])
+        ref = oracle.step(cfg, st, s, q[p], k[p], v[p])
+        torch.cuda.synchronize()
+        seqs = batch.read_seqs()
+        tag = f"{tag0} s={s}"
+        n = st.n_res
+        assert seqs["status"][0] == 0 and seqs["step"][0] == s + 1 and seqs["n_res"][0] == n, tag
+        assert bool(seqs["compacted"][0]) == ref["compacted"], tag
+        evictions += int(ref["compacted"])
+        posd = batch.pos.cpu().numpy()[0, :n]
+        if set(posd.tolist()) != set(st.pos[:n].tolist()):
+            # the two sides evicted different tokens: legitimate only if the oracle's scores of the two tie
+            only_g = sorted(set(posd.tolist()) - set(st.pos[:n].tolist()))
+            only_o = sorted(set(st.pos[:n].tolist()) - set(posd.tolist()))
+            assert len(only_g) == 1 and len(only_o) == 1, tag
+            nb = before.n_res
+            if omode == B.SCORE_VCOS:
+                cls = oracle.classify(cfg, before.pos[:nb], s)
+                cand = np.nonzero(cls == oracle.CANDIDATE)[0]
+                sc = np.zeros(nb)
+                sc[cand] = oracle.vcos(cfg, before.V, cand)
+            else:
+                sc = before.score[:nb].astype(np.float64)
+            a = sc[np.nonzero(before.pos[:nb] == only_g[0])[0][0]]       # the oracle evicted this one
+            b_ = sc[np.nonzero(before.pos[:nb] == only_o[0])[0][0]]      # the GPU evicted this one
+            assert abs(a - b_) <= 4e-6 + 1e-4 * max(abs(a), abs(b_)), tag
+            TALLY["near_tie"] += 1
+            break
+        order = np.argsort(posd, kind="stable")
+        assert np.array_equal(posd[order], st.pos[:n]), tag
+        if policy == B.EVICT_WHEN_FULL:
+            assert np.array_equal(posd, st.pos[:n]), tag                   # this form keeps position order
+        assert np.array_equal(batch.k_host()[0, :n][order], st.K[:n]), tag
+        assert np.array_equal(batch.v_host()[0, :n][order], st.V[:n]), tag
+        if mode == B.SCORE_ATTN_MASS:
+            assert np.allclose(batch.rank_host()[0, :n][order], st.score[:n], rtol=1e-5, atol=1e-6), tag
+        check_out(wl, to_host(batch.out)[0], ref["out"], tag)
+        TALLY["full"] += 1
+    assert evictions >= 1 or cap >= P + H * W, tag0
+
+
 def test_random_cases_were_compared_in_full():
     """The near-tie escape must stay the exception (runs after the cases above, same process)."""
     total = TALLY["full"] + TALLY["near_tie"]
