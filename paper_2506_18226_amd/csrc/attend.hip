@@ -119,7 +119,7 @@ struct AttendArgs {
   int n_heads, n_hg, sel_cap, lg_stride, chunk_max, cap;
   int accumulate, append, advance;     // advance: step += 1 at the end
   int new_f32;                         // k_new / v_new are fp32 although the cache is bf16: round as they enter
-  int head_dim, vcos_fused;
+  int vcos_fused;
   long long slot_stride_b, head_stride_b;
   float scale_log2;     // softmax scale * log2(e)
 };
@@ -161,20 +161,6 @@ __device__ __forceinline__ void add_mass(float* score, int cap, int row0, const 
     for (int u = 0; u < B; ++u)
       if (ptr[u]) *ptr[u] = old[u] + inc[u];
   }
-}
-
-// Last act of a launch on a sequence (one thread): VF marks the score rows as belonging to the next
-// step's eviction if u did (tag 1 + step, kept as floats behind u), then the step may advance.
-template <bool VF>
-__device__ __forceinline__ void finish_step(adsa_seq& sq, const AttendArgs& A) {
-  if constexpr (VF) {
-    if (sq.vcos_u) {
-      float* tags = sq.vcos_u + (size_t)A.n_heads * A.head_dim;
-      const float want = (float)(sq.step + 2);
-      tags[1] = tags[0] == want ? want : 0.0f;
-    }
-  }
-  if (A.advance) sq.step = sq.step + 1;
 }
 
 template <int EB, int D, int HT, int U, int NW, bool VF>
@@ -509,7 +495,19 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
         });
       }
     }
-    if (hg == 0 && tid == 0) finish_step<VF>(sq, A);             // no other workgroup reads step
+    // last act on a sequence (one thread; no other workgroup reads step): VF marks the score rows as the
+    // next step's if u was (tags kept as floats behind u); then the step may advance.  (Written out here:
+    // handing the kernel's argument struct to a helper by reference made every variant slower.)
+    if (hg == 0 && tid == 0) {
+      if constexpr (VF) {
+        if (sq.vcos_u) {
+          float* tags = sq.vcos_u + (size_t)A.n_heads * D;
+          const float want = (float)(sq.step + 2);
+          tags[1] = tags[0] == want ? want : 0.0f;
+        }
+      }
+      if (A.advance) sq.step = sq.step + 1;
+    }
     return;
   }
 
@@ -571,7 +569,16 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
       *slot = min(max(idx[j], 0), cap - 1); *z = ld_dev(lg + (size_t)*sb * lgs + j);
     });
   }
-  if (hg == 0 && tid == 0) finish_step<VF>(sq, A);
+  if (hg == 0 && tid == 0) {
+    if constexpr (VF) {
+      if (sq.vcos_u) {
+        float* tags = sq.vcos_u + (size_t)A.n_heads * D;
+        const float want = (float)(sq.step + 2);
+        tags[1] = tags[0] == want ? want : 0.0f;
+      }
+    }
+    if (A.advance) sq.step = sq.step + 1;
+  }
 }
 
 template <int EB, int D, int HT, int NW, bool VF = false>
@@ -708,7 +715,7 @@ hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq*
   A.chunk_max = plan.chunk_max; A.cap = p.cap;
   A.accumulate = accumulate ? 1 : 0; A.append = append ? 1 : 0; A.advance = advance ? 1 : 0;
   A.new_f32 = (new_f32 && append) ? 1 : 0;
-  A.head_dim = p.head_dim; A.vcos_fused = p.score_mode == ADSA_SCORE_VCOS_FUSED ? 1 : 0;
+  A.vcos_fused = p.score_mode == ADSA_SCORE_VCOS_FUSED ? 1 : 0;
   const int eb = elem_bytes(p);
   A.slot_stride_b = (long long)p.kv_slot_stride * eb;
   A.head_stride_b = (long long)p.kv_head_stride * eb;

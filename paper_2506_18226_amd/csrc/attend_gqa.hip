@@ -183,6 +183,11 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   }
   __syncthreads();
 
+  // (the lambdas below work on copies: they capture by reference, and a reference to the kernel's argument
+  //  struct was measured to cost time in the multi-head kernel)
+  const long long slot_stride_b = A.slot_stride_b;
+  const float scale_log2 = A.scale_log2;
+  const bool keep_logits = A.accumulate != 0;
   const int stage_b = A.stage_b;                     // bytes of LDS each wave owns
   char* const stage = s_stage + wave * stage_b;
   struct Stage { uint4 k[UT][LT]; uint32_t v[UT][4][VW]; };
@@ -195,14 +200,14 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
 #pragma unroll
         for (int u = 0; u < LT; ++u) {
           const int slot = s_slot[min(tile * 16 + u * RPL + ld_row, len - 1)];
-          const char* p = (slot == new_slot) ? kn : k_base + (long long)slot * A.slot_stride_b;
+          const char* p = (slot == new_slot) ? kn : k_base + (long long)slot * slot_stride_b;
           const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + ld_piece * 16));
           st.k[ut][u] = (cvt && slot == new_slot) ? make_uint4(nk[0], nk[1], nk[2], nk[3]) : make_uint4(v.x, v.y, v.z, v.w);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int slot = s_slot[min(tile * 16 + 4 * kg + i, len - 1)];
-          const char* p = (slot == new_slot) ? vn : v_base + (long long)slot * A.slot_stride_b;
+          const char* p = (slot == new_slot) ? vn : v_base + (long long)slot * slot_stride_b;
           VLoad<EV * 2>::load(p + r * (EV * 2), st.v[ut][i]);
           if (cvt && slot == new_slot) {
 #pragma unroll
@@ -240,8 +245,8 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
         const int t0 = tile * 16 + 4 * kg;
         float z[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) z[i] = (t0 + i < len) ? s4[i] * A.scale_log2 : -INFINITY;
-        if (A.accumulate && r < G)
+        for (int i = 0; i < 4; ++i) z[i] = (t0 + i < len) ? s4[i] * scale_log2 : -INFINITY;
+        if (keep_logits && r < G)
           *reinterpret_cast<float4*>(s_logit + (size_t)r * lgs + t0) = make_float4(z[0], z[1], z[2], z[3]);
         float tm = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
         tm = fmaxf(tm, __shfl_xor(tm, 16, kWave));
