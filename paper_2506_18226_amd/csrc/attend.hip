@@ -305,6 +305,8 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
   for (int g0 = wave * TT * U; g0 < len; g0 += kAttWaves * TT * U) {
     uint4 kr[U], vr[U];
     int tl[U];
+    const char* vp[U];
+    bool vnew[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       tl[u] = g0 + u * TT + ts;
@@ -312,8 +314,15 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
       const long long off = (long long)slot * A.slot_stride_b;
       const bool is_new = slot == new_slot;         // the query token itself: read it from k_new / v_new
       kr[u] = load_stream16(is_new ? kn : kb + off);
-      vr[u] = load_stream16(is_new ? vn : vb + off);
-      if (cvt && is_new) { kr[u] = nk; vr[u] = nv; }
+      if (cvt && is_new) kr[u] = nk;
+      vp[u] = is_new ? vn : vb + off;
+      vnew[u] = cvt && is_new;
+    }
+    // all K rows are requested before the V rows: the logits can start while V is still on its way
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      vr[u] = load_stream16(vp[u]);
+      if (vnew[u]) vr[u] = nv;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
