@@ -470,12 +470,26 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
 
   if constexpr (VF) {
     // |v_h|^2 and v_h.u_h of this chunk's tokens, left in LDS by the loop (the barrier above ordered them)
-    if (vf_on)
-      for (int j = tid; j < len; j += kAttThreads) {
+    if (vf_on) {
+      int j0 = tid;
+      if (direct) {                                 // the first slots were fetched before the loop
+#pragma unroll
+        for (int k = 0; k < PF; ++k) {
+          const int j = tid + k * kAttThreads;
+          if (j < len) {
+            const int slot = min(max(pf_slot[k], 0), A.cap - 1);
+            vrows[slot] = s_logit[j];
+            vrows[A.cap + slot] = s_logit[A.chunk_max + j];
+          }
+        }
+        j0 = tid + PF * kAttThreads;
+      }
+      for (int j = j0; j < len; j += kAttThreads) {
         const int slot = min(max(idx[t_begin + j], 0), A.cap - 1);
         vrows[slot] = s_logit[j];
         vrows[A.cap + slot] = s_logit[A.chunk_max + j];
       }
+    }
   }
   if (direct) {
     // -------- per-head attention mass: score[head][slot] += p, from the logits still in LDS
