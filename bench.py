@@ -265,6 +265,8 @@ def main():
             "setup_seconds": round(t_setup, 1),
         },
     }
+    # classifier-free guidance runs two sequences (conditional / unconditional, separate caches) per image
+    result["image_tokens_per_s_under_cfg_pairing"] = tokens / elapsed / 2.0
     timed_attended = int(cnt_log[s0:S].sum())
     result["selected_kv_gb_per_step"] = timed_attended * tau / K / 1e9
     result["selected_kv_gbs_whole_path"] = timed_attended * tau / elapsed / 1e9
