@@ -22,11 +22,11 @@ from test_gpu_parity import DEV, params_for, load_state, check_out
 pytestmark = pytest.mark.gpu
 
 
-def _twin_batches(wl, cfg, n_seq):
+def _twin_batches(wl, cfg, n_seq, make=None):
     batches = []
     toks = [WL.gen_tokens(wl, 0, b, prefix_len=cfg.grid_origin) for b in range(n_seq)]
     for _ in range(3):
-        batch = LayerBatch(params_for(wl, n_seq, cfg.cap), DEV)
+        batch = LayerBatch(make() if make else params_for(wl, n_seq, cfg.cap), DEV)
         for b in range(n_seq):
             q, k, v = toks[b]
             st = oracle.CacheState.from_prefix(cfg, k[:cfg.grid_origin], v[:cfg.grid_origin])
@@ -83,3 +83,46 @@ def test_one_captured_step_replayed_over_a_trajectory(over):
     assert np.isfinite(out).all()
     final = graphed.read_seqs()
     assert (final["n_res"] <= cfg.cap).all() and (final["step"] == S + 1).all()
+
+
+def test_captured_step_of_the_papers_cache_policy_with_fused_ranking():
+    """Evict-one-when-full with slot reuse and the V-cosine ranking fused into the attention launch: five
+    kernels per step (two-pass fallback pair, eviction plan, advance of the running sum, selection, attention),
+    all decisions on the device, captured once and replayed over a whole trajectory; bit-identical to eager."""
+    P, H, W, m, cap, n, h, D = 4, 6, 6, 5, 16, 2, 3, 64
+    wl = WL.get_workload("tiny", n_seq=n, n_heads=h, head_dim=D, grid_h=H, grid_w=W, prefix_len=P, dtype="bf16",
+                         value_kind="gauss", value_scale=0.5, win_rows_back=0, win_col_radius=0)
+    cfg = oracle.make_cfg(n_heads=h, head_dim=D, grid_h=H, grid_w=W, win_rows_back=0, win_col_radius=0, grid_origin=P,
+                          budget=10 ** 6, score_mode=B.SCORE_VCOS, cap=cap, win_recent_m=m, evict_when_full=1)
+
+    def make():
+        return B.make_params(n_seq=n, n_heads=h, head_dim=D, grid_h=H, grid_w=W, win_rows_back=0, win_col_radius=0,
+                             dtype=B.BF16, score_mode=B.SCORE_VCOS_FUSED, cap=cap, win_recent_m=m,
+                             evict_policy=B.EVICT_REUSE_SLOT)
+
+    (eager, graphed, warm), toks = _twin_batches(wl, cfg, n, make)
+    qs, ks, vs = (np.stack([t[i] for t in toks], axis=1) for i in range(3))
+    qd, kd, vd = (to_device(x, eager.params.dtype, DEV) for x in (qs, ks, vs))
+    q_in, k_in, v_in = (torch.zeros_like(x[0]) for x in (qd, kd, vd))
+    warm.step(qd[P - 1], kd[P - 1], vd[P - 1])
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        graphed.step(q_in, k_in, v_in)
+    torch.cuda.synchronize()
+    evictions = 0
+    for s in range(H * W + 1):
+        p = P + s - 1
+        q_in.copy_(qd[p]); k_in.copy_(kd[p]); v_in.copy_(vd[p])
+        g.replay()
+        eager.step(qd[p], kd[p], vd[p])
+        torch.cuda.synchronize()
+        a, b = eager.read_seqs(), graphed.read_seqs()
+        for f in ("n_res", "step", "status", "compacted", "pending_slot", "hole"):
+            assert np.array_equal(a[f], b[f]), (s, f)
+        assert (a["status"] == 0).all() and (a["step"] == s + 1).all(), s
+        evictions += int(a["compacted"].sum())
+        assert torch.equal(eager.out, graphed.out) and torch.equal(eager.lse, graphed.lse), s
+        assert torch.equal(eager.K, graphed.K) and torch.equal(eager.V, graphed.V) and torch.equal(eager.pos, graphed.pos), s
+        assert torch.equal(eager.vcos_u, graphed.vcos_u) and torch.equal(eager.score, graphed.score), s
+    assert evictions >= 2 * 20 and (eager.read_seqs()["n_res"] == cap).all()
