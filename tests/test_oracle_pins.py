@@ -592,3 +592,62 @@ def oracle_cfg_gqa(wl, G, n_heads=None):
         n_heads=wl.n_heads if n_heads is None else n_heads, head_dim=wl.head_dim, grid_h=wl.grid_h,
         grid_w=wl.grid_w, win_rows_back=wl.win_rows_back, win_col_radius=wl.win_col_radius,
         grid_origin=wl.prefix_len, budget=wl.budget, score_mode=WL.SCORE_ATTN_MASS, q_per_kv=G)
+
+
+# ----------------------------------------------------------------------------- randomised properties
+@pytest.mark.parametrize("seed", range(30))
+def test_random_configurations_keep_the_methods_invariants(seed):
+    """Seeded random grids, windows, prefixes, budgets and ranking modes: at every step of the whole
+    trajectory the attended set is prefix + local + exactly min(B, |candidates|) candidates, ascending;
+    the kept candidates are the best by score with the lower slot first among equals (re-derived here by
+    a plain sort); the window of every step is resident; positions stay ascending and within capacity;
+    evicted tokens never come back; softmax rows sum to one through the mass bookkeeping."""
+    g = np.random.default_rng(9000 + seed)
+    H, W = int(g.integers(2, 7)), int(g.integers(2, 9))
+    R, w = int(g.integers(0, min(3, H))), int(g.integers(0, W + 1))
+    P = int(g.integers(1, 9))
+    n_pin = int(g.integers(1, P + 1))                 # (with nothing pinned and B = 0, step 0 would attend nothing)
+    B_ = int(g.integers(0, 10))
+    mode = int(g.choice([WL.SCORE_ATTN_MASS, WL.SCORE_VCOS]))
+    h, D = int(g.integers(1, 4)), 8
+    wl = WL.get_workload("tiny", n_heads=h, head_dim=D, grid_h=H, grid_w=W, prefix_len=P, value_kind="gauss",
+                         value_scale=0.5, seed=0xD000 + seed)
+    cfg = oracle.make_cfg(n_heads=h, head_dim=D, grid_h=H, grid_w=W, win_rows_back=R, win_col_radius=w,
+                          grid_origin=P, n_keep_prefix=n_pin, budget=B_, score_mode=mode)
+    q, k, v = WL.gen_tokens(wl, 0, 0, prefix_len=P)
+    st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+    gone = set()
+    for s in range(0, H * W + 1):
+        p = P + s - 1
+        n0 = st.n_res
+        pos_before = np.append(st.pos[:n0], P + s - 1) if s >= 1 else st.pos[:n0].copy()
+        score_before = np.append(st.score[:n0], 0.0).astype(np.float32) if s >= 1 else st.score[:n0].copy()
+        mass_before = float(score_before.astype(np.float64).sum())
+        res = oracle.step(cfg, st, s, q[p], k[p], v[p])
+        sel = res["sel_idx"]
+        cls = oracle.classify(cfg, pos_before, s)
+        fixed = np.nonzero(cls != oracle.CANDIDATE)[0]
+        cand = np.nonzero(cls == oracle.CANDIDATE)[0]
+        assert (np.diff(sel) > 0).all() and set(fixed.tolist()) <= set(sel.tolist()), (seed, s)
+        chosen = np.array(sorted(set(sel.tolist()) - set(fixed.tolist())), dtype=np.int64)
+        assert chosen.size == min(B_, cand.size) and set(chosen.tolist()) <= set(cand.tolist()), (seed, s)
+        if mode == WL.SCORE_ATTN_MASS and cand.size:
+            # the ranking saw the scores before this step's accumulation: best first, lower slot among equals
+            order = sorted(cand.tolist(), key=lambda i: (-float(score_before[i]), i))
+            assert sorted(order[:chosen.size]) == chosen.tolist(), (seed, s)
+        if s >= 1:                                        # the query's window is resident and attended
+            r, c = divmod(s - 1, W)
+            need = {P + r * W + cc for cc in range(c + 1)}
+            need |= {P + rr * W + cc for rr in range(max(0, r - R), r) for cc in range(W) if abs(cc - c) <= w}
+            assert need <= set(pos_before[sel].tolist()), (seed, s)
+        n = st.n_res
+        assert n <= cfg.cap and (np.diff(st.pos[:n]) > 0).all(), (seed, s)
+        assert not (set(st.pos[:n].tolist()) & gone), (seed, s)
+        if res["compacted"]:
+            km = res["keep_map"]
+            assert km[km >= 0].tolist() == list(range(n)), (seed, s)
+            gone |= set(pos_before.tolist()) - set(st.pos[:n].tolist())
+            assert all(pp >= n_pin for pp in gone), (seed, s)           # pinned positions are never evicted
+        elif mode == WL.SCORE_ATTN_MASS:
+            # one unit of probability per head was handed out (nothing left the cache in this step)
+            assert abs(float(st.score[:n].astype(np.float64).sum()) - mass_before - h) < 1e-4, (seed, s)
