@@ -18,15 +18,32 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source into one shared library; returns its path."""
-    os.makedirs(LIB_DIR, exist_ok=True)
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH]
+def _compile_one(args):
+    cmd, verbose = args
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every HIP source (one hipcc process each, side by side) and link one shared library;
+    returns its path."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    os.makedirs(LIB_DIR, exist_ok=True)
+    obj_dir = os.path.join(LIB_DIR, "obj")
+    os.makedirs(obj_dir, exist_ok=True)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    objs, jobs = [], []
+    for src in SOURCES:
+        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
+        objs.append(obj)
+        jobs.append(([hipcc, *flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c",
+                      os.path.join(CSRC, src), "-o", obj], verbose))
+    with ThreadPoolExecutor(max_workers=min(len(jobs), 6)) as pool:
+        list(pool.map(_compile_one, jobs))
+    _compile_one(([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH], verbose))
     return LIB_PATH
 
 

@@ -2,13 +2,14 @@
 // attention over the selected slots, plus the cache append (Section 4.2) and the per-head
 // attention-mass update, in ONE launch.
 //
-//  k_attend<EB, D, HT, U> : grid (token chunk, head group, sequence), 256 threads.
+//  k_attend<EB, D, HT, U, NW, VF, DIRECT> : grid (token chunk, head group, sequence), NW waves.
 //    A 16-byte-per-lane streaming load of one wave covers RPW = 64 / (D*EB/16) rows of D
 //    elements.  HT of them are different heads of one token ([slot][head][D] caches: HT = RPW, one
 //    contiguous burst per token) or HT = 1 and they are RPW consecutive tokens of ONE head
 //    ([head][slot][D] caches: a workgroup streams one head's rows back to back).  q.k is reduced
 //    over the lanes of a row with DPP; every lane keeps an online-softmax state (m, l, acc) in
-//    registers, fp32, log2 domain.  Lane groups and the four waves merge through shuffles + LDS.
+//    registers, fp32, log2 domain.  The lane groups of a wave merge in registers (DPP and 16-/32-lane
+//    swaps), the waves through one small LDS record each.
 //    With one chunk per (sequence, head group) -- the plan whenever that already fills the chip --
 //    the workgroup writes out / lse itself and adds the probabilities it produced to its OWN
 //    heads' rows of score[]: no workgroup ever talks to another one.
@@ -20,6 +21,19 @@
 #include <hip/hip_ext.h>
 
 #include "adsa_internal.h"
+
+#ifndef ADSA_ROLLING
+#define ADSA_ROLLING 1
+#endif
+#ifndef ADSA_U
+#define ADSA_U 4
+#endif
+#ifndef ADSA_SCORE_ST
+#define ADSA_SCORE_ST 0
+#endif
+#ifndef ADSA_SCORE_NOREAD
+#define ADSA_SCORE_NOREAD 0
+#endif
 
 namespace adsa {
 namespace {
@@ -46,11 +60,26 @@ __device__ __forceinline__ float row_sum(float x) {
   return x;
 }
 
+// Pointers the kernel reads out of the sequence record are declared as what they are, global memory:
+// the accesses then compile to global (not flat) instructions whatever else is done with the value.
+#define ADSA_GLOBAL __attribute__((address_space(1)))
+typedef ADSA_GLOBAL char gchar;
+typedef ADSA_GLOBAL float gfloat;
+typedef ADSA_GLOBAL int32_t gint;
+
 // 16-byte streaming load: K/V rows are read once per step, so keep them out of the caches' way
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 load_stream16(const char* p) {
-  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+__device__ __forceinline__ uint4 load_stream16(const gchar* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const ADSA_GLOBAL u32x4*>(p));
   return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint4 load16(const gchar* p) {
+  const u32x4 v = *reinterpret_cast<const ADSA_GLOBAL u32x4*>(p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store16(gchar* p, const uint4& x) {
+  u32x4 v; v.x = x.x; v.y = x.y; v.z = x.z; v.w = x.w;
+  *reinterpret_cast<ADSA_GLOBAL u32x4*>(p) = v;
 }
 
 template <int EB> struct Elems;
@@ -78,17 +107,18 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 }
 
 // 8 consecutive fp32 values -> 8 bf16 (round to nearest even) in one 16-byte vector
-__device__ __forceinline__ uint4 pack8_bf16(const float* f) {
-  const float4 a = reinterpret_cast<const float4*>(f)[0], b = reinterpret_cast<const float4*>(f)[1];
+__device__ __forceinline__ uint4 pack8_bf16(const gchar* f) {
+  const uint4 ua = load16(f), ub = load16(f + 16);
+  const float4 a = make_float4(__uint_as_float(ua.x), __uint_as_float(ua.y), __uint_as_float(ua.z), __uint_as_float(ua.w));
+  const float4 b = make_float4(__uint_as_float(ub.x), __uint_as_float(ub.y), __uint_as_float(ub.z), __uint_as_float(ub.w));
   return make_uint4(f32_to_bf16_rne(a.x) | (f32_to_bf16_rne(a.y) << 16), f32_to_bf16_rne(a.z) | (f32_to_bf16_rne(a.w) << 16),
                     f32_to_bf16_rne(b.x) | (f32_to_bf16_rne(b.y) << 16), f32_to_bf16_rne(b.z) | (f32_to_bf16_rne(b.w) << 16));
 }
 
 // Data handed from one workgroup to another inside a launch (chunk partials, logits) is written
-// and read with device-scope relaxed atomics: they go through to the level where all XCDs agree,
-// so no L2 write-back / invalidate (a device-scope fence) is needed.  Order is kept by the issue
-// order: the writer waits for its stores (workgroup release + barrier) before it bumps the arrival
-// counter; the reader issues its loads after the counter's old value came back.
+// and read with device-scope atomic accesses: they go through to the level where all XCDs agree
+// and are never left dirty in (or served stale from) one XCD's L2.  The order between them and the
+// arrival counter is made in k_attend's split path (completed stores, barrier, release/acquire ticket).
 __device__ __forceinline__ void st_dev(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -100,16 +130,54 @@ __device__ __forceinline__ void st_dev2(float* p, float a, float b) {   // 8-byt
   __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// chunk c of a list of cnt tokens split evenly over nc chunks
-__device__ __forceinline__ int chunk_begin(int cnt, int c, int nc) { return (int)(((long long)cnt * c) / nc); }
+// chunk c of a list of cnt (<= ADSA_MAX_CAP) tokens split evenly over nc (<= kMaxChunks) chunks
+__device__ __forceinline__ int chunk_begin(int cnt, int c, int nc) { return (int)(((unsigned)cnt * (unsigned)c) / (unsigned)nc); }
+
+// i / n for 0 <= i < 2^22, 1 <= n < 2^22, given r ~= 1/n: the float estimate is off by at most one
+__device__ __forceinline__ int small_div(int i, int n, float r) {
+  int qd = (int)((float)i * r);
+  if (qd * n > i) --qd;
+  else if ((qd + 1) * n <= i) ++qd;
+  return qd;
+}
+
+// Demands a wave-uniform value that was just loaded in scalar registers AT THIS POINT of the program:
+// its load cannot sink below the statement, into a later and then dependent round trip.  (Input only:
+// the value itself, and what the compiler knows about where a pointer points, stay as they are.)
+template <typename T>
+__device__ __forceinline__ void pin_uniform(const T& x) { asm volatile("" : : "s"(x)); }
+
+// Value of lane (lane ^ X) for X in {8, 16, 32}: DPP inside a 16-lane row, register-only swaps of
+// 16- and 32-lane halves beyond it (both outputs of a swap of x with itself are returned).
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+template <int X>
+__device__ __forceinline__ float xor_sum(float x) {
+  if constexpr (X == 8) return x + dpp_f<0x128>(x);            // row_ror:8
+  else {
+    const unsigned u = __float_as_uint(x);
+    const u32x2 r = X == 16 ? __builtin_amdgcn_permlane16_swap(u, u, false, false)
+                            : __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);       // one of the two is x itself, the other its partner
+  }
+}
+template <int X>
+__device__ __forceinline__ float xor_max(float x) {
+  if constexpr (X == 8) return fmaxf(x, dpp_f<0x128>(x));
+  else {
+    const unsigned u = __float_as_uint(x);
+    const u32x2 r = X == 16 ? __builtin_amdgcn_permlane16_swap(u, u, false, false)
+                            : __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+  }
+}
 
 struct AttendArgs {
   adsa_seq* seqs;
+  const int32_t* sel_idx;
+  const int32_t* sel_cnt;
   const char* q;
   const char* k_new;
   const char* v_new;
-  const int32_t* sel_idx;
-  const int32_t* sel_cnt;
   char* out;
   float* lse;
   float* logits;        // [n_seq][n_heads][lg_stride]   scaled logits, log2 units (split launches)
@@ -124,26 +192,14 @@ struct AttendArgs {
   float scale_log2;     // softmax scale * log2(e)
 };
 
-// merge two online-softmax states (log2 domain); (m, l) == (-inf, 0) is the neutral element
-template <int EPL>
-__device__ __forceinline__ void merge_state(float& m, float& l, float* acc, float m2, float l2, const float* acc2) {
-  const float M = fmaxf(m, m2);
-  const float w1 = (m == -INFINITY) ? 0.0f : fast_exp2(m - M);
-  const float w2 = (m2 == -INFINITY) ? 0.0f : fast_exp2(m2 - M);
-  l = l * w1 + l2 * w2;
-#pragma unroll
-  for (int e = 0; e < EPL; ++e) acc[e] = acc[e] * w1 + acc2[e] * w2;
-  m = M;
-}
-
 // score[row][slot] += 2^(z - lse2[row]) for `total` (row, token) pairs, loads batched so that the
 // read-modify-write latencies overlap.  get(i, &row_local, &slot, &z) describes pair i.
 template <typename Get>
-__device__ __forceinline__ void add_mass(float* score, int cap, int row0, const float* s_lse2, int total, Get get) {
+__device__ __forceinline__ void add_mass(gfloat* score, int cap, int row0, const float* s_lse2, int total, Get get) {
   constexpr int B = 4;
   const int kAttThreads = blockDim.x;
   for (int i0 = threadIdx.x; i0 < total; i0 += kAttThreads * B) {
-    float* ptr[B];
+    gfloat* ptr[B];
     float inc[B], old[B];
 #pragma unroll
     for (int u = 0; u < B; ++u) {
@@ -163,28 +219,28 @@ __device__ __forceinline__ void add_mass(float* score, int cap, int row0, const 
   }
 }
 
-template <int EB, int D, int HT, int U, int NW, bool VF>
+// DIRECT: the list of a (sequence, head group) is not split (grid.x == 1): the workgroup finishes its heads alone.
+template <int EB, int D, int HT, int U, int NW, bool VF, bool DIRECT>
 __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
-  constexpr int kAttThreads = NW * kWave, kAttWaves = NW;   // waves of the workgroup share one token chunk
+  constexpr int kAttThreads = NW * kWave;           // the waves of the workgroup share one token chunk
   constexpr int EPL = Elems<EB>::N;                 // elements per lane
   constexpr int LPR = D / EPL;                      // lanes per row
   constexpr int RPW = kWave / LPR;                  // rows per wave-load
   constexpr int TT = RPW / HT;                      // tokens per wave-load
   constexpr int PF = 1024 / kAttThreads;            // score read-modify-writes a thread starts early
   extern __shared__ float s_logit[];                // logits tile [HT][chunk_max]
-  __shared__ float s_pm[kAttWaves * TT][HT], s_pl[kAttWaves * TT][HT];   // partial (m, l) per lane group
-  // Merge layout.  One head per workgroup: all threads share the merge, thread t = (column t / S, split t % S)
-  // adds every S-th partial of its column and the S splits meet by shuffles; rows are padded so that the
-  // 64 lanes of a wave hit 64 different banks.  Several heads: one thread per output element.
-  constexpr int NPART = kAttWaves * TT;
-  constexpr int S = kAttThreads / D;
-  constexpr bool kSplitMerge = HT == 1 && S >= 2 && S <= kWave && NPART % S == 0;
-  constexpr int STR = kSplitMerge ? D + kWave / S : D;
-  __shared__ float s_pacc[NPART * HT * STR];                                // partial accumulators [lane group][head][STR]
+  // merge: the lane groups of a wave meet in registers, the waves through these (one state per wave and head)
+  __shared__ float s_wm[NW][HT], s_wl[NW][HT];
+  __shared__ __attribute__((aligned(16))) float s_wacc[NW * HT * D];
   __shared__ float s_lse2[HT];
   __shared__ int s_ticket;
 
-  const int chunk = blockIdx.x, hg = blockIdx.y, b = blockIdx.z, n_chunks = gridDim.x;
+#ifdef ADSA_ROT
+  const int chunk = DIRECT ? 0 : blockIdx.x, hg = (blockIdx.y + blockIdx.z) % gridDim.y, b = blockIdx.z;
+#else
+  const int chunk = DIRECT ? 0 : blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
+#endif
+  const int n_chunks = DIRECT ? 1 : gridDim.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int sub = lane / LPR, dl = lane - sub * LPR;
@@ -193,28 +249,63 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
   const bool head_ok = head < A.n_heads;
   const int head_c = head_ok ? head : A.n_heads - 1;
   const int heads_here = min(HT, A.n_heads - hg * HT);
-  const bool direct = n_chunks == 1;                // this workgroup sees the whole list of its heads
 
-  // ---- everything the first K/V loads depend on is requested here, in one round trip: the
-  // count, the sequence record, q, and (when the list is not split, so its chunk starts at 0)
-  // the first slots of the loop and the score words this thread will update at the end.
-  adsa_seq& sq = A.seqs[b];
-  const int cnt_raw = A.sel_cnt[b];
-  char* const k_base = reinterpret_cast<char*>(sq.k);
-  char* const v_base = reinterpret_cast<char*>(sq.v);
-  float* const score = sq.score;
-  const int pending = sq.pending_slot;
-  const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
+  // ---- first round trip: everything that depends on the kernel arguments only -- the count, the
+  // sequence record, q and (when the list is not split, so its chunk starts at 0) the first slots of
+  // the loop and the slots whose score words this thread updates at the end.  The record and the
+  // count are pinned here so that they cannot drift behind the count test below.
+  ADSA_GLOBAL adsa_seq* const sqp = (ADSA_GLOBAL adsa_seq*)(A.seqs + b);
+  const int cnt_raw = ((const gint*)A.sel_cnt)[b];
+  gchar* const k_base = (gchar*)sqp->k;
+  gchar* const v_base = (gchar*)sqp->v;
+  gfloat* const score = (gfloat*)sqp->score;
+  const int pending = sqp->pending_slot;
+  gfloat* const u_state = VF ? (gfloat*)sqp->vcos_u : nullptr;
+  const gint* idx = (const gint*)A.sel_idx + (size_t)b * A.sel_cap;
   const size_t row_off = ((size_t)b * A.n_heads + head_c) * D * EB + dl * 16;
-  const uint4 qr = *reinterpret_cast<const uint4*>(A.q + row_off);
+  const gchar* const q_g = (const gchar*)A.q;
+  const gchar* const k_new_g = (const gchar*)A.k_new;
+  const gchar* const v_new_g = (const gchar*)A.v_new;
+  gchar* const out_g = (gchar*)A.out;
+  gfloat* const lse_g = (gfloat*)A.lse;
+  const uint4 qr = load16(q_g + row_off);
+  // the query token's own K/V row (Section 4.2 append), as this launch attends and stores it: every lane keeps
+  // its 16-byte piece in registers; fp32 rows of a bf16 cache are rounded once, here
+  uint4 nk = make_uint4(0u, 0u, 0u, 0u), nv = nk;
+  if (A.append) {
+    if (EB == 2 && A.new_f32) {
+      const size_t off32 = ((size_t)b * A.n_heads + head_c) * D * 4 + dl * 32;
+      nk = pack8_bf16(k_new_g + off32);
+      nv = pack8_bf16(v_new_g + off32);
+    } else {
+      nk = load16(k_new_g + row_off);
+      nv = load16(v_new_g + row_off);
+    }
+  }
+#if ADSA_ROLLING
+  // The wave takes the TT-token units wave, wave + NW, ... of the chunk, in that order; unit number k of the
+  // wave holds, for this lane, token (wave + k * NW) * TT + ts.  slot_a[u]: slot of unit u; slot_nx[u]: of the unit
+  // that takes ring position u next.
+  int slot_a[U], slot_nx[U];
+  int pf_slot[PF];
+  if constexpr (DIRECT) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot_a[u] = idx[min((wave + u * NW) * TT + ts, A.sel_cap - 1)];
+#pragma unroll
+    for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * kAttThreads, A.sel_cap - 1)];
+  }
+#else
   int slot_cur[U];
   int pf_slot[PF];
-  if (direct) {
+  if constexpr (DIRECT) {
 #pragma unroll
     for (int u = 0; u < U; ++u) slot_cur[u] = idx[min(wave * TT * U + u * TT + ts, A.sel_cap - 1)];
 #pragma unroll
     for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * kAttThreads, A.sel_cap - 1)];
   }
+#endif
+  pin_uniform(cnt_raw); pin_uniform(k_base); pin_uniform(v_base); pin_uniform(score); pin_uniform(pending);
+  if constexpr (VF) pin_uniform(u_state);
 
   const int cnt = min(cnt_raw, A.sel_cap);
   if (cnt <= 0) {                                   // inactive or rejected sequence: zero-filled row
@@ -223,40 +314,51 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
         const int hd = hg * HT + o / D;
         if (hd < A.n_heads) {
           const size_t oi = ((size_t)b * A.n_heads + hd) * D + (o % D);
-          if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = 0.0f;
-          else reinterpret_cast<uint16_t*>(A.out)[oi] = 0;
-          if (o % D == 0) A.lse[(size_t)b * A.n_heads + hd] = 0.0f;
+          if (EB == 4) reinterpret_cast<gfloat*>(out_g)[oi] = 0.0f;
+          else reinterpret_cast<ADSA_GLOBAL uint16_t*>(out_g)[oi] = 0;
+          if (o % D == 0) lse_g[(size_t)b * A.n_heads + hd] = 0.0f;
         }
       }
     }
     return;
   }
-  const int t_begin = chunk_begin(cnt, chunk, n_chunks), t_end = chunk_begin(cnt, chunk + 1, n_chunks);
+  const int t_begin = DIRECT ? 0 : chunk_begin(cnt, chunk, n_chunks);
+  const int t_end = DIRECT ? cnt : chunk_begin(cnt, chunk + 1, n_chunks);
   if (t_begin >= t_end) return;                     // fewer tokens than chunks
   const int len = t_end - t_begin;
+  const float inv_len = 1.0f / (float)len;
   // the slot adsa_select reserved for the query token (Section 4.2 append), if this launch fills it
   const int new_slot = (A.append && pending < A.cap) ? pending : -1;
 
   // pair i of the final score update is (head i / len, token i % len); start the first PF reads now
   const int n_pairs = heads_here * len;
   float pf_old[PF];
-  if (direct && A.accumulate) {
+  if (DIRECT && A.accumulate) {
 #pragma unroll
     for (int k = 0; k < PF; ++k) {
       const int i = tid + k * kAttThreads;
       pf_old[k] = 0.0f;
       if (i < n_pairs) {
-        const int sb = i / len;
-        int slot = pf_slot[k];
-        if (HT > 1) slot = idx[i - sb * len];        // several heads per workgroup: pair i is not token i
+        int slot = pf_slot[k], sb = 0;
+        if constexpr (HT > 1) {                     // several heads per workgroup: pair i is not token i
+          sb = small_div(i, len, inv_len);
+          slot = idx[i - sb * len];
+        }
         pf_slot[k] = min(max(slot, 0), A.cap - 1);
+#if !ADSA_SCORE_NOREAD
         pf_old[k] = score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]];
+#endif
       }
     }
   }
-  if (!direct) {
+  if constexpr (!DIRECT) {
+#if ADSA_ROLLING
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot_a[u] = idx[t_begin + min((wave + u * NW) * TT + ts, len - 1)];
+#else
 #pragma unroll
     for (int u = 0; u < U; ++u) slot_cur[u] = idx[t_begin + min(wave * TT * U + u * TT + ts, len - 1)];
+#endif
   }
 
   float qf[EPL];
@@ -264,35 +366,16 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
 #pragma unroll
   for (int e = 0; e < EPL; ++e) qf[e] *= A.scale_log2;
   const long long lane_off = (long long)head_c * A.head_stride_b + dl * 16;
-  char* kb = k_base + lane_off;
-  char* vb = v_base + lane_off;
-  // the new token's row as this launch attends it; fp32 rows of a bf16 cache are rounded once, here, and
-  // every lane keeps its 16-byte piece of the rounded row in registers
-  const bool cvt = EB == 2 && A.new_f32 && new_slot >= 0;
-  const char* kn = cvt ? kb : A.k_new + row_off;     // (cvt: any valid row; the loaded value is replaced)
-  const char* vn = cvt ? vb : A.v_new + row_off;
-  uint4 nk = make_uint4(0u, 0u, 0u, 0u), nv = nk;
-  if (cvt) {
-    const size_t off32 = ((size_t)b * A.n_heads + head_c) * D * 4 + dl * 32;
-    nk = pack8_bf16(reinterpret_cast<const float*>(A.k_new + off32));
-    nv = pack8_bf16(reinterpret_cast<const float*>(A.v_new + off32));
-  }
-  if (new_slot >= 0 && chunk == n_chunks - 1 && wave == 0 && ts == 0 && head_ok) {
-    const long long off = (long long)new_slot * A.slot_stride_b;     // this group's rows of the new token
-    if (!cvt) { nk = *reinterpret_cast<const uint4*>(kn); nv = *reinterpret_cast<const uint4*>(vn); }
-    *reinterpret_cast<uint4*>(kb + off) = nk;
-    *reinterpret_cast<uint4*>(vb + off) = nv;
-  }
-
+  gchar* kb = k_base + lane_off;
+  gchar* vb = v_base + lane_off;
   // VF: this lane's columns of u for its head, and the two score rows of the head
   float uf[EPL];
-  float* vrows = nullptr;
+  gfloat* vrows = nullptr;
   bool vf_on = false;
   if constexpr (VF) {
-    const float* up = sq.vcos_u;
-    vf_on = up != nullptr && head_ok;
+    vf_on = u_state != nullptr && head_ok;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) uf[e] = vf_on ? up[(size_t)head_c * D + dl * EPL + e] : 0.0f;
+    for (int e = 0; e < EPL; ++e) uf[e] = vf_on ? u_state[(size_t)head_c * D + dl * EPL + e] : 0.0f;
     vrows = score + (size_t)(2 * head_c) * A.cap;
   }
 
@@ -300,23 +383,109 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.0f;
 
-  // wave w takes token groups w, w+4, ...; a group is TT*U consecutive tokens of the chunk.
+#if ADSA_ROLLING
+  // Rolling gather: U units (row pairs per lane) are in flight per wave; as soon as the oldest has arrived it is
+  // folded into the lane's online-softmax state and its registers are given to the next unit's loads, so the
+  // number of outstanding requests stays constant instead of draining once per batch.
+  {
+    const int n_units = (len + TT - 1) / TT;
+    const int n_mine = n_units > wave ? (n_units - wave + NW - 1) / NW : 0;       // units of this wave
+    uint4 kr[U], vr[U];
+    int tok[U];                                     // token (chunk-relative) in flight at ring position u; >= len: none
+    bool fresh[U];                                  // ring position u stands for the query token's own row
+#pragma unroll
+    for (int u = 0; u < U; ++u) { kr[u] = make_uint4(0u, 0u, 0u, 0u); vr[u] = kr[u]; tok[u] = len; fresh[u] = false; }
+    auto issue = [&](int u, int slot_raw, int token) {
+      const int slot = min(max(slot_raw, 0), A.cap - 1);      // never touch memory outside the cache
+      const long long off = (long long)slot * A.slot_stride_b;
+      const bool is_new = slot == new_slot;         // the query token itself: its row is in registers (nk, nv)
+      const bool live = token < len && !is_new;     // else (also past the end of the chunk) re-read q's row: cached
+      kr[u] = load_stream16(live ? kb + off : q_g + row_off);
+      vr[u] = load_stream16(live ? vb + off : q_g + row_off);
+      tok[u] = token;
+      fresh[u] = is_new;
+    };
+    auto fold = [&](int u) {
+      const bool on = tok[u] < len;
+      const uint4 kx = fresh[u] ? nk : kr[u], vx = fresh[u] ? nv : vr[u];
+      float kf[EPL];
+      Elems<EB>::unpack(kx, kf);
+      float d = 0.0f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kf[e], d);
+      d = row_sum<LPR>(d);
+      const float z = on ? d : -INFINITY;
+      if (A.accumulate && dl == 0 && on) s_logit[hs * A.chunk_max + tok[u]] = z;
+      const float m_new = fmaxf(m, z);
+      const float corr = (m == -INFINITY) ? 0.0f : fast_exp2(m - m_new);     // (l and acc are 0 while m is -inf)
+      const float pr = on ? fast_exp2(z - m_new) : 0.0f;
+      float vf[EPL];
+      Elems<EB>::unpack(vx, vf);
+      l = fmaf(l, corr, pr);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] = fmaf(acc[e], corr, pr * vf[e]);
+      m = m_new;
+      if constexpr (VF) {                           // Eq. 2-3 bookkeeping of this row: |v_h|^2 and v_h . u_h
+        float dv = 0.0f, sv = 0.0f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) { dv = fmaf(vf[e], uf[e], dv); sv = fmaf(vf[e], vf[e], sv); }
+        dv = row_sum<LPR>(dv);
+        sv = row_sum<LPR>(sv);
+        if (dl == 0 && on) { s_logit[tok[u]] = sv; s_logit[A.chunk_max + tok[u]] = dv; }
+      }
+      // the state is demanded HERE, and no memory access may cross: the unit is folded completely before the
+      // loads that reuse its ring position are issued, and no later unit's arithmetic is pulled in front of it
+      // (left to itself the compiler gathers all the logits of a trip first and so waits for the whole ring)
+      static_assert(EPL == 4 || EPL == 8, "elements per lane");
+      if constexpr (EPL == 8)
+        asm volatile("" : "+v"(m), "+v"(l), "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]), "+v"(acc[4]),
+                     "+v"(acc[5]), "+v"(acc[6]), "+v"(acc[7]) : : "memory");
+      else
+        asm volatile("" : "+v"(m), "+v"(l), "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]) : : "memory");
+    };
+    // unit k of the wave lives at ring position k % U: units 0 .. U-1 are requested here, trip t folds units
+    // tU .. tU+U-1 and requests the units one ring revolution later, the last trip only folds.  (Units past
+    // the wave's last one re-read the chunk's last row, which is cached by then.)
+    auto refill = [&](int u, int k, int slot_raw) { // ring position u <- unit k; fetch the slot of unit k + U
+      const int token = (wave + k * NW) * TT + ts;
+      issue(u, slot_raw, token);
+      slot_nx[u] = idx[t_begin + min(token + U * NW * TT, len - 1)];
+      asm volatile("" : : : "memory");             // requests leave in ring order (the wait counts rely on it)
+      __builtin_amdgcn_sched_barrier(0);            // ... and before the next unit's arithmetic, which waits for ITS rows
+    };
+    const int n_trips = (n_mine + U - 1) / U;
+#pragma unroll
+    for (int u = 0; u < U; ++u) refill(u, u, slot_a[u]);
+    int k_next = U;
+    for (int trip = 1; trip < n_trips; ++trip) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        fold(u);
+        refill(u, k_next + u, slot_nx[u]);
+      }
+      k_next += U;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) fold(u);
+  }
+#else
+  // wave w takes token groups w, w+NW, ...; a group is TT*U consecutive tokens of the chunk.
   // The slots of the next group are fetched while this group's rows are in flight.
-  for (int g0 = wave * TT * U; g0 < len; g0 += kAttWaves * TT * U) {
+  for (int g0 = wave * TT * U; g0 < len; g0 += NW * TT * U) {
     uint4 kr[U], vr[U];
     int tl[U];
-    const char* vp[U];
+    const gchar* vp[U];
     bool vnew[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       tl[u] = g0 + u * TT + ts;
       const int slot = min(max(slot_cur[u], 0), A.cap - 1);   // never touch memory outside the cache
       const long long off = (long long)slot * A.slot_stride_b;
-      const bool is_new = slot == new_slot;         // the query token itself: read it from k_new / v_new
-      kr[u] = load_stream16(is_new ? kn : kb + off);
-      if (cvt && is_new) kr[u] = nk;
-      vp[u] = is_new ? vn : vb + off;
-      vnew[u] = cvt && is_new;
+      const bool is_new = slot == new_slot;         // the query token itself: its row is in registers
+      kr[u] = load_stream16(is_new ? q_g + row_off : kb + off);
+      if (is_new) kr[u] = nk;
+      vp[u] = is_new ? q_g + row_off : vb + off;
+      vnew[u] = is_new;
     }
     // all K rows are requested before the V rows: the logits can start while V is still on its way
 #pragma unroll
@@ -326,7 +495,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      slot_cur[u] = idx[t_begin + min(tl[u] + kAttWaves * TT * U, len - 1)];
+      slot_cur[u] = idx[t_begin + min(tl[u] + NW * TT * U, len - 1)];
     float z[U];
     float m_new = m;
 #pragma unroll
@@ -371,100 +540,64 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
     }
   }
 
-  // ---- merge: every lane group of every wave leaves its partial state in LDS; after ONE barrier each
-  // thread works out, redundantly, the maxima and normalisers it needs (no second barrier), the first
-  // HT*D threads each reduce one output element, and everybody goes on to the score update.
-  constexpr int NP = kAttWaves * TT;                // partial states per head
-  {
-    const int pi = wave * TT + ts;
-    if (dl == 0) { s_pm[pi][hs] = m; s_pl[pi][hs] = l; }
+#endif
+  // ---- merge, step 1 (registers): the TT lane groups of a wave that worked on the same head bring their
+  // states to the wave's maximum and add them up across lanes; every lane ends up with the wave's state.
+  if constexpr (TT > 1) {
+    float M = m;
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) s_pacc[(pi * HT + hs) * STR + dl * EPL + e] = acc[e];
+    for (int x = LPR * HT; x < kWave; x <<= 1)
+      M = x == 8 ? xor_max<8>(M) : x == 16 ? xor_max<16>(M) : xor_max<32>(M);
+    const float sc = (m == -INFINITY) ? 0.0f : fast_exp2(m - M);     // a group that saw no token weighs 0
+    l *= sc;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] *= sc;
+#pragma unroll
+    for (int x = LPR * HT; x < kWave; x <<= 1) {
+      l = x == 8 ? xor_sum<8>(l) : x == 16 ? xor_sum<16>(l) : xor_sum<32>(l);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[e] = x == 8 ? xor_sum<8>(acc[e]) : x == 16 ? xor_sum<16>(acc[e]) : xor_sum<32>(acc[e]);
+    }
+    m = M;
+  }
+  // ---- step 2 (LDS): one state per (wave, head); after ONE barrier every thread works out the
+  // normalisers it needs itself, the first HT*D threads each finish one output element
+  if (ts == 0) {
+    if (dl == 0) { s_wm[wave][hs] = m; s_wl[wave][hs] = l; }
+    float4* dst = reinterpret_cast<float4*>(&s_wacc[(wave * HT + hs) * D + dl * EPL]);
+#pragma unroll
+    for (int e = 0; e < EPL; e += 4) dst[e / 4] = make_float4(acc[e], acc[e + 1], acc[e + 2], acc[e + 3]);
   }
   __syncthreads();
-  float lse2_h[HT];                                 // log2-domain log-sum-exp of this chunk, per head
-  if constexpr (kSplitMerge) {
-    constexpr int PPS = NP / S;                     // partials each thread adds
-    const int d = tid / S, qv = tid - d * S;
-    float M = -INFINITY;
+  // Section 4.2: the query token's row enters the cache (nothing in this launch reads it from there)
+  if (new_slot >= 0 && chunk == n_chunks - 1 && wave == 0 && ts == 0 && head_ok) {
+    const long long off = (long long)new_slot * A.slot_stride_b;
+    store16(kb + off, nk);
+    store16(vb + off, nv);
+  }
+  for (int o = tid; o < heads_here * D; o += kAttThreads) {
+    const int sb = o / D, d = o - sb * D;
+    float mw[NW], M = -INFINITY;
 #pragma unroll
-    for (int pi = 0; pi < NP; ++pi) M = fmaxf(M, s_pm[pi][0]);
+    for (int w = 0; w < NW; ++w) { mw[w] = s_wm[w][sb]; M = fmaxf(M, mw[w]); }
     float L = 0.0f, a = 0.0f;
 #pragma unroll
-    for (int k = 0; k < PPS; ++k) {
-      const int pi = k * S + qv;
-      const float mp = s_pm[pi][0];
-      const float wgt = (mp == -INFINITY) ? 0.0f : fast_exp2(mp - M);      // empty partial: weight 0
-      L = fmaf(s_pl[pi][0], wgt, L);
-      a = fmaf(s_pacc[pi * STR + d], wgt, a);
+    for (int w = 0; w < NW; ++w) {
+      const float wgt = (mw[w] == -INFINITY) ? 0.0f : fast_exp2(mw[w] - M);      // empty wave: weight 0
+      L = fmaf(s_wl[w][sb], wgt, L);
+      a = fmaf(s_wacc[(w * HT + sb) * D + d], wgt, a);
     }
-#pragma unroll
-    for (int x = 1; x < S; x <<= 1) {               // the S splits of a column sit in adjacent lanes
-      L += __shfl_xor(L, x, kWave);
-      a += __shfl_xor(a, x, kWave);
-    }
-    lse2_h[0] = M + __log2f(L);
-    if (qv == 0) {
-      const int hd = hg;
-      if (direct) {
-        const float val = a / L;
-        const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
-        if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
-        else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
-        if (d == 0) A.lse[(size_t)b * A.n_heads + hd] = lse2_h[0] * kLn2;
-      } else {
-        const size_t pidx = ((size_t)b * A.n_heads + hd) * n_chunks + chunk;
-        st_dev(A.part_acc + pidx * D + d, a);
-        if (d == 0) st_dev2(A.part_ml + pidx * 2, M, L);
-      }
-    }
-  } else {
-    float M_mine = -INFINITY, L_mine = 1.0f;
-    const int o_sb = (tid / D) % HT;                 // head of the output element this thread reduces first
-  #pragma unroll
-    for (int sb = 0; sb < HT; ++sb) {
-      float M = -INFINITY;
-  #pragma unroll
-      for (int pi = 0; pi < NP; ++pi) M = fmaxf(M, s_pm[pi][sb]);
-      float L = 0.0f;
-  #pragma unroll
-      for (int pi = 0; pi < NP; ++pi) {
-        const float mp = s_pm[pi][sb];
-        L = fmaf(s_pl[pi][sb], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - M), L);   // empty partial: weight 0
-      }
-      lse2_h[sb] = M + __log2f(L);
-      if (sb == o_sb) { M_mine = M; L_mine = L; }
-    }
-    for (int o = tid; o < heads_here * D; o += kAttThreads) {
-      const int sb = o / D, d = o - sb * D;
-      float Mo = M_mine, Lo = L_mine;
-      if (o >= kAttThreads) {                         // second pass (HT*D > 256): redo this head's scalars
-        Mo = -INFINITY;
-        for (int pi = 0; pi < NP; ++pi) Mo = fmaxf(Mo, s_pm[pi][sb]);
-        Lo = 0.0f;
-        for (int pi = 0; pi < NP; ++pi) {
-          const float mp = s_pm[pi][sb];
-          Lo = fmaf(s_pl[pi][sb], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - Mo), Lo);
-        }
-      }
-      float a = 0.0f;
-  #pragma unroll
-      for (int pi = 0; pi < NP; ++pi) {
-        const float mp = s_pm[pi][sb];
-        a = fmaf(s_pacc[(pi * HT + sb) * STR + d], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - Mo), a);
-      }
-      const int hd = hg * HT + sb;
-      if (direct) {
-        const float val = a / Lo;
-        const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
-        if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
-        else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
-        if (d == 0) A.lse[(size_t)b * A.n_heads + hd] = (Mo + __log2f(Lo)) * kLn2;
-      } else {
-        const size_t pidx = ((size_t)b * A.n_heads + hd) * n_chunks + chunk;
-        st_dev(A.part_acc + pidx * D + d, a);
-        if (d == 0) st_dev2(A.part_ml + pidx * 2, Mo, Lo);
-      }
+    const int hd = hg * HT + sb;
+    if constexpr (DIRECT) {
+      const float val = __fdividef(a, L);
+      const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
+      if (EB == 4) reinterpret_cast<gfloat*>(out_g)[oi] = val;
+      else reinterpret_cast<ADSA_GLOBAL uint16_t*>(out_g)[oi] = (uint16_t)f32_to_bf16_rne(val);
+      if (d == 0) lse_g[(size_t)b * A.n_heads + hd] = (M + __log2f(L)) * kLn2;
+    } else {
+      const size_t pidx = ((size_t)b * A.n_heads + hd) * n_chunks + chunk;
+      st_dev(A.part_acc + pidx * D + d, a);
+      if (d == 0) st_dev2(A.part_ml + pidx * 2, M, L);
     }
   }
 
@@ -472,7 +605,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
     // |v_h|^2 and v_h.u_h of this chunk's tokens, left in LDS by the loop (the barrier above ordered them)
     if (vf_on) {
       int j0 = tid;
-      if (direct) {                                 // the first slots were fetched before the loop
+      if constexpr (DIRECT) {                       // the first slots were fetched before the loop
 #pragma unroll
         for (int k = 0; k < PF; ++k) {
           const int j = tid + k * kAttThreads;
@@ -491,29 +624,66 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
       }
     }
   }
-  if (direct) {
+  if constexpr (DIRECT) {
     // -------- per-head attention mass: score[head][slot] += p, from the logits still in LDS
     if (A.accumulate) {
+      // log2-domain log-sum-exp of the head(s): one head -> every thread redoes the few operations itself
+      float lse2_0 = 0.0f;
+      if constexpr (HT == 1) {
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, s_wm[w][0]);
+        float L = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          const float mp = s_wm[w][0];
+          L = fmaf(s_wl[w][0], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - M), L);
+        }
+        lse2_0 = M + __log2f(L);
+      } else {
+        if (tid < heads_here) {
+          float M = -INFINITY;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) M = fmaxf(M, s_wm[w][tid]);
+          float L = 0.0f;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) {
+            const float mp = s_wm[w][tid];
+            L = fmaf(s_wl[w][tid], (mp == -INFINITY) ? 0.0f : fast_exp2(mp - M), L);
+          }
+          s_lse2[tid] = M + __log2f(L);
+        }
+        __syncthreads();
+      }
 #pragma unroll
       for (int k = 0; k < PF; ++k) {                // reads were started before the loop
         const int i = tid + k * kAttThreads;
         if (i < n_pairs) {
-          const int sb = i / len, j = i - sb * len;
-          float lse2 = lse2_h[0];
-#pragma unroll
-          for (int x = 1; x < HT; ++x) lse2 = sb == x ? lse2_h[x] : lse2;
-          score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]] = pf_old[k] + fast_exp2(s_logit[sb * A.chunk_max + j] - lse2);
+          int sb = 0, j = i;
+          float lse2 = lse2_0;
+          if constexpr (HT > 1) { sb = small_div(i, len, inv_len); j = i - sb * len; lse2 = s_lse2[sb]; }
+          gfloat* sp = score + (size_t)(hg * HT + sb) * A.cap + pf_slot[k];
+          const float sv_new = pf_old[k] + fast_exp2(s_logit[sb * A.chunk_max + j] - lse2);
+#if ADSA_SCORE_ST == 1
+          __hip_atomic_store(sp, sv_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#elif ADSA_SCORE_ST == 2
+          __builtin_nontemporal_store(sv_new, sp);
+#elif ADSA_SCORE_ST == 3
+          __hip_atomic_store(sp, sv_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+#else
+          *sp = sv_new;
+#endif
         }
       }
-      if (n_pairs > PF * kAttThreads) {
-        if (tid < HT) s_lse2[tid] = lse2_h[0];      // rare long lists: hand the per-head values over through LDS
-#pragma unroll
-        for (int x = 1; x < HT; ++x) if (tid == x) s_lse2[x] = lse2_h[x];
-        __syncthreads();
+      if (n_pairs > PF * kAttThreads) {             // rare long lists
+        if constexpr (HT == 1) {
+          if (tid == 0) s_lse2[0] = lse2_0;
+          __syncthreads();
+        }
         const int cm = A.chunk_max, cap = A.cap;
         add_mass(score, A.cap, hg * HT, s_lse2, n_pairs - PF * kAttThreads, [=](int i, int* sb, int* slot, float* z) {
           const int ii = i + PF * kAttThreads;
-          *sb = ii / len; const int j = ii - *sb * len;
+          *sb = HT == 1 ? 0 : small_div(ii, len, inv_len); const int j = ii - *sb * len;
           *slot = min(max(idx[j], 0), cap - 1); *z = s_logit[*sb * cm + j];
         });
       }
@@ -523,115 +693,126 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
     // handing the kernel's argument struct to a helper by reference made every variant slower.)
     if (hg == 0 && tid == 0) {
       if constexpr (VF) {
-        if (sq.vcos_u) {
-          float* tags = sq.vcos_u + (size_t)A.n_heads * D;
-          const float want = (float)(sq.step + 2);
+        if (u_state) {
+          gfloat* tags = u_state + (size_t)A.n_heads * D;
+          const float want = (float)(sqp->step + 2);
           tags[1] = tags[0] == want ? want : 0.0f;
         }
       }
-      if (A.advance) sq.step = sq.step + 1;
+      if (A.advance) sqp->step = sqp->step + 1;
     }
     return;
-  }
-
-  // -------- several chunks: publish logits, arrive, and let the last workgroup finish the group
-  if (A.accumulate) {
-    for (int i = tid; i < heads_here * len; i += kAttThreads) {
-      const int sb = i / len, j = i - sb * len;
-      st_dev(A.logits + ((size_t)b * A.n_heads + hg * HT + sb) * A.lg_stride + t_begin + j, s_logit[sb * A.chunk_max + j]);
-    }
-  }
-  const int n_nonempty = min(cnt, n_chunks);
-  int32_t* ctr = A.counters + (size_t)b * A.n_hg + hg;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // every thread's stores have completed ...
-  __syncthreads();                                          // ... before thread 0 announces them
-  if (tid == 0) s_ticket = atomicAdd(ctr, 1);
-  __syncthreads();
-  if (s_ticket != n_nonempty - 1) return;
-  if (tid == 0) *ctr = 0;                           // ready for the next launch
-
-  const bool all_full = cnt >= n_chunks;            // else only `cnt` scattered chunks hold a token
-  for (int o = tid; o < heads_here * D; o += kAttThreads) {
-    const int sb = o / D, d = o - sb * D;
-    const int hd = hg * HT + sb;
-    const size_t pbase = ((size_t)b * A.n_heads + hd) * n_chunks;
-    float mc[kMaxChunks], lc[kMaxChunks], ac[kMaxChunks];
-#pragma unroll
-    for (int c = 0; c < kMaxChunks; ++c) {          // all loads in flight together
-      const bool on = c < n_chunks && (all_full || chunk_begin(cnt, c, n_chunks) < chunk_begin(cnt, c + 1, n_chunks));
-      mc[c] = on ? ld_dev(A.part_ml + (pbase + c) * 2) : -INFINITY;
-      lc[c] = on ? ld_dev(A.part_ml + (pbase + c) * 2 + 1) : 0.0f;
-      ac[c] = on ? ld_dev(A.part_acc + (pbase + c) * D + d) : 0.0f;
-    }
-    float Mx = -INFINITY;
-#pragma unroll
-    for (int c = 0; c < kMaxChunks; ++c) Mx = fmaxf(Mx, mc[c]);
-    float Lx = 0.0f, a = 0.0f;
-#pragma unroll
-    for (int c = 0; c < kMaxChunks; ++c) {
-      const float wgt = (mc[c] == -INFINITY) ? 0.0f : fast_exp2(mc[c] - Mx);
-      Lx = fmaf(lc[c], wgt, Lx);
-      a = fmaf(ac[c], wgt, a);
-    }
-    const float val = a / Lx;
-    const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
-    if (EB == 4) reinterpret_cast<float*>(A.out)[oi] = val;
-    else reinterpret_cast<uint16_t*>(A.out)[oi] = (uint16_t)f32_to_bf16_rne(val);
-    if (d == 0) {
-      const float lse2 = Mx + __log2f(Lx);
-      A.lse[(size_t)b * A.n_heads + hd] = lse2 * kLn2;
-      s_lse2[sb] = lse2;
-    }
-  }
-  if (A.accumulate) {
-    __syncthreads();
-    const float* lg = A.logits + ((size_t)b * A.n_heads + hg * HT) * A.lg_stride;
-    const int lgs = A.lg_stride, cap = A.cap;
-    add_mass(score, A.cap, hg * HT, s_lse2, heads_here * cnt, [=](int i, int* sb, int* slot, float* z) {
-      *sb = i / cnt; const int j = i - *sb * cnt;
-      *slot = min(max(idx[j], 0), cap - 1); *z = ld_dev(lg + (size_t)*sb * lgs + j);
-    });
-  }
-  if (hg == 0 && tid == 0) {
-    if constexpr (VF) {
-      if (sq.vcos_u) {
-        float* tags = sq.vcos_u + (size_t)A.n_heads * D;
-        const float want = (float)(sq.step + 2);
-        tags[1] = tags[0] == want ? want : 0.0f;
+  } else {
+    // -------- several chunks: publish logits, arrive, and let the last workgroup finish the group.
+    // Hand-off between workgroups (possibly on different XCDs, whose L2s are not coherent with each
+    // other): partials and logits are written with device-scope atomic stores (written through, never
+    // left dirty in an L2); every thread waits until its own stores have completed, the barrier
+    // collects the workgroup, and one thread bumps the arrival counter with a device-scope
+    // release/acquire read-modify-write.  The workgroup that draws the last ticket reads the partials
+    // with device-scope atomic loads, issued after the barrier that follows its acquire.
+    if (A.accumulate) {
+      for (int i = tid; i < heads_here * len; i += kAttThreads) {
+        const int sb = HT == 1 ? 0 : small_div(i, len, inv_len), j = i - sb * len;
+        st_dev(A.logits + ((size_t)b * A.n_heads + hg * HT + sb) * A.lg_stride + t_begin + j, s_logit[sb * A.chunk_max + j]);
       }
     }
-    if (A.advance) sq.step = sq.step + 1;
+    const int n_nonempty = min(cnt, n_chunks);
+    int32_t* ctr = A.counters + (size_t)b * A.n_hg + hg;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this thread's stores have completed ...
+    __syncthreads();                                          // ... and so have everybody's, before thread 0 announces them
+    if (tid == 0) s_ticket = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_ticket != n_nonempty - 1) return;
+    if (tid == 0) *ctr = 0;                         // ready for the next launch
+
+    const bool all_full = cnt >= n_chunks;          // else only `cnt` scattered chunks hold a token
+    for (int o = tid; o < heads_here * D; o += kAttThreads) {
+      const int sb = o / D, d = o - sb * D;
+      const int hd = hg * HT + sb;
+      const size_t pbase = ((size_t)b * A.n_heads + hd) * n_chunks;
+      float mc[kMaxChunks], lc[kMaxChunks], ac[kMaxChunks];
+#pragma unroll
+      for (int c = 0; c < kMaxChunks; ++c) {        // all loads in flight together
+        const bool on = c < n_chunks && (all_full || chunk_begin(cnt, c, n_chunks) < chunk_begin(cnt, c + 1, n_chunks));
+        mc[c] = on ? ld_dev(A.part_ml + (pbase + c) * 2) : -INFINITY;
+        lc[c] = on ? ld_dev(A.part_ml + (pbase + c) * 2 + 1) : 0.0f;
+        ac[c] = on ? ld_dev(A.part_acc + (pbase + c) * D + d) : 0.0f;
+      }
+      float Mx = -INFINITY;
+#pragma unroll
+      for (int c = 0; c < kMaxChunks; ++c) Mx = fmaxf(Mx, mc[c]);
+      float Lx = 0.0f, a = 0.0f;
+#pragma unroll
+      for (int c = 0; c < kMaxChunks; ++c) {
+        const float wgt = (mc[c] == -INFINITY) ? 0.0f : fast_exp2(mc[c] - Mx);
+        Lx = fmaf(lc[c], wgt, Lx);
+        a = fmaf(ac[c], wgt, a);
+      }
+      const float val = __fdividef(a, Lx);
+      const size_t oi = ((size_t)b * A.n_heads + hd) * D + d;
+      if (EB == 4) reinterpret_cast<gfloat*>(out_g)[oi] = val;
+      else reinterpret_cast<ADSA_GLOBAL uint16_t*>(out_g)[oi] = (uint16_t)f32_to_bf16_rne(val);
+      if (d == 0) {
+        const float lse2 = Mx + __log2f(Lx);
+        lse_g[(size_t)b * A.n_heads + hd] = lse2 * kLn2;
+        s_lse2[sb] = lse2;
+      }
+    }
+    if (A.accumulate) {
+      __syncthreads();
+      const float* lg = A.logits + ((size_t)b * A.n_heads + hg * HT) * A.lg_stride;
+      const int lgs = A.lg_stride, cap = A.cap;
+      const float inv_cnt = 1.0f / (float)cnt;
+      add_mass(score, A.cap, hg * HT, s_lse2, heads_here * cnt, [=](int i, int* sb, int* slot, float* z) {
+        *sb = HT == 1 ? 0 : small_div(i, cnt, inv_cnt); const int j = i - *sb * cnt;
+        *slot = min(max(idx[j], 0), cap - 1); *z = ld_dev(lg + (size_t)*sb * lgs + j);
+      });
+    }
+    if (hg == 0 && tid == 0) {
+      if constexpr (VF) {
+        if (u_state) {
+          gfloat* tags = u_state + (size_t)A.n_heads * D;
+          const float want = (float)(sqp->step + 2);
+          tags[1] = tags[0] == want ? want : 0.0f;
+        }
+      }
+      if (A.advance) sqp->step = sqp->step + 1;
+    }
   }
 }
 
-template <int EB, int D, int HT, int NW, bool VF = false>
+template <int EB, int D, int HT, int NW, bool VF, bool DIRECT>
 hipError_t launch_attend_w(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
   // row pairs in flight per lane; 8 was measured slower (register pressure).  A 16-wave workgroup has
   // 128 registers per lane: 2 pairs fit without spilling, and its 1024 lanes keep enough in flight
-  constexpr int U = NW == 16 ? 2 : 4;
+  constexpr int U = NW == 16 ? 2 : ADSA_U;
   const size_t lds = (size_t)(VF ? 2 : HT) * plan.chunk_max * sizeof(float);
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
+    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF, DIRECT>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
   else
-    hipLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF>), grid, dim3(NW * kWave), lds, st, A);
+    hipLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF, DIRECT>), grid, dim3(NW * kWave), lds, st, A);
   return hipGetLastError();
+}
+
+template <int EB, int D, int HT, bool VF>
+hipError_t launch_attend_v(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
+                           hipEvent_t ev_start, hipEvent_t ev_stop) {
+  if (plan.n_chunks > 1)       // split lists always run with 4-wave workgroups
+    return launch_attend_w<EB, D, HT, 4, VF, false>(A, plan, n_seq, st, ev_start, ev_stop);
+  if (plan.waves == 16) return launch_attend_w<EB, D, HT, 16, VF, true>(A, plan, n_seq, st, ev_start, ev_stop);
+  if (plan.waves == 8) return launch_attend_w<EB, D, HT, 8, VF, true>(A, plan, n_seq, st, ev_start, ev_stop);
+  return launch_attend_w<EB, D, HT, 4, VF, true>(A, plan, n_seq, st, ev_start, ev_stop);
 }
 
 template <int EB, int D, int HT>
 hipError_t launch_attend_t(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
   if constexpr (HT == 1) {
-    if (A.vcos_fused) {
-      if (plan.waves == 16) return launch_attend_w<EB, D, HT, 16, true>(A, plan, n_seq, st, ev_start, ev_stop);
-      if (plan.waves == 8) return launch_attend_w<EB, D, HT, 8, true>(A, plan, n_seq, st, ev_start, ev_stop);
-      return launch_attend_w<EB, D, HT, 4, true>(A, plan, n_seq, st, ev_start, ev_stop);
-    }
+    if (A.vcos_fused) return launch_attend_v<EB, D, HT, true>(A, plan, n_seq, st, ev_start, ev_stop);
   }
-  if (plan.waves == 16) return launch_attend_w<EB, D, HT, 16>(A, plan, n_seq, st, ev_start, ev_stop);
-  if (plan.waves == 8) return launch_attend_w<EB, D, HT, 8>(A, plan, n_seq, st, ev_start, ev_stop);
-  return launch_attend_w<EB, D, HT, 4>(A, plan, n_seq, st, ev_start, ev_stop);
+  return launch_attend_v<EB, D, HT, false>(A, plan, n_seq, st, ev_start, ev_stop);
 }
 
 __global__ void k_zero_words(uint32_t* p, size_t n) {
@@ -676,6 +857,7 @@ AttendPlan make_attend_plan(const adsa_params& p) {
   // the logits tile [heads_per_group][chunk] must fit in LDS next to the merge buffers
   const int lds_rows = p.score_mode == ADSA_SCORE_VCOS_FUSED ? 2 : a.heads_per_group;    // floats of LDS per token
   while (nc < kMaxChunks && (size_t)lds_rows * ((p.sel_cap + nc - 1) / nc + 1) * sizeof(float) > 40 * 1024) ++nc;
+  if (nc > 1) a.waves = 4;      // split lists run as 4-wave workgroups (more of them instead of wider ones)
   a.n_chunks = nc;
   a.chunk_max = (p.sel_cap + nc - 1) / nc + 1;
   return a;
