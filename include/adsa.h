@@ -46,6 +46,7 @@ extern "C" {
 
 #define ADSA_VERSION 1
 #define ADSA_MAX_CAP 8192      /* largest `cap` (slots per sequence) the select/compact kernels accept */
+#define ADSA_STATIC_SCRATCH_BYTES (4u << 20)   /* built-in scratch of adsa_step_static, per GPU */
 
 typedef enum {
   ADSA_OK = 0,
@@ -56,7 +57,8 @@ typedef enum {
   ADSA_ERR_CAPACITY = -5,      /* cap or sel_cap too small / above ADSA_MAX_CAP */
   ADSA_ERR_WORKSPACE = -6,     /* workspace missing or smaller than adsa_workspace_bytes() */
   ADSA_ERR_LAUNCH = -7,        /* the HIP runtime refused a launch */
-  ADSA_ERR_UNSUPPORTED = -8    /* valid request this build does not implement */
+  ADSA_ERR_UNSUPPORTED = -8,   /* valid request this build does not implement */
+  ADSA_ERR_STATIC_SCRATCH = -9 /* adsa_step_static: these parameters need more than ADSA_STATIC_SCRATCH_BYTES */
 } adsa_status;
 
 typedef enum { ADSA_F32 = 0, ADSA_BF16 = 1 } adsa_dtype;
@@ -259,6 +261,20 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
               const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
               int32_t* keep_map, uint32_t flags, void* workspace, size_t workspace_bytes,
               void* stream);
+
+/*
+ * adsa_step for callers that cannot allocate device memory or carry a workspace around: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same kernels and
+ * same results as adsa_step, but the scratch memory is a built-in array of ADSA_STATIC_SCRATCH_BYTES that
+ * every GPU the library runs on holds until the process ends; the call allocates nothing (its address is
+ * looked up once per device, at the first call there).  Parameters whose adsa_workspace_bytes() exceeds
+ * ADSA_STATIC_SCRATCH_BYTES are rejected with ADSA_ERR_STATIC_SCRATCH before anything is launched.
+ * All calls on one GPU share the one array: calls ordered on one stream are fine, calls that may
+ * overlap on the same GPU (different streams or host threads) race.
+ */
+int adsa_step_static(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
+                     const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
+                     int32_t* keep_map, uint32_t flags, void* stream);
 
 /* Timing hook for benchmarks: when enabled, adsa_attend/adsa_step attach a start and a stop HIP
    event to every attention-kernel dispatch on the caller's stream.  adsa_profile_read

@@ -154,6 +154,11 @@ class LayerBatch:
                     self.keep_map, self.workspace, flags, stream)
 
 
+    def step_static(self, q, k_new, v_new, flags: int = 0, stream=None):
+        B.adsa_step_static(self.params, self.seqs, q, k_new, v_new, self.out, self.lse, self.sel_idx, self.sel_cnt,
+                           self.keep_map, flags, stream)
+
+
 class ModelBatch(LayerBatch):
     """Caches of ALL layers of a model for one decode batch, laid out as n_layers * n_seq
     independent sequences (layer-major), so that the q-independent phases of a decode step

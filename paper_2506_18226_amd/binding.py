@@ -22,9 +22,12 @@ MAX_CAP = 8192
 EVICT_ROW_END, EVICT_WHEN_FULL, EVICT_REUSE_SLOT = 0, 1, 2
 
 ERRORS = {0: "ADSA_OK", -1: "ADSA_ERR_NULL", -2: "ADSA_ERR_SHAPE", -3: "ADSA_ERR_DTYPE", -4: "ADSA_ERR_ALIGN",
-          -5: "ADSA_ERR_CAPACITY", -6: "ADSA_ERR_WORKSPACE", -7: "ADSA_ERR_LAUNCH", -8: "ADSA_ERR_UNSUPPORTED"}
+          -5: "ADSA_ERR_CAPACITY", -6: "ADSA_ERR_WORKSPACE", -7: "ADSA_ERR_LAUNCH", -8: "ADSA_ERR_UNSUPPORTED",
+          -9: "ADSA_ERR_STATIC_SCRATCH"}
+STATIC_SCRATCH_BYTES = 4 << 20
 
 EXPORTS = ["adsa_workspace_bytes", "adsa_workspace_init", "adsa_select", "adsa_attend", "adsa_compact", "adsa_step",
+           "adsa_step_static",
            "adsa_profile_enable", "adsa_profile_read", "adsa_strerror", "adsa_version"]
 
 
@@ -93,6 +96,8 @@ def load_library() -> C.CDLL:
         lib.adsa_compact.argtypes = [pp, vp, i32p, C.c_uint32, vp, C.c_size_t, vp]
         lib.adsa_step.restype = C.c_int
         lib.adsa_step.argtypes = [pp, vp, vp, vp, vp, vp, f32p, i32p, i32p, i32p, C.c_uint32, vp, C.c_size_t, vp]
+        lib.adsa_step_static.restype = C.c_int
+        lib.adsa_step_static.argtypes = [pp, vp, vp, vp, vp, vp, f32p, i32p, i32p, i32p, C.c_uint32, vp]
         lib.adsa_profile_enable.restype = C.c_int
         lib.adsa_profile_enable.argtypes = [C.c_int]
         lib.adsa_profile_read.restype = C.c_int
@@ -197,6 +202,13 @@ def adsa_step(params, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_ma
     _check(load_library().adsa_step(C.byref(params), _ptr(seqs), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                     _ptr(lse), _ptr(sel_idx), _ptr(sel_cnt), _ptr(keep_map), flags,
                                     _ptr(workspace), _nbytes(workspace), _stream(stream)), "adsa_step")
+
+
+def adsa_step_static(params, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags=0, stream=None) -> None:
+    """adsa_step on the library's built-in scratch array: no workspace argument, no allocation."""
+    _check(load_library().adsa_step_static(C.byref(params), _ptr(seqs), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                           _ptr(lse), _ptr(sel_idx), _ptr(sel_cnt), _ptr(keep_map), flags,
+                                           _stream(stream)), "adsa_step_static")
 
 
 def adsa_profile_enable(on: bool) -> None:

@@ -89,6 +89,78 @@ hipError_t timed_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq* 
                        advance, new_f32 && p.dtype == ADSA_BF16, st, e0, e1);
 }
 
+// ---- built-in scratch of adsa_step_static: one array per GPU, held until the process ends.  In host code
+// the array's NAME is only a handle for hipGetSymbolAddress: the address kernels and fills are given is the
+// one that call returns, kept per device.
+constexpr size_t kStaticScratchBytes = ADSA_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+struct StaticScratch {
+  char* ptr = nullptr;          // device address of `scratch` on this GPU
+  size_t zero_bytes = 0;        // leading bytes (arrival counters) the last call's layout kept at zero; 0 = none yet
+};
+StaticScratch g_static[kMaxDevices];
+
+}  // namespace
+}  // namespace adsa
+
+static __device__ __align__(256) unsigned char scratch[adsa::kStaticScratchBytes];
+
+namespace adsa {
+namespace {
+
+// Device address of this GPU's scratch array (resolved once per device, with that device current).
+int static_scratch(StaticScratch** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ADSA_ERR_LAUNCH;
+  StaticScratch& s = g_static[dev];
+  if (!s.ptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return ADSA_ERR_LAUNCH;
+    s.ptr = static_cast<char*>(ptr);
+    s.zero_bytes = 0;
+  }
+  *out = &s;
+  return ADSA_OK;
+}
+
+// One whole decode step (the body of adsa_step / adsa_step_static); ws is laid out as w.
+int step_launches(const adsa_params* p, const AttendPlan& plan, const Workspace& w, adsa_seq* seqs, const void* q,
+                  const void* k_new, const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
+                  int32_t* keep_map, uint32_t flags, char* ws, hipStream_t st) {
+  const bool compact = !(flags & ADSA_FLAG_NO_COMPACT);
+  const bool vcos = is_vcos(*p);
+  const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS;
+  const bool streaming = p->evict_policy != ADSA_EVICT_ROW_END;
+  if (streaming && compact) {          // Section 4.2 as written: make room BEFORE the insertion
+    if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+    if (launch_compact(*p, seqs, keep_map, ws, w, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+    if (p->score_mode == ADSA_SCORE_VCOS_FUSED && launch_vcos_advance(*p, seqs, st) != hipSuccess)
+      return ADSA_ERR_LAUNCH;
+  }
+  if (vcos && !streaming && launch_vcos(*p, seqs, false, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  if (launch_select(*p, seqs, sel_idx, sel_cnt, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  if (timed_attend(*p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, ws, w, accumulate, true,
+                   !compact || streaming, (flags & ADSA_FLAG_NEW_F32) != 0, st) != hipSuccess)
+    return ADSA_ERR_LAUNCH;
+  if (compact && !streaming) {
+    if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+    if (launch_compact(*p, seqs, keep_map, ws, w, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+  }
+  return ADSA_OK;
+}
+
+int check_step_args(const adsa_params* p, const adsa_seq* seqs, const void* q, const void* k_new, const void* v_new,
+                    const void* out, const float* lse, const int32_t* sel_idx, const int32_t* sel_cnt,
+                    const int32_t* keep_map, uint32_t flags) {
+  int rc = validate_params(p);
+  if (rc) return rc;
+  const bool compact = !(flags & ADSA_FLAG_NO_COMPACT);
+  if (!seqs || !q || !k_new || !v_new || !out || !lse || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
+  if (compact && !keep_map) return ADSA_ERR_NULL;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(k_new) || !aligned16(v_new)) return ADSA_ERR_ALIGN;
+  return ADSA_OK;
+}
+
 }  // namespace
 }  // namespace adsa
 
@@ -109,6 +181,7 @@ const char* adsa_strerror(int code) {
     case ADSA_ERR_WORKSPACE: return "workspace missing or too small";
     case ADSA_ERR_LAUNCH: return "HIP launch failed";
     case ADSA_ERR_UNSUPPORTED: return "not implemented in this build";
+    case ADSA_ERR_STATIC_SCRATCH: return "parameters need more scratch than adsa_step_static's built-in buffer holds";
     default: return "unknown error";
   }
 }
@@ -191,36 +264,35 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
               const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
               int32_t* keep_map, uint32_t flags, void* workspace, size_t workspace_bytes,
               void* stream) {
-  int rc = validate_params(p);
+  int rc = check_step_args(p, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags);
   if (rc) return rc;
-  const bool compact = !(flags & ADSA_FLAG_NO_COMPACT);
-  if (!seqs || !q || !k_new || !v_new || !out || !lse || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
-  if (compact && !keep_map) return ADSA_ERR_NULL;
-  if (!aligned16(q) || !aligned16(out) || !aligned16(k_new) || !aligned16(v_new)) return ADSA_ERR_ALIGN;
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
   if (rc) return rc;
+  return step_launches(p, plan, w, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags,
+                       (char*)workspace, reinterpret_cast<hipStream_t>(stream));
+}
+
+int adsa_step_static(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
+                     const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
+                     int32_t* keep_map, uint32_t flags, void* stream) {
+  int rc = check_step_args(p, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags);
+  if (rc) return rc;
+  const AttendPlan plan = make_attend_plan(*p);
+  const Workspace w = make_workspace(*p, plan);
+  if (w.total > kStaticScratchBytes) return ADSA_ERR_STATIC_SCRATCH;
+  StaticScratch* sc = nullptr;
+  rc = static_scratch(&sc);
+  if (rc) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  char* ws = (char*)workspace;
-  const bool vcos = is_vcos(*p);
-  const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS;
-  const bool streaming = p->evict_policy != ADSA_EVICT_ROW_END;
-  if (streaming && compact) {          // Section 4.2 as written: make room BEFORE the insertion
-    if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
-    if (launch_compact(*p, seqs, keep_map, ws, w, false, st) != hipSuccess) return ADSA_ERR_LAUNCH;
-    if (p->score_mode == ADSA_SCORE_VCOS_FUSED && launch_vcos_advance(*p, seqs, st) != hipSuccess)
-      return ADSA_ERR_LAUNCH;
+  // The array keeps the previous call's contents.  The arrival counters at its head must start at zero: every
+  // launch leaves its own counters zero, so only a call whose counter region differs from the previous call's
+  // (it may reach into bytes that call used for something else) clears it, with a fill kernel.
+  if (sc->zero_bytes != w.persistent_bytes) {
+    if (launch_workspace_init(sc->ptr, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
+    sc->zero_bytes = w.persistent_bytes;
   }
-  if (vcos && !streaming && launch_vcos(*p, seqs, false, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
-  if (launch_select(*p, seqs, sel_idx, sel_cnt, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
-  if (timed_attend(*p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, ws, w, accumulate, true,
-                   !compact || streaming, (flags & ADSA_FLAG_NEW_F32) != 0, st) != hipSuccess)
-    return ADSA_ERR_LAUNCH;
-  if (compact && !streaming) {
-    if (vcos && launch_vcos(*p, seqs, true, ws, w, st) != hipSuccess) return ADSA_ERR_LAUNCH;
-    if (launch_compact(*p, seqs, keep_map, ws, w, true, st) != hipSuccess) return ADSA_ERR_LAUNCH;
-  }
-  return ADSA_OK;
+  return step_launches(p, plan, w, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags, sc->ptr, st);
 }
 
 int adsa_profile_enable(int on) {
