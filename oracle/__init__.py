@@ -4,6 +4,6 @@ Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import 
 package.  It never imports the HIP package and the HIP package never imports it.
 """
 from .adsa_oracle import (  # noqa: F401
-    OracleCfg, build, classify, vcos, rank_keep, budget, select, attend, dense,
+    OracleCfg, build, classify, vcos, rank_keep, budget, select, attend,
     accumulate, compact, step, CacheState, make_cfg, PREFIX, LOCAL, CANDIDATE,
 )

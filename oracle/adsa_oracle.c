@@ -165,16 +165,6 @@ int orc_attend(const orc_cfg* c, const float* K, const float* V, const float* q,
   return 0;
 }
 
-int orc_dense(const orc_cfg* c, const float* K, const float* V, const float* q, int32_t n,
-              double* out, double* lse) {
-  int32_t* all = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
-  if (!all) return -1;
-  for (int32_t i = 0; i < n; ++i) all[i] = i;
-  int rc = orc_attend(c, K, V, q, all, n, out, lse, NULL);
-  free(all);
-  return rc;
-}
-
 int orc_accumulate(const orc_cfg* c, float* score, const int32_t* sel_idx, int32_t sel_cnt,
                    const double* probs) {
   for (int32_t t = 0; t < sel_cnt; ++t) {
@@ -252,8 +242,10 @@ int orc_compact(const orc_cfg* c, float* K, float* V, int32_t* pos, float* score
     int protect = 0;
     if (pos[i] < c->n_keep_prefix) protect = 1;
     else if (pos[i] >= P) {
-      int32_t rj = (pos[i] - P) / W;
-      if (rj >= r - R + 1 && rj <= r) protect = 1;           /* rows the next windows need */
+      int32_t j = pos[i] - P, rj = j / W;
+      if (c->win_recent_m > 0) {                             /* 1-D window (Section 4.1): the next row's queries */
+        if (j > (s - 1) + 1 - c->win_recent_m) protect = 1;  /* s .. s+W-1 see j > query - m; the first reaches furthest back */
+      } else if (rj >= r - R + 1 && rj <= r) protect = 1;    /* rows the next windows need */
     }
     flag[i] = (uint8_t)protect;
     if (!protect) rest[nr++] = i;

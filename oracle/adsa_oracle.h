@@ -45,6 +45,10 @@
  *    per sequence and ATTN_MASS sums the probabilities of all query heads.
  *  - evict_when_full (Section 4.2 as written): requires the 1-D window (win_recent_m > 0), for which
  *    a token that leaves the window never re-enters it, so evicting any candidate is safe.
+ *  - 1-D window (win_recent_m > 0) with the per-row eviction: the local region is exempt from
+ *    eviction like the prefix (Table 3: dropping it is catastrophic), so the row-end eviction keeps,
+ *    instead of the last R rows, every token a window of the NEXT row contains: image tokens
+ *    j > jq + 1 - m for the row-closing query jq (the next row's first query reaches back furthest).
  *
  * parity unpinned: the ATTN_MASS values themselves and the split of a context
  * length into prefix / window / budget are not in the paper; they are pinned
@@ -107,10 +111,6 @@ int orc_select(const orc_cfg* c, int32_t n_res, const int32_t* pos, float* score
    of them; q float [hq][D]).  out double [hq][D], lse double [hq], probs double [hq][sel_cnt] (may be NULL). */
 int orc_attend(const orc_cfg* c, const float* K, const float* V, const float* q,
                const int32_t* sel_idx, int32_t sel_cnt, double* out, double* lse, double* probs);
-
-/* Dense causal attention over the first n slots (textbook baseline of Section 3.4). */
-int orc_dense(const orc_cfg* c, const float* K, const float* V, const float* q, int32_t n,
-              double* out, double* lse);
 
 /* ATTN_MASS update from probs [hq][sel_cnt]: every query head's probability counts. */
 int orc_accumulate(const orc_cfg* c, float* score, const int32_t* sel_idx, int32_t sel_cnt,

@@ -125,16 +125,6 @@ def attend(cfg: OracleCfg, K, V, q, sel_idx, want_probs: bool = False):
     return (out, lse, probs) if want_probs else (out, lse)
 
 
-def dense(cfg: OracleCfg, K, V, q, n: int):
-    K, V, q = _f32(K), _f32(V), _f32(q)
-    h, D = cfg.n_heads * max(cfg.q_per_kv, 1), cfg.head_dim
-    out = np.empty((h, D), dtype=np.float64)
-    lse = np.empty(h, dtype=np.float64)
-    _chk(_load().orc_dense(C.byref(cfg), _p(K, C.c_float), _p(V, C.c_float), _p(q, C.c_float),
-                           C.c_int32(n), _p(out, C.c_double), _p(lse, C.c_double)), "dense")
-    return out, lse
-
-
 def accumulate(cfg: OracleCfg, score, sel_idx, probs) -> np.ndarray:
     score = _f32(score).copy()
     sel_idx = _i32(sel_idx)
@@ -222,7 +212,8 @@ def make_cfg(*, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius
         n_keep_prefix = grid_origin
     if cap <= 0:
         bmax = budget if budget_den == 0 else ((grid_origin + grid_h * grid_w) * budget_num) // budget_den
-        cap = max(grid_origin, n_keep_prefix) + bmax + (win_rows_back + 1) * grid_w
+        held = (win_rows_back + 1) * grid_w if win_recent_m <= 0 else (win_recent_m - 1) + grid_w
+        cap = max(grid_origin, n_keep_prefix) + bmax + held
     return OracleCfg(n_heads, head_dim, grid_h, grid_w, win_rows_back, win_col_radius, grid_origin,
                      n_keep_prefix, budget, budget_num, budget_den, score_mode, cap, win_recent_m,
                      evict_when_full, q_per_kv, softmax_scale)

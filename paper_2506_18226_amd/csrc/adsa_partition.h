@@ -40,12 +40,15 @@ __device__ __forceinline__ int select_class(const QueryCell& c, int pos) {
   return local ? 0 : 1;
 }
 
-// Eviction-time partition at the end of row r: 0 = pinned prefix or one of the last R completed
-// rows (every window of the next row needs them), 1 = competes for the budget.
+// Eviction-time partition at the end of row r: 0 = pinned prefix or a token some window of the next
+// row needs -- the last R completed rows (2-D window) or the m - 1 most recent tokens (1-D window: the
+// next row's first query, jq + 1, reaches back furthest, to j > jq + 1 - m) --, 1 = competes for the budget.
 __device__ __forceinline__ int evict_class(const QueryCell& c, int pos) {
   if (pos < c.n_keep_prefix) return 0;
   if (pos >= c.P) {
-    const int rj = (pos - c.P) / c.W;
+    const int j = pos - c.P;
+    if (c.recent_m > 0) return j > c.jq + 1 - c.recent_m ? 0 : 1;
+    const int rj = j / c.W;
     if (rj >= c.r - c.R + 1 && rj <= c.r) return 0;
   }
   return 1;

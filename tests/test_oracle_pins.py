@@ -458,10 +458,49 @@ def test_recent_m_window_partition_by_hand():
         assert oracle.classify(cfg, np.arange(2 + s, dtype=np.int32), s).tolist() == w, s
 
 
+@pytest.mark.parametrize("P,H,W,m,B_", [(2, 4, 4, 10, 0), (3, 5, 6, 4, 2), (1, 6, 3, 7, 1), (4, 3, 8, 2, 3), (2, 4, 5, 13, 0)])
+def test_row_end_eviction_with_the_1d_window_never_evicts_a_token_a_later_window_holds(P, H, W, m, B_):
+    """Section 4.1's local region (the m most recent tokens) combined with the per-row eviction: local
+    tokens are exempt from eviction like the prefix (Table 3: without the local region generation
+    collapses).  Over whole trajectories, for both rankings: every step attends its complete window --
+    all of image tokens jq-m+1 .. jq that exist --, a row-end eviction removes only tokens that no
+    later window contains (j <= jq + 1 - m at the row-closing query jq), keeps at most B of those,
+    and the cache never exceeds prefix + B + (m - 1) + W.  (First case: 4x4 grid, m = 10, B = 0 --
+    after the first row end the cache must still hold the whole first row, not just the prefix.)"""
+    for mode in (WL.SCORE_ATTN_MASS, WL.SCORE_VCOS):
+        wl = WL.get_workload("tiny", n_heads=2, head_dim=8, grid_h=H, grid_w=W, prefix_len=P, seed=0xF100 + m)
+        cfg = oracle.make_cfg(n_heads=2, head_dim=8, grid_h=H, grid_w=W, win_rows_back=0, win_col_radius=0,
+                              grid_origin=P, budget=B_, score_mode=mode, win_recent_m=m)
+        assert cfg.cap == P + B_ + (m - 1) + W
+        q, k, v = WL.gen_tokens(wl, 0, 0, prefix_len=P)
+        st = oracle.CacheState.from_prefix(cfg, k[:P], v[:P])
+        n_evicted = 0
+        for s in range(0, H * W + 1):
+            p = P + s - 1
+            pos_before = np.append(st.pos[:st.n_res], P + s - 1) if s >= 1 else st.pos[:st.n_res].copy()
+            res = oracle.step(cfg, st, s, q[p], k[p], v[p])
+            attended = set(pos_before[res["sel_idx"]].tolist())
+            jq = s - 1
+            window = {P + j for j in range(max(0, jq - m + 1), jq + 1)}
+            assert window <= attended and set(range(P)) <= attended, (mode, s)
+            assert len(attended) <= P + len(window) + B_, (mode, s)
+            n = st.n_res
+            assert n <= cfg.cap, (mode, s)
+            if res["compacted"]:
+                assert (s - 1) % W == W - 1
+                evicted = set(pos_before.tolist()) - set(st.pos[:n].tolist())
+                assert all(pp - P <= jq + 1 - m for pp in evicted), (mode, s, sorted(evicted))
+                older = [pp for pp in st.pos[:n].tolist() if pp >= P and pp - P <= jq + 1 - m]
+                assert len(older) <= B_, (mode, s)
+                n_evicted += len(evicted)
+        if H * W > m + B_:
+            assert n_evicted > 0
+
+
 def test_streaming_cache_is_the_baseline_until_full_then_evicts_the_most_redundant_token():
-    """Section 4.2: 'behaves identically to the baseline when the cache is not full.  Once the cache
-    reaches its capacity, we compute pairwise token similarity using Eq. 2-3 and evict the most
-    redundant token -- the one most similar to others -- before inserting the newly generated token.'
+    """Section 4.2's cache policy: until the fixed capacity is reached nothing differs from the dense
+    baseline; from then on, before each insertion, the candidate with the highest mean pairwise V-cosine
+    (Eq. 2-3) -- the most redundant one -- is evicted.
     Checked against torch: dense SDPA while not full; afterwards the evicted token is the argmax of
     the mean pairwise cosine (torch) over the candidates, the cache stays exactly full, prefix and the
     recent window are never touched, order is preserved, and attention runs over everything resident
