@@ -75,8 +75,8 @@ typedef enum {
                                   the running sum u of the candidates' normalised V vectors (adsa_seq.vcos_u,
                                   kept up to date by adsa_compact: minus the evicted row, plus the row that
                                   leaves the local window next).  The next eviction ranks from those numbers.
-                                  Needs [head][slot][D] caches, q_per_kv <= 1 and 16*n_heads*head_dim + cap
-                                  bytes of LDS <= 64 KB (else ADSA_ERR_UNSUPPORTED).  Whenever the running state
+                                  Needs [head][slot][D] caches, q_per_kv <= 1, win_recent_m >= 2 and
+                                  16*n_heads*head_dim + cap bytes of LDS <= 64 KB (else ADSA_ERR_UNSUPPORTED).  Whenever the running state
                                   does not belong to the step at hand (first use, a cache edited by the
                                   caller) the call falls back to the two-pass computation, so results never
                                   depend on it being warm */

@@ -41,6 +41,8 @@ int validate_params(const adsa_params* p) {
         p->q_per_kv > 1)
       return ADSA_ERR_UNSUPPORTED;
     if (vcos_advance_lds_bytes(*p) > 64 * 1024) return ADSA_ERR_UNSUPPORTED;
+    // m = 1: the token that turns candidate next step is not resident yet when the running sum is advanced
+    if (p->win_recent_m < 2) return ADSA_ERR_UNSUPPORTED;
   }
   if (p->q_per_kv > 1) {       // grouped queries run on the bf16 matrix cores, logits of one list in LDS
     if (p->dtype != ADSA_BF16) return ADSA_ERR_UNSUPPORTED;

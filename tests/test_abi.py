@@ -95,6 +95,7 @@ def test_fused_vcos_parameters(lib):
     assert B.score_rows(good(**ok)) == 2 * good().n_heads
     for bad in (dict(ok, layout="slot_major"), dict(ok, evict_policy=B.EVICT_WHEN_FULL),
                 dict(ok, evict_policy=B.EVICT_ROW_END, win_recent_m=0), dict(ok, q_per_kv=2),
+                dict(ok, win_recent_m=1),                             # the running sum needs the m - 1 >= 1 newest tokens local
                 dict(ok, n_heads=64, head_dim=64, cap=128)):          # 16 * h * D bytes of LDS do not fit
         p = good(**bad)
         assert B.adsa_workspace_bytes(p) == 0, bad
@@ -149,3 +150,18 @@ def test_product_package_never_imports_the_oracle():
         if f.endswith((".py", ".c", ".h")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2506_18226_amd" not in text and "adsa.h" not in text, f
+
+
+def test_static_scratch_entry_point_checks_its_arguments_on_the_host(lib):
+    """adsa_step_static validates like adsa_step and refuses parameter sets that need more scratch than its
+    built-in array, before touching the GPU."""
+    ok = 0x1000
+    p = good()
+    assert B.adsa_workspace_bytes(p) <= B.STATIC_SCRATCH_BYTES
+    assert lib.adsa_step_static(C.byref(p), None, ok, ok, ok, ok, ok, ok, ok, ok, 0, None) == -1
+    assert lib.adsa_step_static(C.byref(p), ok, ok + 4, ok, ok, ok, ok, ok, ok, ok, 0, None) == -4
+    assert lib.adsa_step_static(C.byref(good(head_dim=96)), ok, ok, ok, ok, ok, ok, ok, ok, ok, 0, None) == -2
+    big = good(n_seq=4096, n_heads=32, head_dim=128, cap=4096, sel_cap=4096, score_mode=B.SCORE_VCOS, layout="head_major")
+    assert B.adsa_workspace_bytes(big) > B.STATIC_SCRATCH_BYTES
+    rc = lib.adsa_step_static(C.byref(big), ok, ok, ok, ok, ok, ok, ok, ok, ok, 0, None)
+    assert rc == -9 and "built-in" in B.strerror(rc)

@@ -108,9 +108,8 @@ def test_step_teacher_forced(name, over, budget, steps, layout):
         n = st.n_res
         if ref["compacted"]:
             km = ref["keep_map"]
-            # the ranking saw GPU-accumulated scores: accept a different keep map only at a near tie
-            if not np.array_equal(keep_map[b, :km.size], km):
-                pytest.fail(f"{tag}: keep map differs from the oracle's")
+            # (both sides ranked the scores of the same state plus ONE step's mass: no near-tie allowance here)
+            assert np.array_equal(keep_map[b, :km.size], km), f"{tag}: keep map differs from the oracle's"
         assert seqs["n_res"][b] == n, tag
         assert np.array_equal(posd[b, :n], st.pos[:n]), tag
         assert np.array_equal(Kd[b, :n], st.K[:n]) and np.array_equal(Vd[b, :n], st.V[:n]), tag
@@ -242,6 +241,54 @@ def test_attend_matches_oracle_on_ragged_index_lists(name, over, layout):
     assert torch.equal(before, batch.score)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout,n_heads", [("head_major", 2), ("slot_major", 8)])
+def test_split_lists_sixteen_chunks_many_sequences(layout, n_heads, dtype):
+    """The split-list launch at its widest: 24 sequences whose lists are cut into 16 chunks each, so 16
+    workgroups (on different XCDs) hand partial softmax states and logits to the one that arrives last.
+    List lengths from 1 (fewer tokens than chunks) to 640; three launches in a row on the same workspace
+    (every launch must leave the arrival counters at zero), the attention mass accumulating over them.
+    Compared with the oracle: outputs, lse and accumulated scores, for both storage types."""
+    wl = WL.get_workload("tiny", n_seq=1, n_heads=n_heads, head_dim=64, grid_h=26, grid_w=26, prefix_len=20, dtype=dtype)
+    rng = np.random.default_rng(11)
+    q, k, v = WL.gen_tokens(wl, 0, 0)
+    n_tok = 672
+    k, v = k[:n_tok], v[:n_tok]
+    lens = [1, 2, 7, 15, 16, 17, 31, 33, 100, 255, 256, 257, 400, 511, 512, 513, 600, 639, 640, 640, 48, 49, 320, 5]
+    cap = n_tok
+    params = params_for(wl, len(lens), cap, score_mode=B.SCORE_ATTN_MASS, sel_cap=640, layout=layout)
+    batch = LayerBatch(params, DEV)
+    # the launch plan is the library's; what the test relies on is checked through the workspace it asks for:
+    # [logits + 16 chunk partials per (sequence, head)] only exist when the lists are split 16 ways
+    per_head = 640 * 4 + 16 * 2 * 4 + 16 * 64 * 4
+    assert B.adsa_workspace_bytes(params) >= len(lens) * n_heads * per_head
+    cfg = oracle_cfg(wl, budget=cap, cap=cap, score_mode=B.SCORE_ATTN_MASS)
+    sels, scores = [], []
+    sel_idx = np.full((len(lens), 640), -1, np.int32)
+    for b, n in enumerate(lens):
+        sel = np.sort(rng.choice(n_tok, size=n, replace=False)).astype(np.int32)
+        sels.append(sel)
+        sel_idx[b, :n] = sel
+        sc = rng.random(n_tok).astype(np.float32)
+        scores.append(sc)
+        batch.set_sequence(b, k=k, v=v, pos=np.arange(n_tok, dtype=np.int32), score=sc, step=600,
+                           grid_origin=20, budget=cap)
+    batch.upload_seqs()
+    batch.sel_idx.copy_(torch.from_numpy(sel_idx).to(DEV))
+    batch.sel_cnt.copy_(torch.tensor(lens, dtype=torch.int32).to(DEV))
+    for launch in range(3):
+        qs = np.stack([q[50 + 30 * launch + b] for b in range(len(lens))])
+        batch.attend(to_device(qs, params.dtype, DEV))
+        torch.cuda.synchronize()
+        out, lse, rank = to_host(batch.out), batch.lse.cpu().numpy(), batch.rank_host()
+        for b, n in enumerate(lens):
+            ro, rl, probs = oracle.attend(cfg, k, v, qs[b], sels[b], want_probs=True)
+            check_out(wl, out[b], ro, f"launch {launch} len={n}")
+            assert np.abs(lse[b] - rl).max() <= lse_tol(wl), (launch, n)
+            scores[b] = oracle.accumulate(cfg, scores[b], sels[b], probs)
+            assert np.allclose(rank[b], scores[b], rtol=1e-5, atol=1e-6), (launch, n)
+
+
 # ----------------------------------------------------------------------------- compact alone
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("name,over", [("tiny", dict(n_heads=2, head_dim=64)), ("xl", dict(n_heads=20, head_dim=64)),
@@ -297,7 +344,8 @@ def test_compact_bit_exact(name, over, layout):
 def test_tiny_free_running_trajectory():
     """The whole Tiny workload (256 decode steps, compaction every row) free-running on the GPU
     against the free-running oracle.  Scores are accumulated in fp32 on the GPU and in fp64 on
-    the CPU, so the two may legitimately part ways at a near tie; until then everything matches."""
+    the CPU, so the two may part ways -- but only at a near tie of the oracle's own ranking: the
+    first differing attended set or eviction is checked for that, and reported with its margin."""
     wl = WL.get_workload("tiny")
     cfg = oracle_cfg(wl)
     P = cfg.grid_origin
@@ -308,24 +356,43 @@ def test_tiny_free_running_trajectory():
     load_state(batch, 0, st, cfg, 0)
     batch.upload_seqs()
     qd, kd, vd = (to_device(x, params.dtype, DEV) for x in (q, k, v))
-    steps_ok = 0
+    steps_ok, diverged = 0, None
+
+    def margin(a, b, score):
+        only = sorted(set(a.tolist()) ^ set(b.tolist()))
+        vals = score[only].astype(np.float64)
+        return float(vals.max() - vals.min()), only
+
     for s in range(0, wl.n_image_tokens):
         p = P + s - 1
         batch.step(qd[p:p + 1], kd[p:p + 1], vd[p:p + 1])
-        score_before = st.score.copy()
-        ref = oracle.step(cfg, st, s, q[p], k[p], v[p])
+        score_before = np.append(st.score[:st.n_res], 0.0) if s >= 1 else st.score[:st.n_res].copy()
+        ref = oracle_step_phases(cfg, st, s, q[p], k[p], v[p])
         cnt = int(batch.sel_cnt.cpu()[0])
         sel = batch.sel_idx.cpu().numpy()[0, :cnt]
         if not np.array_equal(sel, ref["sel_idx"]):
-            assert near_tie_ok(sel, ref["sel_idx"], score_before), f"s={s}: selections differ beyond a near tie"
+            mg, only = margin(sel, ref["sel_idx"], score_before)
+            diverged = f"attended sets first differ at step {s} in slots {only}: oracle score margin {mg:.3e}"
+            assert near_tie_ok(sel, ref["sel_idx"], score_before), diverged
             break
         check_out(wl, to_host(batch.out)[0], ref["out"], f"s={s}")
         seqs = batch.read_seqs()
-        if seqs["n_res"][0] != st.n_res or not np.array_equal(batch.pos.cpu().numpy()[0, :st.n_res], st.pos[:st.n_res]):
-            break                                  # eviction at a near tie: states diverge legitimately
+        assert bool(seqs["compacted"][0]) == ref["compacted"], s
+        if ref["compacted"]:
+            km, g = ref["keep_map"], batch.keep_map.cpu().numpy()[0, :ref["keep_map"].size]
+            if not np.array_equal(g, km):
+                kept_g, kept_r = np.nonzero(g >= 0)[0], np.nonzero(km >= 0)[0]
+                mg, only = margin(kept_g, kept_r, ref["score_ranked"])
+                diverged = f"evictions first differ at step {s} in slots {only}: oracle score margin {mg:.3e}"
+                assert g[kept_g].tolist() == list(range(kept_g.size)), s
+                assert near_tie_ok(kept_g, kept_r, ref["score_ranked"]), diverged
+                break
+        assert seqs["n_res"][0] == st.n_res, s
+        assert np.array_equal(batch.pos.cpu().numpy()[0, :st.n_res], st.pos[:st.n_res]), s
         steps_ok += 1
-    print(f"tiny free-running: {steps_ok} of {wl.n_image_tokens} steps identical to the oracle")
-    assert steps_ok >= 64
+    print(f"tiny free-running: {steps_ok} of {wl.n_image_tokens} steps identical to the oracle; "
+          + (diverged or "never diverged"))
+    assert steps_ok >= 240          # (the committed kernels follow the oracle through all 256 steps)
 
 
 # ----------------------------------------------------------------------------- device-side errors
@@ -545,6 +612,8 @@ def _full_layer(wl_name, steps, layout="head_major"):
     items = []
     for b in range(n):
         P, Bud, s_r = WL.seq_geometry(wl, b)
+        if wl.budget_den > 0 and not wl.ragged:
+            Bud = None                                  # fractional budget: floor((P + s) * num / den) on both sides
         s = s_r if wl.ragged else steps[b % len(steps)]
         syn = WL.synthetic_state(wl, 0, b, s, prefix_len=P, budget=Bud)
         cfg = oracle_cfg(wl, P=P, budget=Bud, cap=cap)
@@ -598,6 +667,19 @@ def test_full_size_xxl_layer():
     batch.compact(flags=B.FLAG_ADVANCE)
     torch.cuda.synchronize()
     assert _check_full_step(wl, batch, items) >= 8
+
+
+def test_full_size_xl_layer():
+    """LlamaGen-XL-shaped layer (16 sequences x 20 heads x 64, bf16, 24x24 grid, prefix 120, budget = half the
+    current context): early, middle and deepest steps incl. three row ends (the last one is the final token),
+    every sequence checked against the oracle (selection bit-exact, float bars)."""
+    wl, params, batch, items, qd, kd, vd = _full_layer("xl", steps=[576, 552, 575, 300, 25, 24, 1, 0, 289, 480, 100, 333])
+    assert wl.budget_den > 0 and params.cap == wl.cap()
+    batch.select(flags=B.FLAG_PLAN_APPEND)
+    batch.attend(qd, flags=B.FLAG_APPEND, k_new=kd, v_new=vd)
+    batch.compact(flags=B.FLAG_ADVANCE)
+    torch.cuda.synchronize()
+    assert _check_full_step(wl, batch, items) >= 4
 
 
 @pytest.mark.parametrize("layout", LAYOUTS)
@@ -773,6 +855,7 @@ def test_streaming_cache_slot_reuse_free_running(mode, layout):
     n_evictions = 0
     for s in range(0, H * W + 1):
         p = P + s - 1
+        before = st.copy()
         batch.step(qd[p:p + 1], kd[p:p + 1], vd[p:p + 1])
         ref = oracle.step(cfg, st, s, q[p], k[p], v[p])
         torch.cuda.synchronize()
@@ -784,8 +867,17 @@ def test_streaming_cache_slot_reuse_free_running(mode, layout):
         n_evictions += int(ref["compacted"])
         posd = batch.pos.cpu().numpy()[0, :n]
         if set(posd.tolist()) != set(st.pos[:n].tolist()):
-            # a different victim is acceptable only at a near tie of the ranking (fp32 vs fp64 scores)
-            assert mode == B.SCORE_ATTN_MASS and n_evictions > 20, tag
+            # a different victim is acceptable only where the oracle's own scores of the two victims tie
+            # (GPU ranks fp32-accumulated mass, the oracle fp64)
+            only_g = sorted(set(posd.tolist()) - set(st.pos[:n].tolist()))
+            only_o = sorted(set(st.pos[:n].tolist()) - set(posd.tolist()))
+            assert mode == B.SCORE_ATTN_MASS and len(only_g) == 1 and len(only_o) == 1, tag
+            nb = before.n_res
+            sc = before.score[:nb].astype(np.float64)
+            a_ = sc[np.nonzero(before.pos[:nb] == only_g[0])[0][0]]      # the oracle evicted this one
+            b_ = sc[np.nonzero(before.pos[:nb] == only_o[0])[0][0]]      # the GPU evicted this one
+            print(f"{tag}: victims differ (positions {only_g[0]} / {only_o[0]}), oracle scores {a_:.7g} / {b_:.7g}")
+            assert abs(a_ - b_) <= 4e-6 + 1e-4 * max(abs(a_), abs(b_)), tag
             break
         order = np.argsort(posd)                         # GPU slots in position order = the oracle's order
         assert np.array_equal(posd[order], st.pos[:n]), tag
