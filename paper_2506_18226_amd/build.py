@@ -9,6 +9,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_DIR = os.path.join(_HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libadsa_hip.so")
+CEILING_PATH = os.path.join(LIB_DIR, "read_ceiling")
 SOURCES = ["api.hip", "select_compact.hip", "attend.hip", "attend_gqa.hip", "vcos.hip"]
 
 HIPCC_FLAGS = [
@@ -44,6 +45,9 @@ def build_library(verbose: bool = False) -> str:
     with ThreadPoolExecutor(max_workers=min(len(jobs), 6)) as pool:
         list(pool.map(_compile_one, jobs))
     _compile_one(([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH], verbose))
+    # measurement aid: the plain-read ceiling the attention kernel's roofline fraction is read against
+    _compile_one(([hipcc, *[f for f in flags if f != "-fPIC"], os.path.join(CSRC, "read_ceiling.hip"), "-o", CEILING_PATH],
+                  verbose))
     return LIB_PATH
 
 

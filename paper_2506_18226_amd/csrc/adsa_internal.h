@@ -84,5 +84,8 @@ hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_
                              bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_map, char* ws,
                           const Workspace& w, bool advance_step, hipStream_t st);
+// once per device, before the first launch there: kernels that may ask for more than 64 KB of dynamic LDS
+hipError_t gqa_prepare_kernels();
+hipError_t vcos_prepare_kernels();
 
 }  // namespace adsa

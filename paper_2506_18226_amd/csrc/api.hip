@@ -51,6 +51,19 @@ int validate_params(const adsa_params* p) {
   return ADSA_OK;
 }
 
+// Per-device set-up that must not sit next to a launch (it would end up inside captured graphs, and tools that
+// intercept launches see it interleaved with them): done at the library's first call on a device.
+bool g_device_ready[64] = {};
+int ensure_device_ready() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return ADSA_ERR_LAUNCH;
+  if (!g_device_ready[dev]) {
+    if (gqa_prepare_kernels() != hipSuccess || vcos_prepare_kernels() != hipSuccess) return ADSA_ERR_LAUNCH;
+    g_device_ready[dev] = true;
+  }
+  return ADSA_OK;
+}
+
 int check_workspace(const adsa_params* p, const void* ws, size_t bytes, AttendPlan* plan, Workspace* w) {
   *plan = make_attend_plan(*p);
   *w = make_workspace(*p, *plan);
@@ -200,6 +213,8 @@ int adsa_workspace_init(const adsa_params* p, void* workspace, size_t workspace_
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
   if (rc) return rc;
+  rc = ensure_device_ready();
+  if (rc) return rc;
   if (launch_workspace_init((char*)workspace, w, reinterpret_cast<hipStream_t>(stream)) != hipSuccess)
     return ADSA_ERR_LAUNCH;
   return ADSA_OK;
@@ -210,6 +225,8 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
   int rc = validate_params(p);
   if (rc) return rc;
   if (!seqs || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
+  rc = ensure_device_ready();
+  if (rc) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   // (with the evict-one-when-full policies everything resident is attended: nothing to rank at selection time)
   if (p->score_mode == ADSA_SCORE_VCOS && p->evict_policy == ADSA_EVICT_ROW_END) {
@@ -236,6 +253,8 @@ int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void*
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
   if (rc) return rc;
+  rc = ensure_device_ready();
+  if (rc) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const bool accumulate = p->score_mode == ADSA_SCORE_ATTN_MASS && !(flags & ADSA_FLAG_NO_ACCUMULATE);
   if (timed_attend(*p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, (char*)workspace, w, accumulate,
@@ -251,6 +270,8 @@ int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map, uint32
   if (!seqs || !keep_map) return ADSA_ERR_NULL;
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
+  if (rc) return rc;
+  rc = ensure_device_ready();
   if (rc) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   if (is_vcos(*p) && launch_vcos(*p, seqs, true, (char*)workspace, w, st) != hipSuccess)
@@ -271,6 +292,8 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
   if (rc) return rc;
+  rc = ensure_device_ready();
+  if (rc) return rc;
   return step_launches(p, plan, w, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags,
                        (char*)workspace, reinterpret_cast<hipStream_t>(stream));
 }
@@ -285,6 +308,8 @@ int adsa_step_static(const adsa_params* p, adsa_seq* seqs, const void* q, const 
   if (w.total > kStaticScratchBytes) return ADSA_ERR_STATIC_SCRATCH;
   StaticScratch* sc = nullptr;
   rc = static_scratch(&sc);
+  if (rc) return rc;
+  rc = ensure_device_ready();
   if (rc) return rc;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   // The array keeps the previous call's contents.  The arrival counters at its head must start at zero: every

@@ -381,12 +381,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
 template <int D, int NW>
 hipError_t launch_gqa_w(const GqaArgs& A, int n_seq, size_t lds, hipStream_t st, hipEvent_t ev_start,
                         hipEvent_t ev_stop) {
-  if (lds > 64 * 1024) {       // above the default per-launch limit (long lists only): ask for it, per device
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<D, NW>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-  }
-  dim3 grid(A.n_heads, n_seq);
+  dim3 grid(A.n_heads, n_seq);     // (lists that need more than 64 KB of LDS: see gqa_prepare_kernels)
   if (ev_start && ev_stop)
     hipExtLaunchKernelGGL((k_attend_gqa<D, NW>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
   else
@@ -402,6 +397,18 @@ hipError_t launch_gqa_d(const GqaArgs& A, int waves, int n_seq, size_t lds, hipS
 }
 
 }  // namespace
+
+// Dynamic LDS above the default 64 KB per-launch limit has to be allowed per kernel, once per device; that is done
+// here, at the library's first use of a device, not next to a launch (where it would also sit inside a captured graph).
+hipError_t gqa_prepare_kernels() {
+  const int lim = (int)kGqaMaxLds;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<64, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<64, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<128, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<128, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+  return e;
+}
+
 
 int gqa_logit_stride(const adsa_params& p) { return (p.sel_cap + 15) / 16 * 16 + 16; }
 

@@ -307,11 +307,7 @@ hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction
   else if (gpl <= 8) hipLaunchKernelGGL(k_vcos_norm_usum<8>, grid, dim3(kVcThreads), lds1, st, A);
   else if (gpl <= 16) hipLaunchKernelGGL(k_vcos_norm_usum<16>, grid, dim3(kVcThreads), lds1, st, A);
   else {
-    // 64..128 KB of LDS: above the default per-launch limit
-    if (lds1 > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_vcos_norm_usum<32>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1) != hipSuccess)
-      return hipErrorInvalidValue;
+    // (64..128 KB of LDS, above the default per-launch limit: allowed once per device by vcos_prepare_kernels)
     hipLaunchKernelGGL(k_vcos_norm_usum<32>, grid, dim3(kVcThreads), lds1, st, A);
   }
   hipError_t e = hipGetLastError();
@@ -321,5 +317,12 @@ hipError_t launch_vcos(const adsa_params& p, adsa_seq* seqs, bool for_compaction
 }
 
 int vcos_tiles(int cap) { return (cap + kVcTile - 1) / kVcTile; }
+
+// The widest first-pass kernel may need up to 128 KB of dynamic LDS (n_heads * head_dim = 8192 floats x 4 waves):
+// allowed here, once per device, at the library's first use of that device.
+hipError_t vcos_prepare_kernels() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&k_vcos_norm_usum<32>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+}
 
 }  // namespace adsa
