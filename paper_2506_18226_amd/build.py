@@ -15,6 +15,7 @@ SOURCES = ["api.hip", "select_compact.hip", "attend.hip", "attend_gqa.hip", "vco
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # never emit packed-fp32 VALU forms
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",                  # leading kernel arguments arrive in SGPRs at wave launch
     "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument",
 ]
 

@@ -22,19 +22,6 @@
 
 #include "adsa_internal.h"
 
-#ifndef ADSA_ROLLING
-#define ADSA_ROLLING 1
-#endif
-#ifndef ADSA_U
-#define ADSA_U 4
-#endif
-#ifndef ADSA_SCORE_ST
-#define ADSA_SCORE_ST 0
-#endif
-#ifndef ADSA_SCORE_NOREAD
-#define ADSA_SCORE_NOREAD 0
-#endif
-
 namespace adsa {
 namespace {
 
@@ -220,52 +207,54 @@ __device__ __forceinline__ void add_mass(gfloat* score, int cap, int row0, const
 }
 
 // DIRECT: the list of a (sequence, head group) is not split (grid.x == 1): the workgroup finishes its heads alone.
+// The arguments the first round trip needs come first, as plain scalars: the build asks for leading kernel
+// arguments to be preloaded into scalar registers at wave launch, so those loads can leave at once.
 template <int EB, int D, int HT, int U, int NW, bool VF, bool DIRECT>
-__global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
+__global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const int32_t* sel_idx_arg, const int32_t* sel_cnt_arg,
+                                                      const char* q_arg, const char* k_new_arg, const char* v_new_arg,
+                                                      int n_heads_arg, int sel_cap_arg, AttendArgs A) {
   constexpr int kAttThreads = NW * kWave;           // the waves of the workgroup share one token chunk
   constexpr int EPL = Elems<EB>::N;                 // elements per lane
   constexpr int LPR = D / EPL;                      // lanes per row
   constexpr int RPW = kWave / LPR;                  // rows per wave-load
   constexpr int TT = RPW / HT;                      // tokens per wave-load
   constexpr int PF = 1024 / kAttThreads;            // score read-modify-writes a thread starts early
-  extern __shared__ float s_logit[];                // logits tile [HT][chunk_max]
+  extern __shared__ float s_logit[];                // logits tile [HT][chunk_max] ([2][chunk_max] for VF), then
+                                                    // the chunk's slot list int [chunk_max]
   // merge: the lane groups of a wave meet in registers, the waves through these (one state per wave and head)
   __shared__ float s_wm[NW][HT], s_wl[NW][HT];
   __shared__ __attribute__((aligned(16))) float s_wacc[NW * HT * D];
   __shared__ float s_lse2[HT];
   __shared__ int s_ticket;
 
-#ifdef ADSA_ROT
-  const int chunk = DIRECT ? 0 : blockIdx.x, hg = (blockIdx.y + blockIdx.z) % gridDim.y, b = blockIdx.z;
-#else
   const int chunk = DIRECT ? 0 : blockIdx.x, hg = blockIdx.y, b = blockIdx.z;
-#endif
   const int n_chunks = DIRECT ? 1 : gridDim.x;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int sub = lane / LPR, dl = lane - sub * LPR;
   const int hs = sub % HT, ts = sub / HT;           // head and token of this lane's row within a wave-load
   const int head = hg * HT + hs;
-  const bool head_ok = head < A.n_heads;
-  const int head_c = head_ok ? head : A.n_heads - 1;
-  const int heads_here = min(HT, A.n_heads - hg * HT);
+  const int n_heads = n_heads_arg, sel_cap = sel_cap_arg;
+  const bool head_ok = head < n_heads;
+  const int head_c = head_ok ? head : n_heads - 1;
+  const int heads_here = min(HT, n_heads - hg * HT);
 
   // ---- first round trip: everything that depends on the kernel arguments only -- the count, the
   // sequence record, q and (when the list is not split, so its chunk starts at 0) the first slots of
   // the loop and the slots whose score words this thread updates at the end.  The record and the
   // count are pinned here so that they cannot drift behind the count test below.
-  ADSA_GLOBAL adsa_seq* const sqp = (ADSA_GLOBAL adsa_seq*)(A.seqs + b);
-  const int cnt_raw = ((const gint*)A.sel_cnt)[b];
+  ADSA_GLOBAL adsa_seq* const sqp = (ADSA_GLOBAL adsa_seq*)(seqs_arg + b);
+  const int cnt_raw = ((const gint*)sel_cnt_arg)[b];
   gchar* const k_base = (gchar*)sqp->k;
   gchar* const v_base = (gchar*)sqp->v;
   gfloat* const score = (gfloat*)sqp->score;
   const int pending = sqp->pending_slot;
   gfloat* const u_state = VF ? (gfloat*)sqp->vcos_u : nullptr;
-  const gint* idx = (const gint*)A.sel_idx + (size_t)b * A.sel_cap;
-  const size_t row_off = ((size_t)b * A.n_heads + head_c) * D * EB + dl * 16;
-  const gchar* const q_g = (const gchar*)A.q;
-  const gchar* const k_new_g = (const gchar*)A.k_new;
-  const gchar* const v_new_g = (const gchar*)A.v_new;
+  const gint* idx = (const gint*)sel_idx_arg + (size_t)b * sel_cap;
+  const size_t row_off = ((size_t)b * n_heads + head_c) * D * EB + dl * 16;
+  const gchar* const q_g = (const gchar*)q_arg;
+  const gchar* const k_new_g = (const gchar*)k_new_arg;
+  const gchar* const v_new_g = (const gchar*)v_new_arg;
   gchar* const out_g = (gchar*)A.out;
   gfloat* const lse_g = (gfloat*)A.lse;
   const uint4 qr = load16(q_g + row_off);
@@ -274,7 +263,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
   uint4 nk = make_uint4(0u, 0u, 0u, 0u), nv = nk;
   if (A.append) {
     if (EB == 2 && A.new_f32) {
-      const size_t off32 = ((size_t)b * A.n_heads + head_c) * D * 4 + dl * 32;
+      const size_t off32 = ((size_t)b * n_heads + head_c) * D * 4 + dl * 32;
       nk = pack8_bf16(k_new_g + off32);
       nv = pack8_bf16(v_new_g + off32);
     } else {
@@ -282,32 +271,22 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
       nv = load16(v_new_g + row_off);
     }
   }
-#if ADSA_ROLLING
   // The wave takes the TT-token units wave, wave + NW, ... of the chunk, in that order; unit number k of the
   // wave holds, for this lane, token (wave + k * NW) * TT + ts.  slot_a[u]: slot of unit u; slot_nx[u]: of the unit
-  // that takes ring position u next.
+  // that takes ring position u next.  pf_slot: the whole list (its first PF * threads entries), one entry per
+  // thread and round: staged in LDS below so that the loop finds its slots there instead of in global memory.
   int slot_a[U], slot_nx[U];
   int pf_slot[PF];
   if constexpr (DIRECT) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) slot_a[u] = idx[min((wave + u * NW) * TT + ts, A.sel_cap - 1)];
+    for (int u = 0; u < U; ++u) slot_a[u] = idx[min((wave + u * NW) * TT + ts, sel_cap - 1)];
 #pragma unroll
-    for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * kAttThreads, A.sel_cap - 1)];
+    for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * kAttThreads, sel_cap - 1)];
   }
-#else
-  int slot_cur[U];
-  int pf_slot[PF];
-  if constexpr (DIRECT) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) slot_cur[u] = idx[min(wave * TT * U + u * TT + ts, A.sel_cap - 1)];
-#pragma unroll
-    for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * kAttThreads, A.sel_cap - 1)];
-  }
-#endif
   pin_uniform(cnt_raw); pin_uniform(k_base); pin_uniform(v_base); pin_uniform(score); pin_uniform(pending);
   if constexpr (VF) pin_uniform(u_state);
 
-  const int cnt = min(cnt_raw, A.sel_cap);
+  const int cnt = min(cnt_raw, sel_cap);
   if (cnt <= 0) {                                   // inactive or rejected sequence: zero-filled row
     if (chunk == 0) {
       for (int o = tid; o < HT * D; o += kAttThreads) {
@@ -327,6 +306,21 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
   if (t_begin >= t_end) return;                     // fewer tokens than chunks
   const int len = t_end - t_begin;
   const float inv_len = 1.0f / (float)len;
+  // ---- the chunk's slot list goes to LDS (clamped to the cache: nothing below ever leaves it)
+  int* const s_idx = reinterpret_cast<int*>(s_logit + (VF ? 2 : HT) * A.chunk_max);
+  if constexpr (DIRECT) {
+#pragma unroll
+    for (int k = 0; k < PF; ++k) {
+      const int j = tid + k * kAttThreads;
+      if (j < len) s_idx[j] = min(max(pf_slot[k], 0), A.cap - 1);
+    }
+    for (int j = tid + PF * kAttThreads; j < len; j += kAttThreads) s_idx[j] = min(max(idx[j], 0), A.cap - 1);
+  } else {
+    for (int j = tid; j < len; j += kAttThreads) s_idx[j] = min(max(idx[t_begin + j], 0), A.cap - 1);
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot_a[u] = idx[t_begin + min((wave + u * NW) * TT + ts, len - 1)];
+  }
+  __syncthreads();
   // the slot adsa_select reserved for the query token (Section 4.2 append), if this launch fills it
   const int new_slot = (A.append && pending < A.cap) ? pending : -1;
 
@@ -339,26 +333,12 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
       const int i = tid + k * kAttThreads;
       pf_old[k] = 0.0f;
       if (i < n_pairs) {
-        int slot = pf_slot[k], sb = 0;
-        if constexpr (HT > 1) {                     // several heads per workgroup: pair i is not token i
-          sb = small_div(i, len, inv_len);
-          slot = idx[i - sb * len];
-        }
-        pf_slot[k] = min(max(slot, 0), A.cap - 1);
-#if !ADSA_SCORE_NOREAD
+        int sb = 0, j = i;
+        if constexpr (HT > 1) { sb = small_div(i, len, inv_len); j = i - sb * len; }   // several heads per workgroup
+        pf_slot[k] = s_idx[j];
         pf_old[k] = score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]];
-#endif
       }
     }
-  }
-  if constexpr (!DIRECT) {
-#if ADSA_ROLLING
-#pragma unroll
-    for (int u = 0; u < U; ++u) slot_a[u] = idx[t_begin + min((wave + u * NW) * TT + ts, len - 1)];
-#else
-#pragma unroll
-    for (int u = 0; u < U; ++u) slot_cur[u] = idx[t_begin + min(wave * TT * U + u * TT + ts, len - 1)];
-#endif
   }
 
   float qf[EPL];
@@ -383,7 +363,6 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
 #pragma unroll
   for (int e = 0; e < EPL; ++e) acc[e] = 0.0f;
 
-#if ADSA_ROLLING
   // Rolling gather: U units (row pairs per lane) are in flight per wave; as soon as the oldest has arrived it is
   // folded into the lane's online-softmax state and its registers are given to the next unit's loads, so the
   // number of outstanding requests stays constant instead of draining once per batch.
@@ -449,7 +428,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
     auto refill = [&](int u, int k, int slot_raw) { // ring position u <- unit k; fetch the slot of unit k + U
       const int token = (wave + k * NW) * TT + ts;
       issue(u, slot_raw, token);
-      slot_nx[u] = idx[t_begin + min(token + U * NW * TT, len - 1)];
+      slot_nx[u] = s_idx[min(token + U * NW * TT, len - 1)];
       asm volatile("" : : : "memory");             // requests leave in ring order (the wait counts rely on it)
       __builtin_amdgcn_sched_barrier(0);            // ... and before the next unit's arithmetic, which waits for ITS rows
     };
@@ -468,79 +447,6 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
 #pragma unroll
     for (int u = 0; u < U; ++u) fold(u);
   }
-#else
-  // wave w takes token groups w, w+NW, ...; a group is TT*U consecutive tokens of the chunk.
-  // The slots of the next group are fetched while this group's rows are in flight.
-  for (int g0 = wave * TT * U; g0 < len; g0 += NW * TT * U) {
-    uint4 kr[U], vr[U];
-    int tl[U];
-    const gchar* vp[U];
-    bool vnew[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      tl[u] = g0 + u * TT + ts;
-      const int slot = min(max(slot_cur[u], 0), A.cap - 1);   // never touch memory outside the cache
-      const long long off = (long long)slot * A.slot_stride_b;
-      const bool is_new = slot == new_slot;         // the query token itself: its row is in registers
-      kr[u] = load_stream16(is_new ? q_g + row_off : kb + off);
-      if (is_new) kr[u] = nk;
-      vp[u] = is_new ? q_g + row_off : vb + off;
-      vnew[u] = is_new;
-    }
-    // all K rows are requested before the V rows: the logits can start while V is still on its way
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      vr[u] = load_stream16(vp[u]);
-      if (vnew[u]) vr[u] = nv;
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-      slot_cur[u] = idx[t_begin + min(tl[u] + NW * TT * U, len - 1)];
-    float z[U];
-    float m_new = m;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      float kf[EPL];
-      Elems<EB>::unpack(kr[u], kf);
-      float d = 0.0f;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) d = fmaf(qf[e], kf[e], d);
-      d = row_sum<LPR>(d);
-      z[u] = (tl[u] < len) ? d : -INFINITY;
-      m_new = fmaxf(m_new, z[u]);
-    }
-    if (A.accumulate && dl == 0) {
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (tl[u] < len) s_logit[hs * A.chunk_max + tl[u]] = z[u];
-    }
-    if (m_new != -INFINITY) {                       // false only while a lane group has seen no token yet
-      const float corr = fast_exp2(m - m_new);
-      l *= corr;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[e] *= corr;
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const float pr = fast_exp2(z[u] - m_new);
-        float vf[EPL];
-        Elems<EB>::unpack(vr[u], vf);
-        l += pr;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] = fmaf(pr, vf[e], acc[e]);
-        if constexpr (VF) {                         // Eq. 2-3 bookkeeping of this row: |v_h|^2 and v_h . u_h
-          float dv = 0.0f, sv = 0.0f;
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) { dv = fmaf(vf[e], uf[e], dv); sv = fmaf(vf[e], vf[e], sv); }
-          dv = row_sum<LPR>(dv);
-          sv = row_sum<LPR>(sv);
-          if (dl == 0 && tl[u] < len) { s_logit[tl[u]] = sv; s_logit[A.chunk_max + tl[u]] = dv; }
-        }
-      }
-      m = m_new;
-    }
-  }
-
-#endif
   // ---- merge, step 1 (registers): the TT lane groups of a wave that worked on the same head bring their
   // states to the wave's maximum and add them up across lanes; every lane ends up with the wave's state.
   if constexpr (TT > 1) {
@@ -618,7 +524,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
         j0 = tid + PF * kAttThreads;
       }
       for (int j = j0; j < len; j += kAttThreads) {
-        const int slot = min(max(idx[t_begin + j], 0), A.cap - 1);
+        const int slot = s_idx[j];
         vrows[slot] = s_logit[j];
         vrows[A.cap + slot] = s_logit[A.chunk_max + j];
       }
@@ -664,15 +570,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
           if constexpr (HT > 1) { sb = small_div(i, len, inv_len); j = i - sb * len; lse2 = s_lse2[sb]; }
           gfloat* sp = score + (size_t)(hg * HT + sb) * A.cap + pf_slot[k];
           const float sv_new = pf_old[k] + fast_exp2(s_logit[sb * A.chunk_max + j] - lse2);
-#if ADSA_SCORE_ST == 1
-          __hip_atomic_store(sp, sv_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#elif ADSA_SCORE_ST == 2
-          __builtin_nontemporal_store(sv_new, sp);
-#elif ADSA_SCORE_ST == 3
-          __hip_atomic_store(sp, sv_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-#else
           *sp = sv_new;
-#endif
         }
       }
       if (n_pairs > PF * kAttThreads) {             // rare long lists
@@ -680,11 +578,11 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(AttendArgs A) {
           if (tid == 0) s_lse2[0] = lse2_0;
           __syncthreads();
         }
-        const int cm = A.chunk_max, cap = A.cap;
+        const int cm = A.chunk_max;
         add_mass(score, A.cap, hg * HT, s_lse2, n_pairs - PF * kAttThreads, [=](int i, int* sb, int* slot, float* z) {
           const int ii = i + PF * kAttThreads;
           *sb = HT == 1 ? 0 : small_div(ii, len, inv_len); const int j = ii - *sb * len;
-          *slot = min(max(idx[j], 0), cap - 1); *z = s_logit[*sb * cm + j];
+          *slot = s_idx[j]; *z = s_logit[*sb * cm + j];
         });
       }
     }
@@ -786,13 +684,15 @@ hipError_t launch_attend_w(const AttendArgs& A, const AttendPlan& plan, int n_se
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
   // row pairs in flight per lane; 8 was measured slower (register pressure).  A 16-wave workgroup has
   // 128 registers per lane: 2 pairs fit without spilling, and its 1024 lanes keep enough in flight
-  constexpr int U = NW == 16 ? 2 : ADSA_U;
-  const size_t lds = (size_t)(VF ? 2 : HT) * plan.chunk_max * sizeof(float);
+  constexpr int U = NW == 16 ? 2 : 4;
+  const size_t lds = (size_t)((VF ? 2 : HT) + 1) * plan.chunk_max * sizeof(float);      // logits rows + the slot list
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF, DIRECT>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
+    hipExtLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF, DIRECT>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0,
+                          A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new, A.n_heads, A.sel_cap, A);
   else
-    hipLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF, DIRECT>), grid, dim3(NW * kWave), lds, st, A);
+    hipLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF, DIRECT>), grid, dim3(NW * kWave), lds, st,
+                       A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new, A.n_heads, A.sel_cap, A);
   return hipGetLastError();
 }
 
@@ -855,7 +755,7 @@ AttendPlan make_attend_plan(const adsa_params& p) {
     if (nc > kMaxChunks) nc = kMaxChunks;
   }
   // the logits tile [heads_per_group][chunk] must fit in LDS next to the merge buffers
-  const int lds_rows = p.score_mode == ADSA_SCORE_VCOS_FUSED ? 2 : a.heads_per_group;    // floats of LDS per token
+  const int lds_rows = (p.score_mode == ADSA_SCORE_VCOS_FUSED ? 2 : a.heads_per_group) + 1;   // words of LDS per token
   while (nc < kMaxChunks && (size_t)lds_rows * ((p.sel_cap + nc - 1) / nc + 1) * sizeof(float) > 40 * 1024) ++nc;
   if (nc > 1) a.waves = 4;      // split lists run as 4-wave workgroups (more of them instead of wider ones)
   a.n_chunks = nc;
