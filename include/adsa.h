@@ -128,10 +128,15 @@ typedef struct adsa_params {
   int32_t win_rows_back;       /* R: rows above the query's row that belong to the local window */
   int32_t win_col_radius;      /* w: column radius in those rows; w >= grid_w-1 gives the paper's
                                   1-D "most recent m tokens" window */
-  int32_t sel_groups;          /* 1: one attended set per sequence shared by all heads.  For one set PER HEAD
-                                  pass every (sequence, head) as its own adsa_seq with n_heads = 1: its K/V are
-                                  that head's rows, and q / out rows [n_seq*heads][1][D] are the same memory as
-                                  [n_seq][heads][D] */
+  int32_t sel_groups;          /* 1: one attended set per sequence shared by all heads.
+                                  n_heads: one set, and one eviction history, PER (cache) HEAD (Eq. 4 does not say
+                                  which).  Every (sequence, head) then is a sequence of one head: `seqs` holds
+                                  n_seq * n_heads records, record b * n_heads + h describing head h of sequence b
+                                  (k / v point at that head's first row, rows kv_slot_stride apart -- either cache
+                                  nesting works, kv_head_stride is not used --, its own pos, score, n_res, step...);
+                                  sel_idx, sel_cnt and keep_map carry one row per record ([n_seq][n_heads][...]);
+                                  q, k_new, v_new, out, lse keep their layouts.  n_seq * n_heads <= 65535.
+                                  Any other value: ADSA_ERR_UNSUPPORTED */
   int32_t dtype;               /* adsa_dtype of q, K, V, out */
   int32_t score_mode;          /* adsa_score_mode */
   int32_t cap;                 /* slots allocated per sequence (<= ADSA_MAX_CAP) */
@@ -280,7 +285,7 @@ int adsa_step_static(const adsa_params* p, adsa_seq* seqs, const void* q, const 
    event to every attention-kernel dispatch on the caller's stream.  adsa_profile_read
    synchronises those events and returns, through its arguments, the number of timed launches and
    their summed duration in milliseconds since the last adsa_profile_enable(1); [host] pointers.
-   Process-wide state, not thread-safe. */
+   adsa_profile_enable(0) switches the hook off and destroys its events.  Process-wide state, not thread-safe. */
 int adsa_profile_enable(int on);
 int adsa_profile_read(int64_t* n_launches, double* total_ms);
 

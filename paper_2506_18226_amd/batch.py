@@ -124,10 +124,6 @@ class LayerBatch:
         v = to_host(self.V)
         return v.transpose(0, 2, 1, 3) if self.head_major else v
 
-    def rank_host(self) -> np.ndarray:
-        """Ranking value of every slot, [n_seq][cap]: the score rows summed (float64 on the host)."""
-        return self.score.cpu().numpy().astype(np.float64).sum(axis=1)
-
     def upload_seqs(self) -> None:
         raw = torch.from_numpy(self.seqs_host.view(np.uint8).reshape(-1).copy())
         self.seqs.copy_(raw.to(self.device))

@@ -152,10 +152,12 @@ def make_params(*, n_seq, n_heads, head_dim, grid_h, grid_w, win_rows_back, win_
 
 
 def score_rows(params: AdsaParams) -> int:
-    """Rows of adsa_seq.score: one per head for ATTN_MASS, two per head for VCOS_FUSED, else one."""
+    """Rows of adsa_seq.score: one per head for ATTN_MASS, two per head for VCOS_FUSED, else one.  (With per-head
+    attended sets, sel_groups == n_heads, every record describes one head.)"""
+    heads = 1 if params.sel_groups == params.n_heads else params.n_heads
     if params.score_mode == SCORE_VCOS_FUSED:
-        return 2 * params.n_heads
-    return params.n_heads if params.score_mode == SCORE_ATTN_MASS else 1
+        return 2 * heads
+    return heads if params.score_mode == SCORE_ATTN_MASS else 1
 
 
 def query_heads(params: AdsaParams) -> int:

@@ -9,7 +9,7 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int validate_params(const adsa_params* p) {
+int validate_resolved(const adsa_params* p) {
   if (!p) return ADSA_ERR_NULL;
   if (p->dtype != ADSA_F32 && p->dtype != ADSA_BF16) return ADSA_ERR_DTYPE;
   if (p->score_mode < ADSA_SCORE_ATTN_MASS || p->score_mode > ADSA_SCORE_VCOS_FUSED) return ADSA_ERR_DTYPE;
@@ -18,7 +18,7 @@ int validate_params(const adsa_params* p) {
   if (p->head_dim != 64 && p->head_dim != 128) return ADSA_ERR_SHAPE;
   if (p->grid_h < 1 || p->grid_w < 1 || (long long)p->grid_h * p->grid_w > (1 << 24)) return ADSA_ERR_SHAPE;
   if (p->win_rows_back < 0 || p->win_col_radius < 0) return ADSA_ERR_SHAPE;
-  if (p->sel_groups != 1) return ADSA_ERR_UNSUPPORTED;
+  if (p->sel_groups != 1) return ADSA_ERR_UNSUPPORTED;     // (resolve_params has rewritten the per-head form)
   if (is_vcos(*p) && (long long)p->n_heads * p->head_dim > 8192) return ADSA_ERR_UNSUPPORTED;
   if (p->cap < 1 || p->cap > ADSA_MAX_CAP) return ADSA_ERR_CAPACITY;
   if (p->sel_cap < 1 || p->sel_cap > p->cap) return ADSA_ERR_CAPACITY;
@@ -49,6 +49,28 @@ int validate_params(const adsa_params* p) {
     if (gqa_lds_bytes(*p, make_attend_plan(*p).waves) > kGqaMaxLds) return ADSA_ERR_UNSUPPORTED;
   }
   return ADSA_OK;
+}
+
+// The parameters the kernels run with.  sel_groups == 1: the caller's own.  sel_groups == n_heads (one attended
+// set, one eviction history per head; Eq. 4 does not say which): every (sequence, head) IS a sequence of one cache
+// head -- the caller passes n_seq * n_heads records, record b * n_heads + h describing head h of sequence b (its K/V
+// rows kv_slot_stride apart, its own pos / score / counters), and sel_idx, sel_cnt, keep_map carry one row per record;
+// q, k_new, v_new, out, lse keep their [n_seq][heads][...] layout, which is the same memory as
+// [n_seq * n_heads][1 (* q_per_kv)][...].
+int resolve_params(const adsa_params* p, adsa_params* eff) {
+  if (!p) return ADSA_ERR_NULL;
+  *eff = *p;
+  if (p->sel_groups != 1) {
+    if (p->n_heads < 1 || p->sel_groups != p->n_heads) return ADSA_ERR_UNSUPPORTED;
+    if (p->n_seq < 1 || (long long)p->n_seq * p->n_heads > 65535) return ADSA_ERR_SHAPE;
+    if (p->cap < 1 || p->kv_slot_stride < 1 || p->kv_head_stride < 1) return ADSA_ERR_SHAPE;
+    eff->n_seq = p->n_seq * p->n_heads;
+    eff->n_heads = 1;
+    eff->sel_groups = 1;
+    // one head per record: its rows are kv_slot_stride apart, whatever the nesting of the caller's cache
+    eff->kv_head_stride = (long long)p->cap * p->kv_slot_stride;
+  }
+  return validate_resolved(eff);
 }
 
 // Per-device set-up that must not sit next to a launch (it would end up inside captured graphs, and tools that
@@ -166,8 +188,8 @@ int step_launches(const adsa_params* p, const AttendPlan& plan, const Workspace&
 
 int check_step_args(const adsa_params* p, const adsa_seq* seqs, const void* q, const void* k_new, const void* v_new,
                     const void* out, const float* lse, const int32_t* sel_idx, const int32_t* sel_cnt,
-                    const int32_t* keep_map, uint32_t flags) {
-  int rc = validate_params(p);
+                    const int32_t* keep_map, uint32_t flags, adsa_params* eff) {
+  int rc = resolve_params(p, eff);      // *eff: the parameters the kernels run with
   if (rc) return rc;
   const bool compact = !(flags & ADSA_FLAG_NO_COMPACT);
   if (!seqs || !q || !k_new || !v_new || !out || !lse || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
@@ -202,14 +224,18 @@ const char* adsa_strerror(int code) {
 }
 
 size_t adsa_workspace_bytes(const adsa_params* p) {
-  if (validate_params(p) != ADSA_OK) return 0;
+  adsa_params eff;
+  if (resolve_params(p, &eff) != ADSA_OK) return 0;
+  p = &eff;
   AttendPlan plan = make_attend_plan(*p);
   return make_workspace(*p, plan).total;
 }
 
 int adsa_workspace_init(const adsa_params* p, void* workspace, size_t workspace_bytes, void* stream) {
-  int rc = validate_params(p);
+  adsa_params eff;
+  int rc = resolve_params(p, &eff);
   if (rc) return rc;
+  p = &eff;
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
   if (rc) return rc;
@@ -222,8 +248,10 @@ int adsa_workspace_init(const adsa_params* p, void* workspace, size_t workspace_
 
 int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
                 uint32_t flags, void* workspace, size_t workspace_bytes, void* stream) {
-  int rc = validate_params(p);
+  adsa_params eff;
+  int rc = resolve_params(p, &eff);
   if (rc) return rc;
+  p = &eff;
   if (!seqs || !sel_idx || !sel_cnt) return ADSA_ERR_NULL;
   rc = ensure_device_ready();
   if (rc) return rc;
@@ -243,8 +271,10 @@ int adsa_select(const adsa_params* p, adsa_seq* seqs, int32_t* sel_idx, int32_t*
 int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
                 const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt, void* out,
                 float* lse, uint32_t flags, void* workspace, size_t workspace_bytes, void* stream) {
-  int rc = validate_params(p);
+  adsa_params eff;
+  int rc = resolve_params(p, &eff);
   if (rc) return rc;
+  p = &eff;
   if (!seqs || !q || !sel_idx || !sel_cnt || !out || !lse) return ADSA_ERR_NULL;
   const bool append = (flags & ADSA_FLAG_APPEND) != 0;
   if (append && (!k_new || !v_new)) return ADSA_ERR_NULL;
@@ -265,8 +295,10 @@ int adsa_attend(const adsa_params* p, adsa_seq* seqs, const void* q, const void*
 
 int adsa_compact(const adsa_params* p, adsa_seq* seqs, int32_t* keep_map, uint32_t flags,
                  void* workspace, size_t workspace_bytes, void* stream) {
-  int rc = validate_params(p);
+  adsa_params eff;
+  int rc = resolve_params(p, &eff);
   if (rc) return rc;
+  p = &eff;
   if (!seqs || !keep_map) return ADSA_ERR_NULL;
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
@@ -287,8 +319,10 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
               const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
               int32_t* keep_map, uint32_t flags, void* workspace, size_t workspace_bytes,
               void* stream) {
-  int rc = check_step_args(p, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags);
+  adsa_params eff;
+  int rc = check_step_args(p, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags, &eff);
   if (rc) return rc;
+  p = &eff;
   AttendPlan plan; Workspace w;
   rc = check_workspace(p, workspace, workspace_bytes, &plan, &w);
   if (rc) return rc;
@@ -301,8 +335,10 @@ int adsa_step(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k
 int adsa_step_static(const adsa_params* p, adsa_seq* seqs, const void* q, const void* k_new,
                      const void* v_new, void* out, float* lse, int32_t* sel_idx, int32_t* sel_cnt,
                      int32_t* keep_map, uint32_t flags, void* stream) {
-  int rc = check_step_args(p, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags);
+  adsa_params eff;
+  int rc = check_step_args(p, seqs, q, k_new, v_new, out, lse, sel_idx, sel_cnt, keep_map, flags, &eff);
   if (rc) return rc;
+  p = &eff;
   const AttendPlan plan = make_attend_plan(*p);
   const Workspace w = make_workspace(*p, plan);
   if (w.total > kStaticScratchBytes) return ADSA_ERR_STATIC_SCRATCH;
@@ -324,7 +360,11 @@ int adsa_step_static(const adsa_params* p, adsa_seq* seqs, const void* q, const 
 
 int adsa_profile_enable(int on) {
   g_prof.on = on != 0;
-  if (on) g_prof.used = 0;
+  g_prof.used = 0;
+  if (!on) {                    // switching the hook off gives its events back
+    for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+    g_prof.ev.clear();
+  }
   return ADSA_OK;
 }
 

@@ -73,3 +73,8 @@ def oracle_step_phases(cfg, st, s, q, k_new, v_new):
         pass  # compact() recomputed the V-cosine over the rest itself
     return {"out": out, "lse": lse, "sel_idx": sel, "keep_map": keep_map if did else None,
             "compacted": did, "n_res": st.n_res, "score_ranked": ranked}
+
+
+def rank_host(batch) -> np.ndarray:
+    """Ranking value of every slot of a LayerBatch, [n_seq][cap]: its score rows summed (float64, on the host)."""
+    return batch.score.cpu().numpy().astype(np.float64).sum(axis=1)

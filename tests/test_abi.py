@@ -61,7 +61,7 @@ def test_workspace_size_is_positive_and_monotone(lib):
     (dict(dtype=7), -3), (dict(score_mode=9), -3), (dict(n_seq=0), -2), (dict(n_heads=0), -2),
     (dict(n_heads=300), -2), (dict(head_dim=96), -2), (dict(grid_w=0), -2), (dict(win_rows_back=-1), -2),
     (dict(cap=0), -5), (dict(cap=B.MAX_CAP + 1, sel_cap=16), -5), (dict(sel_cap=0), -5), (dict(sel_cap=129), -5),
-    (dict(sel_groups=4), -8), (dict(kv_slot_stride=4 * 64 + 4), -4), (dict(kv_head_stride=32), -2),
+    (dict(sel_groups=3), -8), (dict(sel_groups=0), -8), (dict(sel_groups=4, n_seq=20000), -2), (dict(kv_slot_stride=4 * 64 + 4), -4), (dict(kv_head_stride=32), -2),
     (dict(kv_slot_stride=64), -2), (dict(softmax_scale=-1.0), -2),
     (dict(score_mode=B.SCORE_VCOS, n_heads=128, head_dim=128), -8),
     (dict(win_recent_m=-1), -2), (dict(evict_policy=5), -3), (dict(evict_policy=B.EVICT_WHEN_FULL), -8),
@@ -76,6 +76,18 @@ def test_bad_parameters_are_rejected_before_any_launch(lib, kw, code):
     rc = lib.adsa_step(C.byref(p), fake, fake, fake, fake, fake, fake, fake, fake, fake, 0, fake, 1 << 30, None)
     assert rc == code
     assert len(B.strerror(rc)) > 3
+
+
+def test_per_head_attended_sets_are_an_abi_value(lib):
+    """sel_groups == n_heads: every (sequence, head) is a one-head sequence; the workspace is the one of
+    n_seq * n_heads single-head sequences, for either nesting of the caller's cache."""
+    one_head = good(n_seq=2 * 4, n_heads=1, layout="head_major")
+    for layout in ("slot_major", "head_major"):
+        per_head = good(sel_groups=4, layout=layout)
+        assert B.adsa_workspace_bytes(per_head) == B.adsa_workspace_bytes(one_head) > 0
+        assert B.score_rows(per_head) == 1
+    assert B.adsa_workspace_bytes(good(sel_groups=4, q_per_kv=4)) > 0
+    assert B.query_heads(good(sel_groups=4, q_per_kv=4)) == 16
 
 
 def test_grouped_query_parameters(lib):

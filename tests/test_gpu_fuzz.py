@@ -16,7 +16,7 @@ from paper_2506_18226_amd import binding as B
 from paper_2506_18226_amd import workloads as WL
 from paper_2506_18226_amd.batch import LayerBatch, to_device, to_host
 
-from common import oracle_cfg, replay, near_tie_ok, oracle_step_phases
+from common import oracle_cfg, replay, near_tie_ok, oracle_step_phases, rank_host
 from test_gpu_parity import DEV, params_for, load_state, check_out, lse_tol
 
 pytestmark = pytest.mark.gpu
@@ -67,7 +67,7 @@ def test_random_geometry_teacher_forced(seed):
     seqs = batch.read_seqs()
     out, lse = to_host(batch.out), batch.lse.cpu().numpy()
     sel_idx, sel_cnt = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
-    keep_map, posd, rank = batch.keep_map.cpu().numpy(), batch.pos.cpu().numpy(), batch.rank_host()
+    keep_map, posd, rank = batch.keep_map.cpu().numpy(), batch.pos.cpu().numpy(), rank_host(batch)
     Kd, Vd = batch.k_host(), batch.v_host()
     vcos = wl.score_mode == WL.SCORE_VCOS
     for b, s in enumerate(steps):
@@ -188,7 +188,7 @@ def test_random_streaming_cache_free_running(seed):
         assert np.array_equal(batch.k_host()[0, :n][order], st.K[:n]), tag
         assert np.array_equal(batch.v_host()[0, :n][order], st.V[:n]), tag
         if mode == B.SCORE_ATTN_MASS:
-            assert np.allclose(batch.rank_host()[0, :n][order], st.score[:n], rtol=1e-5, atol=1e-6), tag
+            assert np.allclose(rank_host(batch)[0, :n][order], st.score[:n], rtol=1e-5, atol=1e-6), tag
         check_out(wl, to_host(batch.out)[0], ref["out"], tag)
         TALLY["full"] += 1
     assert evictions >= 1 or cap >= P + H * W, tag0

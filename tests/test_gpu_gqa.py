@@ -13,7 +13,7 @@ from paper_2506_18226_amd import binding as B
 from paper_2506_18226_amd import workloads as WL
 from paper_2506_18226_amd.batch import LayerBatch, to_device, to_host
 
-from common import oracle_cfg, replay
+from common import oracle_cfg, replay, rank_host
 from test_gpu_parity import (DEV, LAYOUTS, params_for, load_state, check_out, lse_tol, _full_layer,
                              _check_full_step)
 
@@ -57,7 +57,7 @@ def test_gqa_attend_matches_oracle_on_ragged_index_lists(G, h, D, reps, layout):
     qd = to_device(np.stack([q[100 + b] for b in range(len(lens))]), params.dtype, DEV)
     batch.attend(qd)
     torch.cuda.synchronize()
-    out, lse, score = to_host(batch.out), batch.lse.cpu().numpy(), batch.rank_host()
+    out, lse, score = to_host(batch.out), batch.lse.cpu().numpy(), rank_host(batch)
     for b, n in enumerate(lens):
         ro, rl, probs = oracle.attend(cfg, k, v, q[100 + b], sels[b], want_probs=True)
         check_out(wl, out[b], ro, f"len={n} b={b}")
@@ -97,7 +97,7 @@ def test_gqa_step_teacher_forced(over, budget, steps, layout):
     out, lse = to_host(batch.out), batch.lse.cpu().numpy()
     sel_idx, sel_cnt = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
     keep_map = batch.keep_map.cpu().numpy()
-    Kd, Vd, posd, rank = batch.k_host(), batch.v_host(), batch.pos.cpu().numpy(), batch.rank_host()
+    Kd, Vd, posd, rank = batch.k_host(), batch.v_host(), batch.pos.cpu().numpy(), rank_host(batch)
     for b, s in enumerate(steps):
         st = snaps[s].copy()
         p = P + s - 1
@@ -161,7 +161,7 @@ def test_gqa_long_list_uses_the_raised_lds_limit():
     qd = to_device(np.stack([q[500], q[501]]), params.dtype, DEV)
     batch.attend(qd)
     torch.cuda.synchronize()
-    out, lse, score = to_host(batch.out), batch.lse.cpu().numpy(), batch.rank_host()
+    out, lse, score = to_host(batch.out), batch.lse.cpu().numpy(), rank_host(batch)
     for b, sel in enumerate(sels):
         ro, rl, probs = oracle.attend(cfg, k, v, q[500 + b], sel, want_probs=True)
         check_out(wl, out[b], ro, f"b={b}")

@@ -17,7 +17,7 @@ from paper_2506_18226_amd import binding as B
 from paper_2506_18226_amd import workloads as WL
 from paper_2506_18226_amd.batch import LayerBatch, ModelBatch, to_device, to_host
 
-from common import oracle_cfg, replay, near_tie_ok, oracle_step_phases
+from common import oracle_cfg, replay, near_tie_ok, oracle_step_phases, rank_host
 
 pytestmark = pytest.mark.gpu
 
@@ -92,7 +92,7 @@ def test_step_teacher_forced(name, over, budget, steps, layout):
     sel_idx, sel_cnt = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
     keep_map = batch.keep_map.cpu().numpy()
     Kd, Vd = batch.k_host(), batch.v_host()
-    posd, scored = batch.pos.cpu().numpy(), batch.rank_host()
+    posd, scored = batch.pos.cpu().numpy(), rank_host(batch)
     for b, s in enumerate(steps):
         st = snaps[s].copy()
         p = P + s - 1
@@ -227,7 +227,7 @@ def test_attend_matches_oracle_on_ragged_index_lists(name, over, layout):
     qd = to_device(np.stack([q[100 + b] for b in range(len(lens))]), params.dtype, DEV)
     batch.attend(qd)
     torch.cuda.synchronize()
-    out, lse, score = to_host(batch.out), batch.lse.cpu().numpy(), batch.rank_host()
+    out, lse, score = to_host(batch.out), batch.lse.cpu().numpy(), rank_host(batch)
     for b, n in enumerate(lens):
         ro, rl, probs = oracle.attend(cfg, k, v, q[100 + b], sels[b], want_probs=True)
         check_out(wl, out[b], ro, f"len={n}")
@@ -280,7 +280,7 @@ def test_split_lists_sixteen_chunks_many_sequences(layout, n_heads, dtype):
         qs = np.stack([q[50 + 30 * launch + b] for b in range(len(lens))])
         batch.attend(to_device(qs, params.dtype, DEV))
         torch.cuda.synchronize()
-        out, lse, rank = to_host(batch.out), batch.lse.cpu().numpy(), batch.rank_host()
+        out, lse, rank = to_host(batch.out), batch.lse.cpu().numpy(), rank_host(batch)
         for b, n in enumerate(lens):
             ro, rl, probs = oracle.attend(cfg, k, v, qs[b], sels[b], want_probs=True)
             check_out(wl, out[b], ro, f"launch {launch} len={n}")
@@ -323,7 +323,7 @@ def test_compact_bit_exact(name, over, layout):
     torch.cuda.synchronize()
     seqs = batch.read_seqs()
     km = batch.keep_map.cpu().numpy()
-    Kd, Vd, posd, scored = batch.k_host(), batch.v_host(), batch.pos.cpu().numpy(), batch.rank_host()
+    Kd, Vd, posd, scored = batch.k_host(), batch.v_host(), batch.pos.cpu().numpy(), rank_host(batch)
     for b, (s, Bud) in enumerate(cases):
         cfg, st = states[b]
         n_old = st.n_res
@@ -559,7 +559,7 @@ def test_vcos_step_teacher_forced(name, over, budget, steps, layout):
     qd, kd, vd = (to_device(np.stack(x), params.dtype, DEV) for x in (qs, kn, vn))
     batch.select(flags=B.FLAG_PLAN_APPEND)            # phase 1: scores + attended set
     torch.cuda.synchronize()
-    score_sel = batch.rank_host()
+    score_sel = rank_host(batch)
     sel_idx, sel_cnt = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
     batch.attend(qd, flags=B.FLAG_APPEND, k_new=kd, v_new=vd)
     batch.compact(flags=B.FLAG_ADVANCE)
@@ -631,7 +631,7 @@ def _check_full_step(wl, batch, items):
     seqs = batch.read_seqs()
     out, lse = to_host(batch.out), batch.lse.cpu().numpy()
     sel_idx, sel_cnt = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
-    keep_map, posd, rank = batch.keep_map.cpu().numpy(), batch.pos.cpu().numpy(), batch.rank_host()
+    keep_map, posd, rank = batch.keep_map.cpu().numpy(), batch.pos.cpu().numpy(), rank_host(batch)
     Kd, Vd = batch.k_host(), batch.v_host()
     n_compacted = 0
     for b, (cfg, st, s, syn) in enumerate(items):
@@ -764,7 +764,7 @@ def test_attend_on_a_maximum_length_list(layout):
     ro, rl, probs = oracle.attend(cfg, k, v, q, np.arange(n, dtype=np.int32), want_probs=True)
     check_out(wl, to_host(batch.out)[0], ro)
     assert np.abs(batch.lse.cpu().numpy()[0] - rl).max() <= 1e-5
-    assert np.allclose(batch.rank_host()[0], probs.sum(axis=0), rtol=1e-5, atol=1e-7)
+    assert np.allclose(rank_host(batch)[0], probs.sum(axis=0), rtol=1e-5, atol=1e-7)
 
 
 # ----------------------------------------------------------------------------- Section 4.2 as written
@@ -884,7 +884,7 @@ def test_streaming_cache_slot_reuse_free_running(mode, layout):
         assert np.array_equal(batch.k_host()[0, :n][order], st.K[:n]), tag
         assert np.array_equal(batch.v_host()[0, :n][order], st.V[:n]), tag
         if mode == B.SCORE_ATTN_MASS:
-            assert np.allclose(batch.rank_host()[0, :n][order], st.score[:n], rtol=1e-5, atol=1e-6), tag
+            assert np.allclose(rank_host(batch)[0, :n][order], st.score[:n], rtol=1e-5, atol=1e-6), tag
         cnt = int(batch.sel_cnt.cpu()[0])
         assert cnt == n and np.array_equal(batch.sel_idx.cpu().numpy()[0, :cnt], np.arange(n)), tag
         check_out(wl, to_host(batch.out)[0], ref["out"], tag)
@@ -947,6 +947,68 @@ def test_append_rounds_fp32_rows_into_a_bf16_cache(G, layout):
 
 
 # ----------------------------------------------------------------------------- per-head attended sets
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_per_head_selection_through_sel_groups(layout):
+    """sel_groups = n_heads as an ABI value: the caller keeps its [n_seq][heads] view of q / out and of either cache
+    nesting and passes one record per (sequence, head).  Free-running against one single-head oracle per
+    (sequence, head), row-end evictions included; the cache rows are compared at the end."""
+    n_seq, h, D = 2, 4, 64
+    geom = dict(n_seq=1, head_dim=D, grid_h=5, grid_w=6, prefix_len=4, win_rows_back=1, win_col_radius=1,
+                budget=5, budget_num=0, budget_den=0)
+    wl = WL.get_workload("xl", n_heads=h, **geom)
+    wl1 = WL.get_workload("xl", n_heads=1, **geom)
+    cfg = oracle_cfg(wl1, budget=5)
+    P, cap = 4, cfg.cap
+    toks = [WL.gen_tokens(wl, 0, b) for b in range(n_seq)]
+    # records, pos, score, lists: those of n_seq * h one-head sequences
+    batch = LayerBatch(params_for(wl1, n_seq * h, cap), DEV)
+    states = {}
+    for b in range(n_seq):
+        for hd in range(h):
+            q, k, v = toks[b]
+            states[b, hd] = oracle.CacheState.from_prefix(cfg, k[:P, hd:hd + 1], v[:P, hd:hd + 1])
+            load_state(batch, b * h + hd, states[b, hd], cfg, 0)
+    params = params_for(wl, n_seq, cap, layout=layout)
+    params.sel_groups = h
+    elem = batch.K.element_size()
+    if layout == "slot_major":       # the caller's cache is [n_seq][slot][head][D]: point every record into it
+        K = batch.K.reshape(n_seq, h, cap, D).transpose(1, 2).contiguous()
+        V = batch.V.reshape(n_seq, h, cap, D).transpose(1, 2).contiguous()
+        for b in range(n_seq):
+            for hd in range(h):
+                batch.seqs_host[b * h + hd]["k"] = K.data_ptr() + ((b * cap * h) + hd) * D * elem
+                batch.seqs_host[b * h + hd]["v"] = V.data_ptr() + ((b * cap * h) + hd) * D * elem
+    else:                            # [n_seq][head][slot][D] is the memory LayerBatch allocated
+        K, V = batch.K.reshape(n_seq, h, cap, D), batch.V.reshape(n_seq, h, cap, D)
+    batch.upload_seqs()
+    assert B.adsa_workspace_bytes(params) == batch.workspace.numel()
+    out = torch.zeros((n_seq, h, D), dtype=batch.tdtype, device=DEV)
+    for s in range(0, wl.n_image_tokens):
+        p = P + s - 1
+        qd, kd, vd = (to_device(np.stack([toks[b][i][p] for b in range(n_seq)]), params.dtype, DEV) for i in range(3))
+        B.adsa_step(params, batch.seqs, qd, kd, vd, out, batch.lse, batch.sel_idx, batch.sel_cnt, batch.keep_map,
+                    batch.workspace, 0, None)
+        torch.cuda.synchronize()
+        o, sel_idx, sel_cnt = to_host(out), batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy()
+        seqs = batch.read_seqs()
+        for b in range(n_seq):
+            for hd in range(h):
+                i = b * h + hd
+                q, k, v = toks[b]
+                st = states[b, hd]
+                before = st.score.copy()
+                ref = oracle.step(cfg, st, s, q[p, hd:hd + 1], k[p, hd:hd + 1], v[p, hd:hd + 1])
+                sel = sel_idx[i, :sel_cnt[i]]
+                assert seqs["n_res"][i] == st.n_res and seqs["step"][i] == s + 1
+                assert np.array_equal(sel, ref["sel_idx"]) or near_tie_ok(sel, ref["sel_idx"], before)
+                check_out(wl1, o[b, hd:hd + 1], ref["out"], f"{layout} s={s} seq={b} head={hd}")
+    Kh, Vh = to_host(K), to_host(V)
+    for (b, hd), st in states.items():
+        rows = (lambda A: A[b, :st.n_res, hd]) if layout == "slot_major" else (lambda A: A[b, hd, :st.n_res])
+        assert np.array_equal(rows(Kh), st.K[:st.n_res, 0].astype(np.float32))
+        assert np.array_equal(rows(Vh), st.V[:st.n_res, 0].astype(np.float32))
+
+
 def test_per_head_selection_is_one_single_head_sequence_per_head():
     """The paper does not say whether heads share one attended set.  Per-head sets need no extra
     kernel: every (sequence, head) is passed as its own adsa_seq with n_heads = 1 (q / out rows
