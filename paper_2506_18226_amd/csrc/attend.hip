@@ -208,11 +208,12 @@ __device__ __forceinline__ void add_mass(gfloat* score, int cap, int row0, const
 
 // DIRECT: the list of a (sequence, head group) is not split (grid.x == 1): the workgroup finishes its heads alone.
 // The arguments the first round trip needs come first, as plain scalars: the build asks for leading kernel
-// arguments to be preloaded into scalar registers at wave launch, so those loads can leave at once.
+// arguments to be preloaded into scalar registers at wave launch, so those loads can leave at once, without
+// waiting for a scalar load of the argument block (which would also wait for the sequence record's).
 template <int EB, int D, int HT, int U, int NW, bool VF, bool DIRECT>
 __global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const int32_t* sel_idx_arg, const int32_t* sel_cnt_arg,
                                                       const char* q_arg, const char* k_new_arg, const char* v_new_arg,
-                                                      int n_heads_arg, int sel_cap_arg, AttendArgs A) {
+                                                      int heads_and_flags, int sel_cap_arg, AttendArgs A) {
   constexpr int kAttThreads = NW * kWave;           // the waves of the workgroup share one token chunk
   constexpr int EPL = Elems<EB>::N;                 // elements per lane
   constexpr int LPR = D / EPL;                      // lanes per row
@@ -234,7 +235,8 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const
   const int sub = lane / LPR, dl = lane - sub * LPR;
   const int hs = sub % HT, ts = sub / HT;           // head and token of this lane's row within a wave-load
   const int head = hg * HT + hs;
-  const int n_heads = n_heads_arg, sel_cap = sel_cap_arg;
+  // (only 14 dwords of arguments are preloaded: the two flags the first trip needs ride on the head count)
+  const int n_heads = heads_and_flags & 0xFFFF, sel_cap = sel_cap_arg;
   const bool head_ok = head < n_heads;
   const int head_c = head_ok ? head : n_heads - 1;
   const int heads_here = min(HT, n_heads - hg * HT);
@@ -258,23 +260,11 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const
   gchar* const out_g = (gchar*)A.out;
   gfloat* const lse_g = (gfloat*)A.lse;
   const uint4 qr = load16(q_g + row_off);
-  // the query token's own K/V row (Section 4.2 append), as this launch attends and stores it: every lane keeps
-  // its 16-byte piece in registers; fp32 rows of a bf16 cache are rounded once, here
-  uint4 nk = make_uint4(0u, 0u, 0u, 0u), nv = nk;
-  if (A.append) {
-    if (EB == 2 && A.new_f32) {
-      const size_t off32 = ((size_t)b * n_heads + head_c) * D * 4 + dl * 32;
-      nk = pack8_bf16(k_new_g + off32);
-      nv = pack8_bf16(v_new_g + off32);
-    } else {
-      nk = load16(k_new_g + row_off);
-      nv = load16(v_new_g + row_off);
-    }
-  }
   // The wave takes the TT-token units wave, wave + NW, ... of the chunk, in that order; unit number k of the
   // wave holds, for this lane, token (wave + k * NW) * TT + ts.  slot_a[u]: slot of unit u; slot_nx[u]: of the unit
   // that takes ring position u next.  pf_slot: the whole list (its first PF * threads entries), one entry per
   // thread and round: staged in LDS below so that the loop finds its slots there instead of in global memory.
+  // (These loads need nothing but preloaded arguments: they leave before anything waits for a scalar load.)
   int slot_a[U], slot_nx[U];
   int pf_slot[PF];
   if constexpr (DIRECT) {
@@ -283,8 +273,25 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const
 #pragma unroll
     for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * kAttThreads, sel_cap - 1)];
   }
+  // the query token's own K/V row (Section 4.2 append), as this launch attends and stores it: every lane keeps
+  // its 16-byte piece in registers; fp32 rows of a bf16 cache are rounded once, here
+  const bool append = (heads_and_flags & 0x10000) != 0, new_f32 = (heads_and_flags & 0x20000) != 0;
+  uint4 nk = make_uint4(0u, 0u, 0u, 0u), nv = nk;
+  if (append) {
+    if (EB == 2 && new_f32) {
+      const size_t off32 = ((size_t)b * n_heads + head_c) * D * 4 + dl * 32;
+      nk = pack8_bf16(k_new_g + off32);
+      nv = pack8_bf16(v_new_g + off32);
+    } else {
+      nk = load16(k_new_g + row_off);
+      nv = load16(v_new_g + row_off);
+    }
+  }
   pin_uniform(cnt_raw); pin_uniform(k_base); pin_uniform(v_base); pin_uniform(score); pin_uniform(pending);
   if constexpr (VF) pin_uniform(u_state);
+  // (the remaining arguments the loop needs: fetched in the same batch of scalar loads, not after it)
+  pin_uniform(A.cap); pin_uniform(A.chunk_max); pin_uniform(A.slot_stride_b); pin_uniform(A.head_stride_b);
+  pin_uniform(A.scale_log2); pin_uniform(A.accumulate);
 
   const int cnt = min(cnt_raw, sel_cap);
   if (cnt <= 0) {                                   // inactive or rejected sequence: zero-filled row
@@ -306,41 +313,16 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const
   if (t_begin >= t_end) return;                     // fewer tokens than chunks
   const int len = t_end - t_begin;
   const float inv_len = 1.0f / (float)len;
-  // ---- the chunk's slot list goes to LDS (clamped to the cache: nothing below ever leaves it)
-  int* const s_idx = reinterpret_cast<int*>(s_logit + (VF ? 2 : HT) * A.chunk_max);
-  if constexpr (DIRECT) {
-#pragma unroll
-    for (int k = 0; k < PF; ++k) {
-      const int j = tid + k * kAttThreads;
-      if (j < len) s_idx[j] = min(max(pf_slot[k], 0), A.cap - 1);
-    }
-    for (int j = tid + PF * kAttThreads; j < len; j += kAttThreads) s_idx[j] = min(max(idx[j], 0), A.cap - 1);
-  } else {
-    for (int j = tid; j < len; j += kAttThreads) s_idx[j] = min(max(idx[t_begin + j], 0), A.cap - 1);
+  int* const s_idx = reinterpret_cast<int*>(s_logit + (VF ? 2 : HT) * A.chunk_max);   // the chunk's slot list (filled below)
+  if constexpr (!DIRECT) {
 #pragma unroll
     for (int u = 0; u < U; ++u) slot_a[u] = idx[t_begin + min((wave + u * NW) * TT + ts, len - 1)];
   }
-  __syncthreads();
   // the slot adsa_select reserved for the query token (Section 4.2 append), if this launch fills it
-  const int new_slot = (A.append && pending < A.cap) ? pending : -1;
+  const int new_slot = (append && pending < A.cap) ? pending : -1;
 
-  // pair i of the final score update is (head i / len, token i % len); start the first PF reads now
   const int n_pairs = heads_here * len;
   float pf_old[PF];
-  if (DIRECT && A.accumulate) {
-#pragma unroll
-    for (int k = 0; k < PF; ++k) {
-      const int i = tid + k * kAttThreads;
-      pf_old[k] = 0.0f;
-      if (i < n_pairs) {
-        int sb = 0, j = i;
-        if constexpr (HT > 1) { sb = small_div(i, len, inv_len); j = i - sb * len; }   // several heads per workgroup
-        pf_slot[k] = s_idx[j];
-        pf_old[k] = score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]];
-      }
-    }
-  }
-
   float qf[EPL];
   Elems<EB>::unpack(qr, qf);
 #pragma unroll
@@ -424,7 +406,7 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const
     };
     // unit k of the wave lives at ring position k % U: units 0 .. U-1 are requested here, trip t folds units
     // tU .. tU+U-1 and requests the units one ring revolution later, the last trip only folds.  (Units past
-    // the wave's last one re-read the chunk's last row, which is cached by then.)
+    // the wave's last one re-read the q row, which is cached by then.)
     auto refill = [&](int u, int k, int slot_raw) { // ring position u <- unit k; fetch the slot of unit k + U
       const int token = (wave + k * NW) * TT + ts;
       issue(u, slot_raw, token);
@@ -433,8 +415,44 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const
       __builtin_amdgcn_sched_barrier(0);            // ... and before the next unit's arithmetic, which waits for ITS rows
     };
     const int n_trips = (n_mine + U - 1) / U;
+    // The first revolution's rows are requested at once, from the slots the first round trip brought in registers ...
 #pragma unroll
-    for (int u = 0; u < U; ++u) refill(u, u, slot_a[u]);
+    for (int u = 0; u < U; ++u) {
+      issue(u, slot_a[u], (wave + u * NW) * TT + ts);
+      asm volatile("" : : : "memory");
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // ... and while they are on their way the chunk's slot list goes to LDS (clamped to the cache: nothing below
+    // ever leaves it), where the later revolutions and the score update find it
+    if constexpr (DIRECT) {
+#pragma unroll
+      for (int k = 0; k < PF; ++k) {
+        const int j = tid + k * kAttThreads;
+        if (j < len) s_idx[j] = min(max(pf_slot[k], 0), A.cap - 1);
+      }
+      for (int j = tid + PF * kAttThreads; j < len; j += kAttThreads) s_idx[j] = min(max(idx[j], 0), A.cap - 1);
+    } else {
+      for (int j = tid; j < len; j += kAttThreads) s_idx[j] = min(max(idx[t_begin + j], 0), A.cap - 1);
+    }
+    __syncthreads();
+    // pair i of the final score update is (head i / len, token i % len); start the first PF reads now
+    if (DIRECT && A.accumulate) {
+#pragma unroll
+      for (int k = 0; k < PF; ++k) {
+        const int i = tid + k * kAttThreads;
+        pf_old[k] = 0.0f;
+        if (i < n_pairs) {
+          int sb = 0, j = i;
+          if constexpr (HT > 1) { sb = small_div(i, len, inv_len); j = i - sb * len; }   // several heads per workgroup
+          pf_slot[k] = s_idx[j];
+          pf_old[k] = score[(size_t)(hg * HT + sb) * A.cap + pf_slot[k]];
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) slot_nx[u] = s_idx[min((wave + (u + U) * NW) * TT + ts, len - 1)];
+    asm volatile("" : : : "memory");
+    __builtin_amdgcn_sched_barrier(0);
     int k_next = U;
     for (int trip = 1; trip < n_trips; ++trip) {
 #pragma unroll
@@ -689,10 +707,12 @@ hipError_t launch_attend_w(const AttendArgs& A, const AttendPlan& plan, int n_se
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)
     hipExtLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF, DIRECT>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0,
-                          A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new, A.n_heads, A.sel_cap, A);
+                          A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new,
+                          A.n_heads | (A.append ? 0x10000 : 0) | (A.new_f32 ? 0x20000 : 0), A.sel_cap, A);
   else
     hipLaunchKernelGGL((k_attend<EB, D, HT, U, NW, VF, DIRECT>), grid, dim3(NW * kWave), lds, st,
-                       A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new, A.n_heads, A.sel_cap, A);
+                       A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new,
+                          A.n_heads | (A.append ? 0x10000 : 0) | (A.new_f32 ? 0x20000 : 0), A.sel_cap, A);
   return hipGetLastError();
 }
 
