@@ -19,13 +19,19 @@
 //            contraction runs over tokens).  P is split into two bf16 halves (hi + lo) so that the
 //            product carries ~16 mantissa bits of the probabilities.  When a query's running maximum
 //            m[g] grows, the accumulators are rescaled (factors fetched across lanes).
-//    K and V of the next tiles are in flight while the current ones are multiplied.
-//    At the end the waves' (m, l, partial out) are merged through LDS in wave order, the workgroup writes out / lse for its G query heads and adds the
-//    probabilities of all G queries, summed in ascending head order, to its OWN cache head's row of
-//    score[]: no workgroup talks to another.
+//    Each wave keeps a small ring of tiles in flight: it waits for the OLDEST tile's K rows only (in-order wait
+//    counts; a tile is always requested as its K loads followed by its V loads, with no branch in between),
+//    multiplies it and refills its registers with the tile one ring revolution later.  Loads take a uniform base
+//    and a 32-bit lane offset; the query token's own slot is read like any other and replaced from registers.
+//    The first round trip (count, sequence record, q, slot list, the query token's row) depends on preloaded
+//    kernel arguments only, and leaves before anything waits for a scalar load.
+//    At the end the waves' (m, l, partial out) are merged through LDS in wave order, the workgroup writes
+//    out / lse for its G query heads and adds the probabilities of all G queries, summed in ascending head
+//    order, to its OWN cache head's row of score[]: no workgroup talks to another.
 #include <hip/hip_ext.h>
 
 #include "adsa_internal.h"
+#include "adsa_device.h"
 
 namespace adsa {
 namespace {
@@ -35,10 +41,6 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ s16x4 as_bf16x4(uint32_t lo, uint32_t hi) {
   const u32x2 v = {lo, hi};
@@ -57,32 +59,27 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
-  uint32_t u = __float_as_uint(x);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// c ? a : b by components (a ternary on the structs themselves would select between their ADDRESSES and
+// keep both in memory)
+__device__ __forceinline__ uint4 pick16(bool c, const uint4& a, const uint4& b) {
+  return make_uint4(c ? a.x : b.x, c ? a.y : b.y, c ? a.z : b.z, c ? a.w : b.w);
 }
 
-// n consecutive fp32 values (n = 4 or 8) -> bf16, round to nearest even, packed two per dword
-__device__ __forceinline__ void pack_bf16(const float* f, int n, uint32_t* w) {
-  for (int i = 0; i < n / 2; ++i) w[i] = f32_to_bf16_rne(f[2 * i]) | (f32_to_bf16_rne(f[2 * i + 1]) << 16);
-}
-
-template <int BYTES> struct VLoad;
-template <> struct VLoad<8> {
-  static constexpr int W = 2;
-  static __device__ __forceinline__ void load(const char* p, uint32_t* w) {
-    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+// 2 or 4 dwords of a V row: streaming (nontemporal) or plain
+template <int W, bool stream>
+__device__ __forceinline__ void vload(const gchar* p, uint32_t* w) {
+  if constexpr (W == 2) {
+    u32x2 v;
+    if constexpr (stream) v = __builtin_nontemporal_load(reinterpret_cast<const ADSA_GLOBAL u32x2*>(p));
+    else v = *reinterpret_cast<const ADSA_GLOBAL u32x2*>(p);
     w[0] = v.x; w[1] = v.y;
-  }
-};
-template <> struct VLoad<16> {
-  static constexpr int W = 4;
-  static __device__ __forceinline__ void load(const char* p, uint32_t* w) {
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  } else {
+    uint4 v;
+    if constexpr (stream) v = load_stream16(p);
+    else v = load16(p);
     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
   }
-};
+}
 
 struct GqaArgs {
   adsa_seq* seqs;
@@ -100,8 +97,14 @@ struct GqaArgs {
   float scale_log2;
 };
 
+// The arguments the first round trip needs come first, as plain scalars (the build asks for leading kernel
+// arguments to be preloaded into scalar registers at wave launch): the vector loads of that trip then leave
+// without waiting for a scalar load of the argument block.  Only 14 dwords are preloaded, so the group size and
+// the two append flags ride on the head count: heads | G << 16 | append << 24 | new_f32 << 25.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
+__global__ __launch_bounds__(NW * kWave) void k_attend_gqa(adsa_seq* seqs_arg, const int32_t* sel_idx_arg, const int32_t* sel_cnt_arg,
+                                                          const char* q_arg, const char* k_new_arg, const char* v_new_arg,
+                                                          int heads_g_flags, int sel_cap_arg, GqaArgs A) {
   constexpr int T = NW * kWave;
   constexpr int ROWB = D * 2 + 16;          // bytes of a staged K row (padded against bank conflicts)
   constexpr int LPR = D / 8;                // lanes per K row with 16-byte loads
@@ -109,8 +112,10 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   constexpr int LT = 16 / RPL;              // wave-loads per 16-token tile
   constexpr int NC = D / 16;                // 16-wide chunks of the q.k contraction
   constexpr int EV = D / 16;                // V columns a lane holds per token
-  constexpr int UT = D == 64 ? 2 : 1;       // 16-token tiles per pipeline stage (two stages in flight)
-  constexpr int VW = VLoad<EV * 2>::W;      // dwords of V a lane loads per token
+  constexpr int VW = EV / 2;                // dwords of V a lane loads per token
+  constexpr int R = D == 64 ? 4 : 2;        // tiles in flight per wave (a ring: the oldest is multiplied, then refilled;
+                                            // 1, 2 and 3 were measured within 1 % of each other on 8 x 128 x 8-wave lists)
+  constexpr int PF = 2048 / T;              // slot-list entries a thread fetches in the first round trip
   extern __shared__ __align__(16) char smem[];
   __shared__ float s_wm[NW][16], s_wl[NW][16], s_lse2[16];
 
@@ -118,38 +123,72 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int r = lane & 15, kg = lane >> 4;                 // matrix-operand role of this lane
-  const int G = A.G, lgs = A.lg_stride, HQ = A.n_heads * G;
+  const int n_heads = heads_g_flags & 0xFFFF, G = (heads_g_flags >> 16) & 0xFF, sel_cap = sel_cap_arg;
+  const bool append = (heads_g_flags & (1 << 24)) != 0, cvt = (heads_g_flags & (1 << 25)) != 0;
+  const int HQ = n_heads * G;
+
+  // ---- first round trip: the count and the sequence record (scalar loads), q, the whole slot list (one entry per
+  // thread and round) and the query token's own K/V row as this launch attends and stores it -- everything that
+  // depends on the kernel arguments only.  The record and the count are pinned so that they cannot drift behind
+  // the count test below, into a second, dependent trip.
+  ADSA_GLOBAL adsa_seq* const sqp = (ADSA_GLOBAL adsa_seq*)(seqs_arg + b);
+  const int cnt_raw = ((const gint*)sel_cnt_arg)[b];
+  gchar* const k_rec = (gchar*)sqp->k;
+  gchar* const v_rec = (gchar*)sqp->v;
+  gfloat* const score_rec = (gfloat*)sqp->score;
+  const int pending = sqp->pending_slot;
+  const gint* const idx = (const gint*)sel_idx_arg + (size_t)b * sel_cap;
+  const gchar* const q_g = (const gchar*)q_arg;
+  // q as the B operand of the first product: lane (g = r, kg) holds columns [D/4*kg, D/4*(kg+1)) of query g
+  const gchar* const q_row0 = q_g + ((size_t)b * HQ + (size_t)hk * G) * D * 2;        // query 0 of this cache head
+  uint4 qx[NC / 2];
+#pragma unroll
+  for (int c2 = 0; c2 < NC / 2; ++c2) qx[c2] = load16(q_row0 + ((size_t)min(r, G - 1) * D + (D / 4) * kg) * 2 + c2 * 16);
+  int pf_slot[PF];
+#pragma unroll
+  for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * T, sel_cap - 1)];
+  // the query token's row (Section 4.2 append); fp32 rows are rounded once, here: every lane keeps the pieces of
+  // the rounded row it would load from the cache (K: 16 bytes at ld_piece, V: its EV columns)
+  const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
+  const size_t new_row = ((size_t)b * n_heads + hk) * D;
+  uint4 nk = make_uint4(0u, 0u, 0u, 0u);
+  uint32_t nv[VW];
+#pragma unroll
+  for (int i = 0; i < VW; ++i) nv[i] = 0u;
+  if (append) {
+    const gchar* const kn = (const gchar*)k_new_arg;
+    const gchar* const vn = (const gchar*)v_new_arg;
+    if (cvt) {
+      nk = pack8_bf16(kn + (new_row + ld_piece * 8) * 4);
+      if constexpr (EV == 8) {
+        const uint4 x = pack8_bf16(vn + (new_row + r * 8) * 4);
+        nv[0] = x.x; nv[1] = x.y; nv[2] = x.z; nv[3] = x.w;
+      } else {
+        const uint4 x = load16(vn + (new_row + r * 4) * 4);
+        nv[0] = f32_to_bf16_rne(__uint_as_float(x.x)) | (f32_to_bf16_rne(__uint_as_float(x.y)) << 16);
+        nv[1] = f32_to_bf16_rne(__uint_as_float(x.z)) | (f32_to_bf16_rne(__uint_as_float(x.w)) << 16);
+      }
+    } else {
+      nk = load16(kn + new_row * 2 + ld_piece * 16);
+      vload<VW, false>(vn + new_row * 2 + r * (EV * 2), nv);
+    }
+  }
+  pin_uniform(cnt_raw); pin_uniform(k_rec); pin_uniform(v_rec); pin_uniform(score_rec); pin_uniform(pending);
+  // (the remaining arguments: fetched in the same batch of scalar loads, not after it)
+  pin_uniform(A.cap); pin_uniform(A.lg_stride); pin_uniform(A.stage_b); pin_uniform(A.slot_stride_b);
+  pin_uniform(A.head_stride_b); pin_uniform(A.scale_log2); pin_uniform(A.accumulate);
+
+  const int lgs = A.lg_stride;
   float* const s_logit = reinterpret_cast<float*>(smem);                 // [G][lgs]
   int* const s_slot = reinterpret_cast<int*>(s_logit + (size_t)G * lgs); // [lgs]
   char* const s_stage = reinterpret_cast<char*>(s_slot + lgs);           // [NW][stage_b]: K tile [16][ROWB], later partial out [G][D]
+  gchar* const k_base = k_rec + (long long)hk * A.head_stride_b;
+  gchar* const v_base = v_rec + (long long)hk * A.head_stride_b;
+  gfloat* const score = score_rec + (size_t)hk * A.cap;
+  ADSA_GLOBAL uint16_t* const out = reinterpret_cast<ADSA_GLOBAL uint16_t*>((gchar*)A.out) + ((size_t)b * HQ + (size_t)hk * G) * D;
+  gfloat* const lse = (gfloat*)A.lse + (size_t)b * HQ + (size_t)hk * G;
 
-  // One round trip brings everything the first K loads depend on: the sequence record, the count, q,
-  // and the whole slot list (its address and extent do not depend on the count).
-  adsa_seq& sq = A.seqs[b];
-  const int cnt_raw = A.sel_cnt[b];
-  char* const k_base = reinterpret_cast<char*>(sq.k) + (long long)hk * A.head_stride_b;
-  char* const v_base = reinterpret_cast<char*>(sq.v) + (long long)hk * A.head_stride_b;
-  float* const score = sq.score + (size_t)hk * A.cap;
-  const int pending = sq.pending_slot;
-  const int32_t* idx = A.sel_idx + (size_t)b * A.sel_cap;
-  uint16_t* const out = reinterpret_cast<uint16_t*>(A.out) + ((size_t)b * HQ + (size_t)hk * G) * D;
-  float* const lse = A.lse + (size_t)b * HQ + (size_t)hk * G;
-  // slots of the list, clamped into the cache (entries past the count are never used: readers clamp
-  // their list position to the last token)
-  for (int t = tid; t < A.sel_cap; t += T) s_slot[t] = min(max(idx[t], 0), A.cap - 1);
-  // q as the B operand of pass 1: lane (g = r, kg) holds columns [D/4*kg, D/4*(kg+1)) of query g
-  s16x4 qb[NC];
-  {
-    const char* qp = A.q + (((size_t)b * HQ + (size_t)hk * G + min(r, G - 1)) * D + (D / 4) * kg) * 2;
-#pragma unroll
-    for (int c2 = 0; c2 < NC / 2; ++c2) {
-      uint4 x = *reinterpret_cast<const uint4*>(qp + c2 * 16);
-      if (r >= G) x = make_uint4(0u, 0u, 0u, 0u);
-      qb[2 * c2] = as_bf16x4(x.x, x.y);
-      qb[2 * c2 + 1] = as_bf16x4(x.z, x.w);
-    }
-  }
-  const int cnt = min(cnt_raw, A.sel_cap);
+  const int cnt = min(cnt_raw, sel_cap);
   if (cnt <= 0) {                                    // inactive or rejected sequence: zero-filled rows
     for (int o = tid; o < G * D; o += T) {
       out[o] = 0;
@@ -159,28 +198,21 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   }
   const int len = cnt;
   const int n_tiles = (len + 15) / 16;
-  const int new_slot = (A.append && pending >= 0 && pending < A.cap) ? pending : -1;
-  // the new token's row as this launch attends it; fp32 rows are rounded once, here: every lane keeps
-  // the pieces of the rounded row it would load (K: 16 bytes at ld_piece, V: its EV columns)
-  const bool cvt = A.new_f32 && new_slot >= 0;
-  const size_t new_row = ((size_t)b * A.n_heads + hk) * D;
-  const char* const kn = cvt ? k_base : A.k_new + new_row * 2;     // (cvt: any valid row; the value is replaced)
-  const char* const vn = cvt ? v_base : A.v_new + new_row * 2;
-  const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
-  uint32_t nk[4] = {0u, 0u, 0u, 0u}, nv[VW];
+  // slots of the list, clamped into the cache, go to LDS (readers clamp their list position to the last token)
 #pragma unroll
-  for (int i = 0; i < VW; ++i) nv[i] = 0u;
-  if (cvt) {
-    const float* k32 = reinterpret_cast<const float*>(A.k_new) + new_row;
-    const float* v32 = reinterpret_cast<const float*>(A.v_new) + new_row;
-    float t[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) t[i] = k32[ld_piece * 8 + i];
-    pack_bf16(t, 8, nk);
-#pragma unroll
-    for (int i = 0; i < EV; ++i) t[i] = v32[r * EV + i];
-    pack_bf16(t, EV, nv);
+  for (int k = 0; k < PF; ++k) {
+    const int j = tid + k * T;
+    if (j < len) s_slot[j] = min(max(pf_slot[k], 0), A.cap - 1);
   }
+  for (int j = tid + PF * T; j < len; j += T) s_slot[j] = min(max(idx[j], 0), A.cap - 1);
+  s16x4 qb[NC];
+#pragma unroll
+  for (int c2 = 0; c2 < NC / 2; ++c2) {
+    const uint4 x = r < G ? qx[c2] : make_uint4(0u, 0u, 0u, 0u);
+    qb[2 * c2] = as_bf16x4(x.x, x.y);
+    qb[2 * c2 + 1] = as_bf16x4(x.z, x.w);
+  }
+  const int new_slot = (append && pending >= 0 && pending < A.cap) ? pending : -1;
   __syncthreads();
 
   // (the lambdas below work on copies: they capture by reference, and a reference to the kernel's argument
@@ -188,34 +220,40 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
   const long long slot_stride_b = A.slot_stride_b;
   const float scale_log2 = A.scale_log2;
   const bool keep_logits = A.accumulate != 0;
-  const int stage_b = A.stage_b;                     // bytes of LDS each wave owns
-  char* const stage = s_stage + wave * stage_b;
-  struct Stage { uint4 k[UT][LT]; uint32_t v[UT][4][VW]; };
+  char* const stage = s_stage + wave * A.stage_b;    // LDS this wave owns
 
-  auto load = [&](Stage& st, int sid) {
+  // Ring of R tiles per wave.  Ring position u holds unit k of the wave, i.e. tile wave + k * NW, for k = u, u + R, ...
+  // A tile is requested as LT K loads followed by 4 V loads per lane, always in that order and with no branch in
+  // between, so that "the oldest K rows have arrived" is one in-order wait count.
+  uint4 kr[R][LT];
+  uint32_t vr[R][4][VW];
+  uint32_t fresh[R];                                 // bit l: K load l, bit 8 + i: V load i stands for the query token's own row
+  // byte offsets inside one head's rows fit 32 bits (cap <= 8192 slots, rows at most 64 KB apart): the loads then
+  // take a uniform base and a 32-bit lane offset, two instructions of address arithmetic instead of a 64-bit product
+  const uint32_t stride32 = (uint32_t)slot_stride_b;
+  const uint32_t k_lane_off = (uint32_t)ld_piece * 16u, v_lane_off = (uint32_t)r * (EV * 2);
+  auto issue = [&](int u, int tile) {
+    int slot_k[LT], slot_v[4];                       // all slots of the tile first: one LDS round trip, then the loads
 #pragma unroll
-    for (int ut = 0; ut < UT; ++ut) {
-      const int tile = sid * UT + ut;
-      if (tile < n_tiles) {                          // wave-uniform
+    for (int l = 0; l < LT; ++l) slot_k[l] = s_slot[min(tile * 16 + l * RPL + ld_row, len - 1)];   // (tiles past the end re-read the last row)
 #pragma unroll
-        for (int u = 0; u < LT; ++u) {
-          const int slot = s_slot[min(tile * 16 + u * RPL + ld_row, len - 1)];
-          const char* p = (slot == new_slot) ? kn : k_base + (long long)slot * slot_stride_b;
-          const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + ld_piece * 16));
-          st.k[ut][u] = (cvt && slot == new_slot) ? make_uint4(nk[0], nk[1], nk[2], nk[3]) : make_uint4(v.x, v.y, v.z, v.w);
-        }
+    for (int i = 0; i < 4; ++i) slot_v[i] = s_slot[min(tile * 16 + 4 * kg + i, len - 1)];
+    // The query token's own slot is read like any other (valid memory of the cache; the row is stored at the end of
+    // this launch) and what arrives is replaced by the row held in registers when the tile is multiplied.
+    uint32_t f = 0u;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int slot = s_slot[min(tile * 16 + 4 * kg + i, len - 1)];
-          const char* p = (slot == new_slot) ? vn : v_base + (long long)slot * slot_stride_b;
-          VLoad<EV * 2>::load(p + r * (EV * 2), st.v[ut][i]);
-          if (cvt && slot == new_slot) {
-#pragma unroll
-            for (int w2 = 0; w2 < VW; ++w2) st.v[ut][i][w2] = nv[w2];
-          }
-        }
-      }
+    for (int l = 0; l < LT; ++l) {
+      kr[u][l] = load_stream16(k_base + ((uint32_t)slot_k[l] * stride32 + k_lane_off));
+      f |= slot_k[l] == new_slot ? (1u << l) : 0u;
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      vload<VW, true>(v_base + ((uint32_t)slot_v[i] * stride32 + v_lane_off), vr[u][i]);
+      f |= slot_v[i] == new_slot ? (1u << (8 + i)) : 0u;
+    }
+    fresh[u] = f;
+    asm volatile("" : : : "memory");                 // requests leave in ring order (the wait counts rely on it)
+    __builtin_amdgcn_sched_barrier(0);               // ... and before the next tile's arithmetic, which waits for ITS rows
   };
 
   float m_run = -INFINITY, l_lane = 0.0f;            // online softmax of query g = r (l: this lane's tokens only)
@@ -223,97 +261,108 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
 #pragma unroll
   for (int j = 0; j < EV; ++j) acc[j] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-  auto mul = [&](const Stage& st, int sid) {
+  auto fold = [&](int u, int tile) {
+    if (__any(fresh[u] != 0u)) {                     // (rare) the tile holds the query token: its row comes from registers
 #pragma unroll
-    for (int ut = 0; ut < UT; ++ut) {
-      const int tile = sid * UT + ut;
-      if (tile < n_tiles) {
-        wave_lds_sync();                             // the previous tile's operand reads are issued
+      for (int l = 0; l < LT; ++l) kr[u][l] = pick16(((fresh[u] >> l) & 1u) != 0, nk, kr[u][l]);
 #pragma unroll
-        for (int u = 0; u < LT; ++u)
-          *reinterpret_cast<uint4*>(stage + (u * RPL + ld_row) * ROWB + ld_piece * 16) = st.k[ut][u];
-        wave_lds_sync();
-        const char* rowp = stage + r * ROWB + kg * (D / 2);   // token r of the tile, this lane's columns
-        f32x4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
+      for (int i = 0; i < 4; ++i) {
 #pragma unroll
-        for (int c2 = 0; c2 < NC / 2; ++c2) {
-          const uint4 x = *reinterpret_cast<const uint4*>(rowp + c2 * 16);
-          s4 = mfma_bf16(as_bf16x4(x.x, x.y), qb[2 * c2], s4);
-          s4 = mfma_bf16(as_bf16x4(x.z, x.w), qb[2 * c2 + 1], s4);
-        }
-        // s4[i] = q[g = r] . K[token tile*16 + 4*kg + i]
-        const int t0 = tile * 16 + 4 * kg;
-        float z[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) z[i] = (t0 + i < len) ? s4[i] * scale_log2 : -INFINITY;
-        if (keep_logits && r < G)
-          *reinterpret_cast<float4*>(s_logit + (size_t)r * lgs + t0) = make_float4(z[0], z[1], z[2], z[3]);
-        float tm = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
-        tm = fmaxf(tm, __shfl_xor(tm, 16, kWave));
-        tm = fmaxf(tm, __shfl_xor(tm, 32, kWave));   // maximum of query r over the tile (its first token is valid)
-        const float m_new = fmaxf(m_run, tm);
-        if (__any(m_new > m_run)) {                  // some query's maximum grew: rescale what was summed so far
-          const float c = fast_exp2(m_run - m_new);  // 0 for the first tile
-          l_lane *= c;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float ci = __shfl(c, 4 * kg + i, kWave);   // factor of query 4*kg + i
-#pragma unroll
-            for (int j = 0; j < EV; ++j) acc[j][i] *= ci;
-          }
-          m_run = m_new;
-        }
-        uint32_t hi[4], lo[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float p = fast_exp2(z[i] - m_run);
-          if (r >= G) p = 0.0f;
-          l_lane += p;
-          hi[i] = __float_as_uint(p) & 0xFFFF0000u;
-          lo[i] = __float_as_uint(p - __uint_as_float(hi[i])) >> 16;     // exact difference, truncated
-        }
-        const s16x4 a_hi = as_bf16x4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
-        const s16x4 a_lo = as_bf16x4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
-#pragma unroll
-        for (int w2 = 0; w2 < VW; ++w2) {
-          const uint32_t r0 = st.v[ut][0][w2], r1 = st.v[ut][1][w2], r2 = st.v[ut][2][w2], r3 = st.v[ut][3][w2];
-          // columns 2*w2 (low halves) and 2*w2+1 (high halves) of the 4 tokens
-          const s16x4 b_even = as_bf16x4((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
-          const s16x4 b_odd = as_bf16x4((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
-          acc[2 * w2] = mfma_bf16(a_hi, b_even, acc[2 * w2]);
-          acc[2 * w2] = mfma_bf16(a_lo, b_even, acc[2 * w2]);
-          acc[2 * w2 + 1] = mfma_bf16(a_hi, b_odd, acc[2 * w2 + 1]);
-          acc[2 * w2 + 1] = mfma_bf16(a_lo, b_odd, acc[2 * w2 + 1]);
-        }
+        for (int w2 = 0; w2 < VW; ++w2) vr[u][i][w2] = (fresh[u] >> (8 + i)) & 1u ? nv[w2] : vr[u][i][w2];
       }
     }
+    wave_lds_sync();                                 // the previous tile's operand reads are issued
+#pragma unroll
+    for (int l = 0; l < LT; ++l)
+      *reinterpret_cast<uint4*>(stage + (l * RPL + ld_row) * ROWB + ld_piece * 16) = kr[u][l];
+    wave_lds_sync();
+    const char* rowp = stage + r * ROWB + kg * (D / 2);     // token r of the tile, this lane's columns
+    f32x4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int c2 = 0; c2 < NC / 2; ++c2) {
+      const uint4 x = *reinterpret_cast<const uint4*>(rowp + c2 * 16);
+      s4 = mfma_bf16(as_bf16x4(x.x, x.y), qb[2 * c2], s4);
+      s4 = mfma_bf16(as_bf16x4(x.z, x.w), qb[2 * c2 + 1], s4);
+    }
+    // s4[i] = q[g = r] . K[token tile*16 + 4*kg + i]
+    const int t0 = tile * 16 + 4 * kg;
+    float z[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) z[i] = (t0 + i < len) ? s4[i] * scale_log2 : -INFINITY;
+    if (keep_logits && r < G)
+      *reinterpret_cast<float4*>(s_logit + (size_t)r * lgs + t0) = make_float4(z[0], z[1], z[2], z[3]);
+    float tm = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+    tm = xor_max<32>(xor_max<16>(tm));               // maximum of query r over the tile (its first token is valid)
+    const float m_new = fmaxf(m_run, tm);
+    if (__any(m_new > m_run)) {                      // some query's maximum grew: rescale what was summed so far
+      const float c = fast_exp2(m_run - m_new);      // 0 for the first tile
+      l_lane *= c;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float ci = __shfl(c, 4 * kg + i, kWave);     // factor of query 4*kg + i
+#pragma unroll
+        for (int j = 0; j < EV; ++j) acc[j][i] *= ci;
+      }
+      m_run = m_new;
+    }
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float p = fast_exp2(z[i] - m_run);
+      if (r >= G) p = 0.0f;
+      l_lane += p;
+      hi[i] = __float_as_uint(p) & 0xFFFF0000u;
+      lo[i] = __float_as_uint(p - __uint_as_float(hi[i])) >> 16;     // exact difference, truncated
+    }
+    const s16x4 a_hi = as_bf16x4((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
+    const s16x4 a_lo = as_bf16x4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+#pragma unroll
+    for (int w2 = 0; w2 < VW; ++w2) {
+      const uint32_t r0 = vr[u][0][w2], r1 = vr[u][1][w2], r2 = vr[u][2][w2], r3 = vr[u][3][w2];
+      // columns 2*w2 (low halves) and 2*w2+1 (high halves) of the 4 tokens
+      const s16x4 b_even = as_bf16x4((r0 & 0xFFFFu) | (r1 << 16), (r2 & 0xFFFFu) | (r3 << 16));
+      const s16x4 b_odd = as_bf16x4((r0 >> 16) | (r1 & 0xFFFF0000u), (r2 >> 16) | (r3 & 0xFFFF0000u));
+      acc[2 * w2] = mfma_bf16(a_hi, b_even, acc[2 * w2]);
+      acc[2 * w2] = mfma_bf16(a_lo, b_even, acc[2 * w2]);
+      acc[2 * w2 + 1] = mfma_bf16(a_hi, b_odd, acc[2 * w2 + 1]);
+      acc[2 * w2 + 1] = mfma_bf16(a_lo, b_odd, acc[2 * w2 + 1]);
+    }
+    // the tile is multiplied completely before the loads that reuse its ring position are issued
+    asm volatile("" : "+v"(m_run), "+v"(l_lane) : : "memory");
   };
 
   {
-    Stage sa, sb;
-    // wave w takes stages w, w + NW, ...: a fixed assignment, so results are reproducible bit for bit
-    int ia = wave, ib = wave + NW;
-    load(sa, ia);
-    load(sb, ib);
-    while (ia * UT < n_tiles) {
-      mul(sa, ia);
-      ia += 2 * NW;
-      load(sa, ia);
-      if (ib * UT >= n_tiles) break;
-      mul(sb, ib);
-      ib += 2 * NW;
-      load(sb, ib);
+    // wave w takes tiles w, w + NW, ...: a fixed assignment, so results are reproducible bit for bit.  Units
+    // 0 .. R-1 are requested here; trip t multiplies units (t-1)R .. tR-1 (all of them real tiles) and requests
+    // the units one ring revolution later; the last trip only multiplies, and skips ring positions without a tile.
+    const int n_mine = n_tiles > wave ? (n_tiles - wave + NW - 1) / NW : 0;
+    const int n_trips = (n_mine + R - 1) / R;
+#pragma unroll
+    for (int u = 0; u < R; ++u) issue(u, wave + u * NW);
+    int k0 = 0;                                      // unit at ring position 0
+    for (int trip = 1; trip < n_trips; ++trip) {
+#pragma unroll
+      for (int u = 0; u < R; ++u) {
+        fold(u, wave + (k0 + u) * NW);
+        issue(u, wave + (k0 + R + u) * NW);
+      }
+      k0 += R;
+    }
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+      const int tile = wave + (k0 + u) * NW;
+      if (tile < n_tiles) fold(u, tile);             // wave-uniform
     }
   }
-  l_lane += __shfl_xor(l_lane, 16, kWave);
-  l_lane += __shfl_xor(l_lane, 32, kWave);
+  l_lane = xor_sum<32>(xor_sum<16>(l_lane));
   if (lane < 16) { s_wm[wave][lane] = m_run; s_wl[wave][lane] = l_lane; }
   // one slab of partial outputs per wave, merged below with the waves' softmax weights
+  wave_lds_sync();                                   // (the slab reuses the wave's K tile)
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int g = 4 * kg + i;
     if (g < G) {
-      float* dst = reinterpret_cast<float*>(s_stage + wave * stage_b) + (size_t)g * D + EV * r;
+      float* dst = reinterpret_cast<float*>(stage) + (size_t)g * D + EV * r;
 #pragma unroll
       for (int j = 0; j < EV; ++j) dst[j] = acc[j][i];
     }
@@ -342,50 +391,48 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(GqaArgs A) {
     const int g = o / D, d = o - g * D;
     float a = 0.0f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) a = fmaf(reinterpret_cast<const float*>(s_stage + w * stage_b)[o], s_wm[w][g], a);
+    for (int w = 0; w < NW; ++w) a = fmaf(reinterpret_cast<const float*>(s_stage + w * A.stage_b)[o], s_wm[w][g], a);
     out[o] = (uint16_t)f32_to_bf16_rne(a * s_wl[0][g]);
     if (d == 0) lse[g] = s_lse2[g] * kLn2;
   }
-  if (new_slot >= 0 && tid < D / 8) {                // Section 4.2 append: this cache head's rows of the new token
-    const long long off = (long long)new_slot * A.slot_stride_b + tid * 16;
-    if (cvt) {
-      float t[8];
-      uint32_t w[4];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) t[i] = reinterpret_cast<const float*>(A.k_new)[new_row + tid * 8 + i];
-      pack_bf16(t, 8, w);
-      *reinterpret_cast<uint4*>(k_base + off) = make_uint4(w[0], w[1], w[2], w[3]);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) t[i] = reinterpret_cast<const float*>(A.v_new)[new_row + tid * 8 + i];
-      pack_bf16(t, 8, w);
-      *reinterpret_cast<uint4*>(v_base + off) = make_uint4(w[0], w[1], w[2], w[3]);
-    } else {
-      *reinterpret_cast<uint4*>(k_base + off) = *reinterpret_cast<const uint4*>(kn + tid * 16);
-      *reinterpret_cast<uint4*>(v_base + off) = *reinterpret_cast<const uint4*>(vn + tid * 16);
+  // Section 4.2 append: this cache head's rows of the new token, from the registers that attended them
+  if (new_slot >= 0 && wave == 0) {
+    const long long off = (long long)new_slot * slot_stride_b;
+    if (ld_row == 0) store16(k_base + off + ld_piece * 16, nk);
+    if (kg == 0) {
+      if constexpr (VW == 4) store16(v_base + off + r * 16, make_uint4(nv[0], nv[1], nv[2], nv[3]));
+      else {
+        u32x2 v; v.x = nv[0]; v.y = nv[1];
+        *reinterpret_cast<ADSA_GLOBAL u32x2*>(v_base + off + r * 8) = v;
+      }
     }
   }
 
   // ---------------- attention mass of this cache head: sum over its G queries, ascending
   // Each (cache head, slot) word is touched by exactly one thread of one workgroup per launch, so a
-  // no-return hardware add gives the same fp32 sum as a load + store, without waiting for the load.
+  // no-return hardware add gives the same fp32 sum as a load + store, without waiting for the load
+  // (requesting the old values before the loop and storing plainly was measured: not faster).
   if (A.accumulate) {
     for (int t = tid; t < len; t += T) {
       float inc = 0.0f;
       for (int g = 0; g < G; ++g) inc += fast_exp2(s_logit[(size_t)g * lgs + t] - s_lse2[g]);
-      unsafeAtomicAdd(score + s_slot[t], inc);
+      unsafeAtomicAdd((float*)(score + s_slot[t]), inc);
     }
   }
-  if (hk == 0 && tid == 0 && A.advance) sq.step = sq.step + 1;     // no other workgroup reads step
+  if (hk == 0 && tid == 0 && A.advance) sqp->step = sqp->step + 1;     // no other workgroup reads step
 }
 
 template <int D, int NW>
 hipError_t launch_gqa_w(const GqaArgs& A, int n_seq, size_t lds, hipStream_t st, hipEvent_t ev_start,
                         hipEvent_t ev_stop) {
   dim3 grid(A.n_heads, n_seq);     // (lists that need more than 64 KB of LDS: see gqa_prepare_kernels)
+  const int hgf = A.n_heads | (A.G << 16) | (A.append ? 1 << 24 : 0) | (A.new_f32 ? 1 << 25 : 0);
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_attend_gqa<D, NW>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0, A);
+    hipExtLaunchKernelGGL((k_attend_gqa<D, NW>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0,
+                          A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new, hgf, A.sel_cap, A);
   else
-    hipLaunchKernelGGL((k_attend_gqa<D, NW>), grid, dim3(NW * kWave), lds, st, A);
+    hipLaunchKernelGGL((k_attend_gqa<D, NW>), grid, dim3(NW * kWave), lds, st,
+                       A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new, hgf, A.sel_cap, A);
   return hipGetLastError();
 }
 
