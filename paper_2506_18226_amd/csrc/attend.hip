@@ -627,9 +627,9 @@ __global__ __launch_bounds__(NW * kWave) void k_attend(adsa_seq* seqs_arg, const
 template <int EB, int D, int HT, int NW, bool VF, bool DIRECT>
 hipError_t launch_attend_w(const AttendArgs& A, const AttendPlan& plan, int n_seq, hipStream_t st,
                            hipEvent_t ev_start, hipEvent_t ev_stop) {
-  // row pairs in flight per lane; 8 was measured slower (register pressure).  A 16-wave workgroup has
-  // 128 registers per lane: 2 pairs fit without spilling, and its 1024 lanes keep enough in flight
-  constexpr int U = NW == 16 ? 2 : 4;
+  // row pairs in flight per lane: 2, 3, 6 and 8 were measured slower on 4-wave workgroups; 16-wave workgroups
+  // (at most 128 registers per lane: the kernel needs < 100) run the same within 1 % with 2 or 4
+  constexpr int U = 4;
   const size_t lds = (size_t)((VF ? 2 : HT) + 1) * plan.chunk_max * sizeof(float);      // logits rows + the slot list
   dim3 grid(plan.n_chunks, plan.n_head_groups, n_seq);
   if (ev_start && ev_stop)

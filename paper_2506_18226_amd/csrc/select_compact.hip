@@ -398,19 +398,27 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   const uint32_t n_new = (total & 0xFFFFu) + min(total >> 16, need_eq);
 
   // in-place, order-preserving move of pos[] and every score row: ascending tiles, load -> barrier ->
-  // store.  A tile's destinations are <= its sources and below the next tile's sources.
-  for (int row = -1; row < L.score_rows; ++row) {
-    float* srow = row >= 0 ? sq.score + (size_t)row * L.cap : nullptr;
-    for (int base = (first / kSelThreads) * kSelThreads; base < n; base += kSelThreads) {
-      const int i = base + tid;
-      int m = -1, pv = 0;
-      float sv = 0.0f;
-      if (i < n) {
-        m = (int)key[i];
-        if (m >= 0 && m != i) { if (row < 0) pv = sq.pos[i]; else sv = srow[i]; }
-      }
+  // store.  A tile's destinations are <= its sources and below the next tile's sources; the rows are
+  // independent arrays, so kRowBatch of them travel together (their loads overlap: the move costs one
+  // memory round trip per tile and batch instead of one per tile and row).
+  constexpr int kRowBatch = 8;
+  for (int base = (first / kSelThreads) * kSelThreads; base < n; base += kSelThreads) {
+    const int i = base + tid;
+    const int m = i < n ? (int)key[i] : -1;
+    const bool mv = m >= 0 && m != i;
+    const int pv = mv ? sq.pos[i] : 0;
+    for (int r0 = 0; r0 < L.score_rows; r0 += kRowBatch) {
+      float sv[kRowBatch];
+#pragma unroll
+      for (int k = 0; k < kRowBatch; ++k)
+        sv[k] = (mv && r0 + k < L.score_rows) ? sq.score[(size_t)(r0 + k) * L.cap + i] : 0.0f;
       __syncthreads();
-      if (m >= 0 && m != i) { if (row < 0) sq.pos[m] = pv; else srow[m] = sv; }
+      if (mv) {
+        if (r0 == 0) sq.pos[m] = pv;
+#pragma unroll
+        for (int k = 0; k < kRowBatch; ++k)
+          if (r0 + k < L.score_rows) sq.score[(size_t)(r0 + k) * L.cap + m] = sv[k];
+      }
     }
   }
   if (tid == 0) {
