@@ -132,25 +132,44 @@ struct LaunchShape {
   long long slot_stride_b, head_stride_b;    // bytes
 };
 
-// Rank of slot i: sum over the score rows, ascending row order, plain fp32 adds (8 loads in flight).
-__device__ __forceinline__ float rank_value(const float* score, int rows, int cap, int i) {
-  float v = score[i];
-  int r = 1;
-  for (; r + 8 <= rows; r += 8) {
-    float t[8];
+// Ranks of kRankSlots slots at once (4 when few workgroups run and memory latency is what counts, 1 when the launch
+// fills the chip anyway and registers are better spent on occupancy): v[u] = sum over the score rows of slot idx[u], ascending row order, plain fp32
+// adds (the order one slot at a time would use); slots with on[u] false give 0 and touch no memory.  The loads of all
+// slots, and of the next batch of rows while one batch is added, are in flight together: a workgroup ranks its
+// sequence in two or three memory round trips instead of one per slot and batch.
+constexpr int kRankRows = 8;
+template <int kRankSlots>
+__device__ __forceinline__ void rank_values(const float* score, int rows, int cap, const int* idx, const bool* on, float* v) {
+  float cur[kRankSlots][kRankRows], nxt[kRankSlots][kRankRows];
+  auto load_rows = [&](int r0, float (&t)[kRankSlots][kRankRows]) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t[k] = score[(size_t)(r + k) * cap + i];
+    for (int u = 0; u < kRankSlots; ++u)
 #pragma unroll
-    for (int k = 0; k < 8; ++k) v += t[k];
+      for (int k = 0; k < kRankRows; ++k)
+        t[u][k] = (on[u] && r0 + k < rows) ? score[(size_t)(r0 + k) * cap + idx[u]] : 0.0f;
+  };
+#pragma unroll
+  for (int u = 0; u < kRankSlots; ++u) v[u] = on[u] ? score[idx[u]] : 0.0f;
+  if (rows > 1) load_rows(1, cur);
+  for (int r = 1; r < rows; r += kRankRows) {
+    if (r + kRankRows < rows) load_rows(r + kRankRows, nxt);
+#pragma unroll
+    for (int u = 0; u < kRankSlots; ++u)
+#pragma unroll
+      for (int k = 0; k < kRankRows; ++k)
+        if (r + k < rows) v[u] += cur[u][k];
+#pragma unroll
+    for (int u = 0; u < kRankSlots; ++u)
+#pragma unroll
+      for (int k = 0; k < kRankRows; ++k) cur[u][k] = nxt[u][k];
   }
-  for (; r < rows; ++r) v += score[(size_t)r * cap + i];
-  return v;
 }
 
 __device__ __forceinline__ bool keep_largest_of(int mode) {
   return mode == ADSA_SCORE_ATTN_MASS || mode == ADSA_SCORE_EXT_LARGEST;
 }
 
+template <int kRankSlots>
 __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq* seqs, int32_t* sel_idx,
                                                        int32_t* sel_cnt, int plan_append) {
   __shared__ RankShared sh;
@@ -192,15 +211,32 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
   const bool largest = keep_largest_of(L.score_mode);
   const bool ranked = L.evict_policy == ADSA_EVICT_ROW_END;
   uint32_t my_cand = 0;
-  for (int i = tid; i < n; i += kSelThreads) {
-    const bool planned = i == slot_new;             // the slot the query token will occupy
-    const bool freed = i == hole && !planned;       // evicted, not yet reused: nobody attends it
-    const int c = (planned || freed) ? 0 : select_class(cell, sq.pos[i]);
-    if (c < 0) s_bad = 1;
-    cls[i] = freed ? kSkip : c == 1 ? kCand : kFixed;
-    // (evict-one-when-full policies attend every candidate: their rank is never looked at)
-    key[i] = order_key((planned || !ranked) ? 0.0f : rank_value(sq.score, L.score_rows, L.cap, i), largest);
-    my_cand += (c == 1);
+  for (int i0 = tid; i0 < n; i0 += kRankSlots * kSelThreads) {
+    int idx[kRankSlots], posv[kRankSlots];
+    bool in[kRankSlots], planned[kRankSlots], rk[kRankSlots];
+    float rv[kRankSlots];
+#pragma unroll
+    for (int u = 0; u < kRankSlots; ++u) {
+      const int i = i0 + u * kSelThreads;
+      in[u] = i < n;
+      idx[u] = in[u] ? i : n - 1;
+      planned[u] = i == slot_new;                   // the slot the query token will occupy
+      posv[u] = sq.pos[idx[u]];
+      // (evict-one-when-full policies attend every candidate: their rank is never looked at)
+      rk[u] = in[u] && ranked && !planned[u];
+    }
+    rank_values<kRankSlots>(sq.score, L.score_rows, L.cap, idx, rk, rv);
+#pragma unroll
+    for (int u = 0; u < kRankSlots; ++u) {
+      if (!in[u]) continue;
+      const int i = idx[u];
+      const bool freed = i == hole && !planned[u];  // evicted, not yet reused: nobody attends it
+      const int c = (planned[u] || freed) ? 0 : select_class(cell, posv[u]);
+      if (c < 0) s_bad = 1;
+      cls[i] = freed ? kSkip : c == 1 ? kCand : kFixed;
+      key[i] = order_key(rv[u], largest);
+      my_cand += (c == 1);
+    }
   }
   uint32_t n_cand;
   block_excl_scan(sh, my_cand, &n_cand);   // also orders the LDS writes above before the reads below
@@ -258,6 +294,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(LaunchShape L, adsa_seq*
 }
 
 // plan[b] = { old n_res, first slot that moves, did compact, new n_res }
+template <int kRankSlots>
 __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, adsa_seq* seqs,
                                                              int32_t* keep_map, int32_t* plan,
                                                              int advance_step, const float* vcos_s) {
@@ -286,13 +323,29 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   const QueryCell cell = make_query_cell(sq, s, W, L.R, L.w, L.recent_m);
   const bool largest = keep_largest_of(L.score_mode);
   uint32_t my_rest = 0;
-  for (int i = tid; i < n; i += kSelThreads) {
-    // streaming: the partition of the incoming query (its local region must survive)
-    const int c = streaming ? (select_class(cell, sq.pos[i]) == 1 ? 1 : 0) : evict_class(cell, sq.pos[i]);
-    cls[i] = c == 1 ? kCand : kFixed;
-    key[i] = L.score_mode == ADSA_SCORE_VCOS_FUSED ? 0u      // (keys of the candidates follow once N is known)
-                                                   : order_key(rank_value(sq.score, L.score_rows, L.cap, i), largest);
-    my_rest += (c == 1);
+  for (int i0 = tid; i0 < n; i0 += kRankSlots * kSelThreads) {
+    int idx[kRankSlots], posv[kRankSlots];
+    bool in[kRankSlots], rk[kRankSlots];
+    float rv[kRankSlots];
+#pragma unroll
+    for (int u = 0; u < kRankSlots; ++u) {
+      const int i = i0 + u * kSelThreads;
+      in[u] = i < n;
+      idx[u] = in[u] ? i : n - 1;
+      posv[u] = sq.pos[idx[u]];
+      rk[u] = in[u] && L.score_mode != ADSA_SCORE_VCOS_FUSED;      // (fused form: keys of the candidates follow once N is known)
+    }
+    rank_values<kRankSlots>(sq.score, L.score_rows, L.cap, idx, rk, rv);
+#pragma unroll
+    for (int u = 0; u < kRankSlots; ++u) {
+      if (!in[u]) continue;
+      const int i = idx[u];
+      // streaming: the partition of the incoming query (its local region must survive)
+      const int c = streaming ? (select_class(cell, posv[u]) == 1 ? 1 : 0) : evict_class(cell, posv[u]);
+      cls[i] = c == 1 ? kCand : kFixed;
+      key[i] = L.score_mode == ADSA_SCORE_VCOS_FUSED ? 0u : order_key(rv[u], largest);
+      my_rest += (c == 1);
+    }
   }
   uint32_t n_rest;
   block_excl_scan(sh, my_rest, &n_rest);
@@ -401,23 +454,33 @@ __global__ __launch_bounds__(kSelThreads) void k_compact_plan(LaunchShape L, ads
   // store.  A tile's destinations are <= its sources and below the next tile's sources; the rows are
   // independent arrays, so kRowBatch of them travel together (their loads overlap: the move costs one
   // memory round trip per tile and batch instead of one per tile and row).
-  constexpr int kRowBatch = 8;
-  for (int base = (first / kSelThreads) * kSelThreads; base < n; base += kSelThreads) {
-    const int i = base + tid;
-    const int m = i < n ? (int)key[i] : -1;
-    const bool mv = m >= 0 && m != i;
-    const int pv = mv ? sq.pos[i] : 0;
-    for (int r0 = 0; r0 < L.score_rows; r0 += kRowBatch) {
-      float sv[kRowBatch];
+  constexpr int kRowBatch = 8, kTileSlots = 4;       // a tile: kTileSlots slots per thread
+  for (int base = (first / kSelThreads) * kSelThreads; base < n; base += kTileSlots * kSelThreads) {
+    int m[kTileSlots], src[kTileSlots], pv[kTileSlots];
+    bool mv[kTileSlots];
 #pragma unroll
-      for (int k = 0; k < kRowBatch; ++k)
-        sv[k] = (mv && r0 + k < L.score_rows) ? sq.score[(size_t)(r0 + k) * L.cap + i] : 0.0f;
-      __syncthreads();
-      if (mv) {
-        if (r0 == 0) sq.pos[m] = pv;
+    for (int u = 0; u < kTileSlots; ++u) {
+      const int i = base + u * kSelThreads + tid;
+      m[u] = i < n ? (int)key[i] : -1;
+      mv[u] = m[u] >= 0 && m[u] != i;
+      src[u] = mv[u] ? i : 0;
+      pv[u] = mv[u] ? sq.pos[i] : 0;
+    }
+    for (int r0 = 0; r0 < L.score_rows; r0 += kRowBatch) {
+      float sv[kTileSlots][kRowBatch];
+#pragma unroll
+      for (int u = 0; u < kTileSlots; ++u)
 #pragma unroll
         for (int k = 0; k < kRowBatch; ++k)
-          if (r0 + k < L.score_rows) sq.score[(size_t)(r0 + k) * L.cap + m] = sv[k];
+          sv[u][k] = (mv[u] && r0 + k < L.score_rows) ? sq.score[(size_t)(r0 + k) * L.cap + src[u]] : 0.0f;
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < kTileSlots; ++u) {
+        if (!mv[u]) continue;
+        if (r0 == 0) sq.pos[m[u]] = pv[u];
+#pragma unroll
+        for (int k = 0; k < kRowBatch; ++k)
+          if (r0 + k < L.score_rows) sq.score[(size_t)(r0 + k) * L.cap + m[u]] = sv[u][k];
       }
     }
   }
@@ -483,10 +546,17 @@ LaunchShape shape_of(const adsa_params& p) {
 
 }  // namespace
 
+// from this many sequences per launch on the ranking kernels are throughput-bound (two workgroups per CU and more)
+constexpr int kManySequences = 512;
+
 hipError_t launch_select(const adsa_params& p, adsa_seq* seqs, int32_t* sel_idx, int32_t* sel_cnt,
                          bool plan_append, hipStream_t st) {
-  hipLaunchKernelGGL(k_select, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, shape_of(p), seqs,
-                     sel_idx, sel_cnt, plan_append ? 1 : 0);
+  if (p.n_seq >= kManySequences)
+    hipLaunchKernelGGL(k_select<1>, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, shape_of(p), seqs,
+                       sel_idx, sel_cnt, plan_append ? 1 : 0);
+  else
+    hipLaunchKernelGGL(k_select<4>, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, shape_of(p), seqs,
+                       sel_idx, sel_cnt, plan_append ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -495,8 +565,12 @@ hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_ma
   int32_t* plan = reinterpret_cast<int32_t*>(ws + w.plan_off);
   LaunchShape L = shape_of(p);
   const float* vcos_s = p.score_mode == ADSA_SCORE_VCOS_FUSED ? reinterpret_cast<const float*>(ws + w.vcos_s_off) : nullptr;
-  hipLaunchKernelGGL(k_compact_plan, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, L, seqs,
-                     keep_map, plan, advance_step ? 1 : 0, vcos_s);
+  if (p.n_seq >= kManySequences)
+    hipLaunchKernelGGL(k_compact_plan<1>, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, L, seqs,
+                       keep_map, plan, advance_step ? 1 : 0, vcos_s);
+  else
+    hipLaunchKernelGGL(k_compact_plan<4>, dim3(p.n_seq), dim3(kSelThreads), rank_lds_bytes(p.cap), st, L, seqs,
+                       keep_map, plan, advance_step ? 1 : 0, vcos_s);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || p.evict_policy == ADSA_EVICT_REUSE_SLOT) return e;     // slot reuse moves no row
   // one workgroup per 128-byte column slice of a head row (whole head row when it is narrower)
