@@ -47,6 +47,8 @@ int validate_resolved(const adsa_params* p) {
   if (p->q_per_kv > 1) {       // grouped queries run on the bf16 matrix cores, logits of one list in LDS
     if (p->dtype != ADSA_BF16) return ADSA_ERR_UNSUPPORTED;
     if (gqa_lds_bytes(*p, make_attend_plan(*p).waves) > kGqaMaxLds) return ADSA_ERR_UNSUPPORTED;
+    // the kernel reaches a head's rows with 32-bit byte offsets
+    if ((long long)p->cap * p->kv_slot_stride * 2 >= (1ll << 32)) return ADSA_ERR_UNSUPPORTED;
   }
   return ADSA_OK;
 }

@@ -98,6 +98,10 @@ def test_grouped_query_parameters(lib):
     big = dict(dtype=B.BF16, cap=B.MAX_CAP, sel_cap=B.MAX_CAP, kv_slot_stride=None, kv_head_stride=None)
     assert B.adsa_workspace_bytes(good(q_per_kv=2, **big)) > 0            # 3 x 8.2k x 4 B of logits: fits
     assert B.adsa_workspace_bytes(good(q_per_kv=16, **big)) == 0          # 17 x 8.2k x 4 B: does not
+    # a head's rows are addressed with 32-bit byte offsets: padded strides that push them past 4 GiB are refused
+    wide = dict(dtype=B.BF16, cap=8192, sel_cap=128, kv_slot_stride=1 << 18, kv_head_stride=64)
+    assert B.adsa_workspace_bytes(good(q_per_kv=1, **wide)) > 0
+    assert B.adsa_workspace_bytes(good(q_per_kv=2, **wide)) == 0
 
 
 def test_fused_vcos_parameters(lib):
