@@ -521,6 +521,55 @@ def test_rank_is_the_sum_of_the_per_head_score_rows():
             assert np.array_equal(score_rows[b, :, :kept.size], rows_all[b][:, kept])
 
 
+@pytest.mark.parametrize("n_seq,h", [(6, 3), (6, 11), (6, 26), (520, 3), (520, 11), (520, 26)])
+def test_ranking_kernels_at_both_launch_sizes(n_seq, h):
+    """The ranking kernels fetch the score rows of one slot (launches of >= 512 sequences) or of four slots
+    (smaller launches) at a time, eight rows per batch: both forms, with 3, 11 and 26 score rows (one partial batch,
+    two, four), against the oracle given the summed array.  Row sums are exact in fp32, so the sum is order-free:
+    attended sets, keep maps and moved score rows bit for bit."""
+    rng = np.random.default_rng(1000 * n_seq + h)
+    W, H, P = 6, 9, 5
+    wl = WL.get_workload("tiny", n_heads=h, head_dim=64, grid_h=H, grid_w=W, prefix_len=P, win_rows_back=1, win_col_radius=1)
+    q, k, v = WL.gen_tokens(wl, 0, 0)
+    cap = P + H * W
+    params = params_for(wl, n_seq, cap, score_mode=B.SCORE_ATTN_MASS)
+    batch = LayerBatch(params, DEV)
+    cases = []
+    for b in range(n_seq):
+        s = int(rng.integers(1, H * W + 1)) if b % 3 else W * int(rng.integers(1, H + 1))      # a third at row ends
+        Bud = int(rng.integers(0, 12))
+        n = P + s
+        rows = (rng.integers(0, 5, size=(h, n)) / 8.0).astype(np.float32)
+        cfg = oracle_cfg(wl, P=P, budget=Bud, score_mode=B.SCORE_ATTN_MASS, cap=cap)
+        pos = np.arange(n, dtype=np.int32)
+        cases.append((s, Bud, rows, cfg, pos))
+        batch.set_sequence(b, k=k[:n], v=v[:n], pos=pos, score=rows, step=s, grid_origin=P, budget=Bud)
+    batch.upload_seqs()
+    batch.select()
+    batch.compact()
+    torch.cuda.synchronize()
+    sel_idx, sel_cnt, km = batch.sel_idx.cpu().numpy(), batch.sel_cnt.cpu().numpy(), batch.keep_map.cpu().numpy()
+    score_rows, posd = batch.score.cpu().numpy(), batch.pos.cpu().numpy()
+    seqs = batch.read_seqs()
+    assert (seqs["status"] == 0).all()
+    n_compacted = 0
+    for b, (s, Bud, rows, cfg, pos) in enumerate(cases):
+        total = rows.sum(axis=0, dtype=np.float32)
+        ref_sel, _ = oracle.select(cfg, pos, total, None, s)
+        assert sel_cnt[b] == ref_sel.size and np.array_equal(sel_idx[b, :sel_cnt[b]], ref_sel), (b, s, Bud)
+        n = P + s
+        st = oracle.CacheState.from_arrays(cfg, k[:n], v[:n], pos, total)
+        ref_map, did = oracle.compact(cfg, st, s)
+        assert bool(seqs["compacted"][b]) == did and seqs["n_res"][b] == st.n_res, (b, s, Bud)
+        if did:
+            n_compacted += 1
+            assert np.array_equal(km[b, :n], ref_map), (b, s, Bud)
+            kept = np.nonzero(ref_map >= 0)[0]
+            assert np.array_equal(score_rows[b, :, :kept.size], rows[:, kept]), (b, s, Bud)
+            assert np.array_equal(posd[b, :kept.size], pos[kept]), (b, s, Bud)
+    assert n_compacted >= n_seq // 4
+
+
 # ----------------------------------------------------------------------------- TopK-V (Eq. 2-4) on the GPU
 def vcos_close(gpu, ref):
     """fp32 two-pass closed form vs the fp64 pairwise definition: |S| <= 1, sums of up to ~1e3 unit
