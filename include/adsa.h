@@ -149,8 +149,7 @@ typedef struct adsa_params {
   int32_t evict_policy;        /* adsa_evict_policy */
   int32_t q_per_kv;            /* G: query heads per cache head.  0 or 1: multi-head attention.  2..16:
                                   grouped-query attention, query head j reads cache head floor(j/G); bf16 only,
-                                  the logits of one list, (G + 1) * (sel_cap + 32) * 4 bytes, must fit in about
-                                  100 KB of LDS, and one head's rows must span less than 4 GiB
+                                  one head's rows must span less than 4 GiB
                                   (cap * kv_slot_stride * 2 bytes: the kernel addresses them with 32-bit
                                   offsets), else ADSA_ERR_UNSUPPORTED */
 } adsa_params;

@@ -80,4 +80,19 @@ __device__ __forceinline__ float xor_max(float x) {
   }
 }
 
+// Data handed from one workgroup to another inside a launch (chunk partials, logits) is written
+// and read with device-scope atomic accesses: they go through to the level where all XCDs agree
+// and are never left dirty in (or served stale from) one XCD's L2.  The order between them and the
+// arrival counter is made in the kernels' split paths (completed stores, barrier, release/acquire ticket).
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev2(float* p, float a, float b) {   // 8-byte aligned pair
+  const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 }  // namespace adsa

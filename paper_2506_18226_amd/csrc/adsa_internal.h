@@ -14,6 +14,7 @@ namespace adsa {
 constexpr int kWave = 64;
 constexpr int kSelThreads = 256;       // select / compact-plan workgroup
 constexpr int kMoveThreads = 256;
+constexpr int kMaxChunks = 16;         // a list is split over at most this many workgroups
 
 // Attend launch plan: a workgroup handles (sequence, head group, token chunk).
 struct AttendPlan {
@@ -74,14 +75,16 @@ hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq*
                          const void* k_new, const void* v_new, const int32_t* sel_idx, const int32_t* sel_cnt,
                          void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
                          bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
-// grouped-query path (q_per_kv >= 2): matrix-core kernel, one workgroup per (sequence, cache head)
+// grouped-query path (q_per_kv >= 2): matrix-core kernel, one workgroup per (sequence, cache head, chunk of the list)
 constexpr size_t kGqaMaxLds = 128 * 1024;     // dynamic LDS one workgroup may ask for
-int gqa_logit_stride(const adsa_params& p);
-size_t gqa_lds_bytes(const adsa_params& p, int waves);
+int gqa_logit_stride(const adsa_params& p, int n_chunks);
+int gqa_global_logit_stride(const adsa_params& p);
+size_t gqa_lds_bytes(const adsa_params& p, int waves, int n_chunks);
 hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
                              const void* k_new, const void* v_new, const int32_t* sel_idx,
-                             const int32_t* sel_cnt, void* out, float* lse, bool accumulate, bool append,
-                             bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop);
+                             const int32_t* sel_cnt, void* out, float* lse, char* ws, const Workspace& w,
+                             bool accumulate, bool append, bool advance, bool new_f32, hipStream_t st,
+                             hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t launch_compact(const adsa_params& p, adsa_seq* seqs, int32_t* keep_map, char* ws,
                           const Workspace& w, bool advance_step, hipStream_t st);
 // once per device, before the first launch there: kernels that may ask for more than 64 KB of dynamic LDS

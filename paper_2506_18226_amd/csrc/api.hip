@@ -44,9 +44,10 @@ int validate_resolved(const adsa_params* p) {
     // m = 1: the token that turns candidate next step is not resident yet when the running sum is advanced
     if (p->win_recent_m < 2) return ADSA_ERR_UNSUPPORTED;
   }
-  if (p->q_per_kv > 1) {       // grouped queries run on the bf16 matrix cores, logits of one list in LDS
+  if (p->q_per_kv > 1) {       // grouped queries run on the bf16 matrix cores, logits of one chunk of the list in LDS
     if (p->dtype != ADSA_BF16) return ADSA_ERR_UNSUPPORTED;
-    if (gqa_lds_bytes(*p, make_attend_plan(*p).waves) > kGqaMaxLds) return ADSA_ERR_UNSUPPORTED;
+    const AttendPlan gp = make_attend_plan(*p);
+    if (gqa_lds_bytes(*p, gp.waves, gp.n_chunks) > kGqaMaxLds) return ADSA_ERR_UNSUPPORTED;
     // the kernel reaches a head's rows with 32-bit byte offsets
     if ((long long)p->cap * p->kv_slot_stride * 2 >= (1ll << 32)) return ADSA_ERR_UNSUPPORTED;
   }

@@ -28,7 +28,6 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kMaxChunks = 16;
 
 // Sum over the LPR consecutive lanes that hold one row; every lane of the group gets the sum.
 template <int LPR>
@@ -58,21 +57,6 @@ template <> struct Elems<4> {      // fp32: 4 values per 16-byte vector
     f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
   }
 };
-
-// Data handed from one workgroup to another inside a launch (chunk partials, logits) is written
-// and read with device-scope atomic accesses: they go through to the level where all XCDs agree
-// and are never left dirty in (or served stale from) one XCD's L2.  The order between them and the
-// arrival counter is made in k_attend's split path (completed stores, barrier, release/acquire ticket).
-__device__ __forceinline__ void st_dev(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_dev(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_dev2(float* p, float a, float b) {   // 8-byte aligned pair
-  const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
-  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // chunk c of a list of cnt (<= ADSA_MAX_CAP) tokens split evenly over nc (<= kMaxChunks) chunks
 __device__ __forceinline__ int chunk_begin(int cnt, int c, int nc) { return (int)(((unsigned)cnt * (unsigned)c) / (unsigned)nc); }
@@ -675,14 +659,30 @@ AttendPlan make_attend_plan(const adsa_params& p) {
   const int rpw = kWave / a.lanes_per_row;
   // [slot][head][D]: a wave-load takes rpw heads of one token; [head][slot][D]: rpw tokens of one head
   a.head_major = p.kv_slot_stride < p.kv_head_stride;
-  if (p.q_per_kv > 1) {      // grouped queries: one workgroup per (sequence, cache head), never split
+  if (p.q_per_kv > 1) {      // grouped queries: one workgroup per (sequence, cache head, chunk of whole 16-token tiles)
     a.heads_per_group = 1;
     a.n_head_groups = p.n_heads;
     const long long wgs = (long long)p.n_seq * p.n_heads;
     a.waves = wgs >= 512 ? 4 : 8;
-    while (a.waves > 4 && gqa_lds_bytes(p, a.waves) > kGqaMaxLds) a.waves /= 2;
-    a.n_chunks = 1;
-    a.chunk_max = p.sel_cap + 1;
+    // Lists are split only when they must be (the logits of a whole list, all G queries, do not fit in LDS even
+    // with 4 waves) or when it was measured to pay: long lists (>= 2560 slots) of at most 32 (sequence, cache head)
+    // pairs.  The hand-off between workgroups costs a release/acquire at device scope per workgroup, which grows
+    // with the number of workgroups: 88 pairs x 16 chunks of 2800-token lists took 82 us, unsplit 42 us; one
+    // sequence (8 pairs) 25 us against 41 us.  Hence: as many chunks as fit the LDS limit, and more only while the
+    // launch stays near 128 workgroups.
+    int nc = 1;
+    const bool must = gqa_lds_bytes(p, 4, 1) > kGqaMaxLds;
+    if (must || (p.sel_cap >= 2560 && wgs <= 32)) {
+      while (nc < kMaxChunks && gqa_lds_bytes(p, 4, nc) > kGqaMaxLds) ++nc;
+      int more = (int)((128 + wgs - 1) / wgs);
+      if (more > p.sel_cap / 160) more = p.sel_cap / 160;
+      if (more > kMaxChunks) more = kMaxChunks;
+      if (nc < more) nc = more;
+    }
+    while (nc == 1 && a.waves > 4 && gqa_lds_bytes(p, a.waves, 1) > kGqaMaxLds) a.waves /= 2;
+    if (nc > 1) a.waves = 4;
+    a.n_chunks = nc;
+    a.chunk_max = gqa_logit_stride(p, nc);
     return a;
   }
   a.heads_per_group = a.head_major ? 1 : rpw;
@@ -716,16 +716,17 @@ Workspace make_workspace(const adsa_params& p, const AttendPlan& plan) {
   Workspace w;
   size_t off = 0;
   const bool split = plan.n_chunks > 1;
-  w.lg_stride = (int)align_up((size_t)p.sel_cap, 4);
+  const size_t hq = (size_t)p.n_heads * (p.q_per_kv > 1 ? p.q_per_kv : 1);      // rows of out / logits / partials per sequence
+  w.lg_stride = p.q_per_kv > 1 ? gqa_global_logit_stride(p) : (int)align_up((size_t)p.sel_cap, 4);
   w.counters_off = off;
   off = align_up(off + sizeof(int32_t) * (size_t)p.n_seq * plan.n_head_groups, 256);
   w.persistent_bytes = off;     // must stay zero between launches
   w.logits_off = off;
-  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * w.lg_stride, 256);
+  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * hq * w.lg_stride, 256);
   w.part_ml_off = off;
-  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * 2, 256);
+  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * hq * plan.n_chunks * 2, 256);
   w.part_acc_off = off;
-  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * p.n_heads * plan.n_chunks * p.head_dim, 256);
+  if (split) off = align_up(off + sizeof(float) * (size_t)p.n_seq * hq * plan.n_chunks * p.head_dim, 256);
   w.plan_off = off;
   off = align_up(off + sizeof(int32_t) * (size_t)p.n_seq * 4, 256);
   w.vcos_off = off;
@@ -754,7 +755,7 @@ hipError_t launch_attend(const adsa_params& p, const AttendPlan& plan, adsa_seq*
                          void* out, float* lse, char* ws, const Workspace& w, bool accumulate, bool append,
                          bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (p.q_per_kv > 1)
-    return launch_attend_gqa(p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, accumulate, append,
+    return launch_attend_gqa(p, plan, seqs, q, k_new, v_new, sel_idx, sel_cnt, out, lse, ws, w, accumulate, append,
                              advance, new_f32, st, ev_start, ev_stop);
   AttendArgs A;
   A.seqs = seqs; A.q = (const char*)q; A.k_new = (const char*)k_new; A.v_new = (const char*)v_new;

@@ -90,6 +90,11 @@ struct GqaArgs {
   const int32_t* sel_cnt;
   char* out;
   float* lse;
+  float* logits;        // [n_seq][n_heads * G][lg_global]  scaled logits, log2 units (split launches)
+  float* part_ml;       // [n_seq][n_heads * G][n_chunks][2]
+  float* part_acc;      // [n_seq][n_heads * G][n_chunks][D]
+  int32_t* counters;    // [n_seq][n_heads]                 arrival counters, zero between launches
+  int lg_global;        // row stride of logits
   int n_heads, G, sel_cap, lg_stride, cap, stage_b;
   int accumulate, append, advance;
   int new_f32;          // k_new / v_new are fp32 although the cache is bf16: round as they enter
@@ -101,7 +106,10 @@ struct GqaArgs {
 // arguments to be preloaded into scalar registers at wave launch): the vector loads of that trip then leave
 // without waiting for a scalar load of the argument block.  Only 14 dwords are preloaded, so the group size and
 // the two append flags ride on the head count: heads | G << 16 | append << 24 | new_f32 << 25.
-template <int D, int NW>
+// SPLIT: the list of a (sequence, cache head) is cut into gridDim.z chunks of whole 16-token tiles, one workgroup
+// each; every workgroup leaves a partial and its logits in the workspace and the LAST one to arrive merges them, in
+// chunk order (an arrival counter; nothing waits).
+template <int D, int NW, bool SPLIT>
 __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(adsa_seq* seqs_arg, const int32_t* sel_idx_arg, const int32_t* sel_cnt_arg,
                                                           const char* q_arg, const char* k_new_arg, const char* v_new_arg,
                                                           int heads_g_flags, int sel_cap_arg, GqaArgs A) {
@@ -117,9 +125,11 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(adsa_seq* seqs_arg, c
                                             // 1, 2 and 3 were measured within 1 % of each other on 8 x 128 x 8-wave lists)
   constexpr int PF = 2048 / T;              // slot-list entries a thread fetches in the first round trip
   extern __shared__ __align__(16) char smem[];
-  __shared__ float s_wm[NW][16], s_wl[NW][16], s_lse2[16];
+  __shared__ float s_wm[NW][16], s_wl[NW][16], s_lse2[16], s_m[16], s_l[16];
+  __shared__ int s_ticket;
 
   const int hk = blockIdx.x, b = blockIdx.y;
+  const int chunk = SPLIT ? blockIdx.z : 0, n_chunks = SPLIT ? gridDim.z : 1;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int r = lane & 15, kg = lane >> 4;                 // matrix-operand role of this lane
@@ -144,9 +154,11 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(adsa_seq* seqs_arg, c
   uint4 qx[NC / 2];
 #pragma unroll
   for (int c2 = 0; c2 < NC / 2; ++c2) qx[c2] = load16(q_row0 + ((size_t)min(r, G - 1) * D + (D / 4) * kg) * 2 + c2 * 16);
-  int pf_slot[PF];
+  int pf_slot[PF];                                   // (a chunk of a split list starts where the count says: fetched below)
+  if constexpr (!SPLIT) {
 #pragma unroll
-  for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * T, sel_cap - 1)];
+    for (int k = 0; k < PF; ++k) pf_slot[k] = idx[min(tid + k * T, sel_cap - 1)];
+  }
   // the query token's row (Section 4.2 append); fp32 rows are rounded once, here: every lane keeps the pieces of
   // the rounded row it would load from the cache (K: 16 bytes at ld_piece, V: its EV columns)
   const int ld_row = lane / LPR, ld_piece = lane - ld_row * LPR;
@@ -190,21 +202,34 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(adsa_seq* seqs_arg, c
 
   const int cnt = min(cnt_raw, sel_cap);
   if (cnt <= 0) {                                    // inactive or rejected sequence: zero-filled rows
-    for (int o = tid; o < G * D; o += T) {
-      out[o] = 0;
-      if (o % D == 0) lse[o / D] = 0.0f;
+    if (chunk == 0) {
+      for (int o = tid; o < G * D; o += T) {
+        out[o] = 0;
+        if (o % D == 0) lse[o / D] = 0.0f;
+      }
     }
     return;
   }
-  const int len = cnt;
-  const int n_tiles = (len + 15) / 16;
+  // this workgroup's tiles of the list: all of them, or chunk `chunk` of n_chunks (whole tiles; the last chunk is
+  // never empty, chunks beyond the number of tiles are)
+  const int tiles_all = (cnt + 15) / 16;
+  const int tile_begin = SPLIT ? (int)(((unsigned)tiles_all * (unsigned)chunk) / (unsigned)n_chunks) : 0;
+  const int tile_end = SPLIT ? (int)(((unsigned)tiles_all * (unsigned)(chunk + 1)) / (unsigned)n_chunks) : tiles_all;
+  if (tile_begin >= tile_end) return;
+  const int t_begin = tile_begin * 16;
+  const int len = min(cnt, tile_end * 16) - t_begin;           // tokens of this workgroup, numbered from 0 below
+  const int n_tiles = tile_end - tile_begin;
   // slots of the list, clamped into the cache, go to LDS (readers clamp their list position to the last token)
+  if constexpr (!SPLIT) {
 #pragma unroll
-  for (int k = 0; k < PF; ++k) {
-    const int j = tid + k * T;
-    if (j < len) s_slot[j] = min(max(pf_slot[k], 0), A.cap - 1);
+    for (int k = 0; k < PF; ++k) {
+      const int j = tid + k * T;
+      if (j < len) s_slot[j] = min(max(pf_slot[k], 0), A.cap - 1);
+    }
+    for (int j = tid + PF * T; j < len; j += T) s_slot[j] = min(max(idx[j], 0), A.cap - 1);
+  } else {
+    for (int j = tid; j < len; j += T) s_slot[j] = min(max(idx[t_begin + j], 0), A.cap - 1);
   }
-  for (int j = tid + PF * T; j < len; j += T) s_slot[j] = min(max(idx[j], 0), A.cap - 1);
   s16x4 qb[NC];
 #pragma unroll
   for (int c2 = 0; c2 < NC / 2; ++c2) {
@@ -384,19 +409,27 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(adsa_seq* seqs_arg, c
       s_wm[w][tid] = wgt;
     }
     s_lse2[tid] = M + __log2f(L);
+    s_m[tid] = M; s_l[tid] = L;
     s_wl[0][tid] = 1.0f / L;
   }
   __syncthreads();
+  const size_t hq0 = (size_t)b * HQ + (size_t)hk * G;           // first query head of this cache head
   for (int o = tid; o < G * D; o += T) {
     const int g = o / D, d = o - g * D;
     float a = 0.0f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) a = fmaf(reinterpret_cast<const float*>(s_stage + w * A.stage_b)[o], s_wm[w][g], a);
-    out[o] = (uint16_t)f32_to_bf16_rne(a * s_wl[0][g]);
-    if (d == 0) lse[g] = s_lse2[g] * kLn2;
+    if constexpr (!SPLIT) {
+      out[o] = (uint16_t)f32_to_bf16_rne(a * s_wl[0][g]);
+      if (d == 0) lse[g] = s_lse2[g] * kLn2;
+    } else {                                         // this chunk's partial, relative to its own maximum
+      const size_t pidx = (hq0 + g) * n_chunks + chunk;
+      st_dev(A.part_acc + pidx * D + d, a);
+      if (d == 0) st_dev2(A.part_ml + pidx * 2, s_m[g], s_l[g]);
+    }
   }
   // Section 4.2 append: this cache head's rows of the new token, from the registers that attended them
-  if (new_slot >= 0 && wave == 0) {
+  if (new_slot >= 0 && wave == 0 && chunk == n_chunks - 1) {
     const long long off = (long long)new_slot * slot_stride_b;
     if (ld_row == 0) store16(k_base + off + ld_piece * 16, nk);
     if (kg == 0) {
@@ -408,39 +441,116 @@ __global__ __launch_bounds__(NW * kWave) void k_attend_gqa(adsa_seq* seqs_arg, c
     }
   }
 
-  // ---------------- attention mass of this cache head: sum over its G queries, ascending
-  // Each (cache head, slot) word is touched by exactly one thread of one workgroup per launch, so a
-  // no-return hardware add gives the same fp32 sum as a load + store, without waiting for the load
-  // (requesting the old values before the loop and storing plainly was measured: not faster).
-  if (A.accumulate) {
-    for (int t = tid; t < len; t += T) {
-      float inc = 0.0f;
-      for (int g = 0; g < G; ++g) inc += fast_exp2(s_logit[(size_t)g * lgs + t] - s_lse2[g]);
-      unsafeAtomicAdd((float*)(score + s_slot[t]), inc);
+  if constexpr (!SPLIT) {
+    // ---------------- attention mass of this cache head: sum over its G queries, ascending
+    // Each (cache head, slot) word is touched by exactly one thread of one workgroup per launch, so a
+    // no-return hardware add gives the same fp32 sum as a load + store, without waiting for the load
+    // (requesting the old values before the loop and storing plainly was measured: not faster).
+    if (A.accumulate) {
+      for (int t = tid; t < len; t += T) {
+        float inc = 0.0f;
+        for (int g = 0; g < G; ++g) inc += fast_exp2(s_logit[(size_t)g * lgs + t] - s_lse2[g]);
+        unsafeAtomicAdd((float*)(score + s_slot[t]), inc);
+      }
     }
+    if (hk == 0 && tid == 0 && A.advance) sqp->step = sqp->step + 1;     // no other workgroup reads step
+  } else {
+    // ---------------- several chunks: publish the logits, arrive, and let the last workgroup finish the cache head.
+    // Partials and logits are written with device-scope atomic stores (written through to where all XCDs agree);
+    // every thread waits until its own stores have completed, the barrier collects the workgroup, one thread bumps
+    // the arrival counter with a device-scope release/acquire read-modify-write, and the workgroup that draws the
+    // last ticket reads everything back with device-scope atomic loads after the barrier that follows its acquire.
+    const int lgG = A.lg_global;
+    if (keep_logits) {
+      for (int i = tid; i < G * len; i += T) {
+        const int g = i / len, t = i - g * len;
+        st_dev(A.logits + (hq0 + g) * lgG + t_begin + t, s_logit[(size_t)g * lgs + t]);
+      }
+    }
+    const int n_nonempty = min(tiles_all, n_chunks);
+    int32_t* ctr = A.counters + (size_t)b * n_heads + hk;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) s_ticket = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_ticket != n_nonempty - 1) return;
+    if (tid == 0) *ctr = 0;                          // ready for the next launch
+    for (int o = tid; o < G * D; o += T) {
+      const int g = o / D, d = o - g * D;
+      const size_t pbase = (hq0 + g) * n_chunks;
+      float mc[kMaxChunks], lc[kMaxChunks], ac[kMaxChunks];
+#pragma unroll
+      for (int c = 0; c < kMaxChunks; ++c) {         // all loads in flight together
+        const bool on = c < n_chunks && ((unsigned)tiles_all * (unsigned)c) / (unsigned)n_chunks <
+                                            ((unsigned)tiles_all * (unsigned)(c + 1)) / (unsigned)n_chunks;
+        mc[c] = on ? ld_dev(A.part_ml + (pbase + c) * 2) : -INFINITY;
+        lc[c] = on ? ld_dev(A.part_ml + (pbase + c) * 2 + 1) : 0.0f;
+        ac[c] = on ? ld_dev(A.part_acc + (pbase + c) * D + d) : 0.0f;
+      }
+      float Mx = -INFINITY;
+#pragma unroll
+      for (int c = 0; c < kMaxChunks; ++c) Mx = fmaxf(Mx, mc[c]);
+      float Lx = 0.0f, a = 0.0f;
+#pragma unroll
+      for (int c = 0; c < kMaxChunks; ++c) {
+        const float wgt = (mc[c] == -INFINITY) ? 0.0f : fast_exp2(mc[c] - Mx);
+        Lx = fmaf(lc[c], wgt, Lx);
+        a = fmaf(ac[c], wgt, a);
+      }
+      out[o] = (uint16_t)f32_to_bf16_rne(__fdividef(a, Lx));
+      if (d == 0) {
+        const float lse2 = Mx + __log2f(Lx);
+        lse[g] = lse2 * kLn2;
+        s_lse2[g] = lse2;
+      }
+    }
+    if (A.accumulate) {
+      __syncthreads();
+      for (int t0 = tid; t0 < cnt; t0 += 2 * T) {     // two tokens per thread and trip: all their logits in flight together
+        float z[2][16];
+        int slot[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int t = min(t0 + u * T, cnt - 1);
+#pragma unroll
+          for (int g = 0; g < 16; ++g) z[u][g] = g < G ? ld_dev(A.logits + (hq0 + g) * lgG + t) : 0.0f;
+          slot[u] = min(max(idx[t], 0), A.cap - 1);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          if (t0 + u * T >= cnt) continue;
+          float inc = 0.0f;
+#pragma unroll
+          for (int g = 0; g < 16; ++g)
+            if (g < G) inc += fast_exp2(z[u][g] - s_lse2[g]);
+          unsafeAtomicAdd((float*)(score + slot[u]), inc);
+        }
+      }
+    }
+    if (hk == 0 && tid == 0 && A.advance) sqp->step = sqp->step + 1;
   }
-  if (hk == 0 && tid == 0 && A.advance) sqp->step = sqp->step + 1;     // no other workgroup reads step
 }
 
-template <int D, int NW>
-hipError_t launch_gqa_w(const GqaArgs& A, int n_seq, size_t lds, hipStream_t st, hipEvent_t ev_start,
+template <int D, int NW, bool SPLIT>
+hipError_t launch_gqa_w(const GqaArgs& A, int n_seq, int n_chunks, size_t lds, hipStream_t st, hipEvent_t ev_start,
                         hipEvent_t ev_stop) {
-  dim3 grid(A.n_heads, n_seq);     // (lists that need more than 64 KB of LDS: see gqa_prepare_kernels)
+  dim3 grid(A.n_heads, n_seq, n_chunks);     // (lists that need more than 64 KB of LDS: see gqa_prepare_kernels)
   const int hgf = A.n_heads | (A.G << 16) | (A.append ? 1 << 24 : 0) | (A.new_f32 ? 1 << 25 : 0);
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_attend_gqa<D, NW>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0,
+    hipExtLaunchKernelGGL((k_attend_gqa<D, NW, SPLIT>), grid, dim3(NW * kWave), (uint32_t)lds, st, ev_start, ev_stop, 0,
                           A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new, hgf, A.sel_cap, A);
   else
-    hipLaunchKernelGGL((k_attend_gqa<D, NW>), grid, dim3(NW * kWave), lds, st,
+    hipLaunchKernelGGL((k_attend_gqa<D, NW, SPLIT>), grid, dim3(NW * kWave), lds, st,
                        A.seqs, A.sel_idx, A.sel_cnt, A.q, A.k_new, A.v_new, hgf, A.sel_cap, A);
   return hipGetLastError();
 }
 
 template <int D>
-hipError_t launch_gqa_d(const GqaArgs& A, int waves, int n_seq, size_t lds, hipStream_t st, hipEvent_t e0,
+hipError_t launch_gqa_d(const GqaArgs& A, const AttendPlan& plan, int n_seq, size_t lds, hipStream_t st, hipEvent_t e0,
                         hipEvent_t e1) {
-  if (waves == 8) return launch_gqa_w<D, 8>(A, n_seq, lds, st, e0, e1);
-  return launch_gqa_w<D, 4>(A, n_seq, lds, st, e0, e1);
+  if (plan.n_chunks > 1) return launch_gqa_w<D, 4, true>(A, n_seq, plan.n_chunks, lds, st, e0, e1);     // split lists: 4 waves
+  if (plan.waves == 8) return launch_gqa_w<D, 8, false>(A, n_seq, 1, lds, st, e0, e1);
+  return launch_gqa_w<D, 4, false>(A, n_seq, 1, lds, st, e0, e1);
 }
 
 }  // namespace
@@ -449,15 +559,25 @@ hipError_t launch_gqa_d(const GqaArgs& A, int waves, int n_seq, size_t lds, hipS
 // here, at the library's first use of a device, not next to a launch (where it would also sit inside a captured graph).
 hipError_t gqa_prepare_kernels() {
   const int lim = (int)kGqaMaxLds;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<64, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<64, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<128, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attend_gqa<128, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, lim);
-  return e;
+  const void* kernels[] = {
+      reinterpret_cast<const void*>(&k_attend_gqa<64, 4, false>), reinterpret_cast<const void*>(&k_attend_gqa<64, 8, false>),
+      reinterpret_cast<const void*>(&k_attend_gqa<128, 4, false>), reinterpret_cast<const void*>(&k_attend_gqa<128, 8, false>),
+      reinterpret_cast<const void*>(&k_attend_gqa<64, 4, true>), reinterpret_cast<const void*>(&k_attend_gqa<128, 4, true>)};
+  for (const void* k : kernels) {
+    const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 
-int gqa_logit_stride(const adsa_params& p) { return (p.sel_cap + 15) / 16 * 16 + 16; }
+// row stride of the logits one workgroup keeps in LDS: the tokens of its chunk (whole tiles) + one tile of slack
+int gqa_logit_stride(const adsa_params& p, int n_chunks) {
+  const int tiles = (p.sel_cap + 15) / 16;
+  return ((tiles + n_chunks - 1) / n_chunks) * 16 + 16;
+}
+// row stride of the logits in the workspace (split launches)
+int gqa_global_logit_stride(const adsa_params& p) { return (p.sel_cap + 15) / 16 * 16 + 16; }
 
 // LDS each wave owns: a staged K tile [16][D*2+16 bytes], reused for its partial output [G][D] floats
 static size_t gqa_stage_bytes(const adsa_params& p) {
@@ -465,20 +585,27 @@ static size_t gqa_stage_bytes(const adsa_params& p) {
   return tile > part ? tile : part;
 }
 
-size_t gqa_lds_bytes(const adsa_params& p, int waves) {
-  const size_t lgs = (size_t)gqa_logit_stride(p);
+size_t gqa_lds_bytes(const adsa_params& p, int waves, int n_chunks) {
+  const size_t lgs = (size_t)gqa_logit_stride(p, n_chunks);
   return ((size_t)p.q_per_kv + 1) * lgs * sizeof(float) + (size_t)waves * gqa_stage_bytes(p);
 }
 
 hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_seq* seqs, const void* q,
                              const void* k_new, const void* v_new, const int32_t* sel_idx,
-                             const int32_t* sel_cnt, void* out, float* lse, bool accumulate, bool append,
-                             bool advance, bool new_f32, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                             const int32_t* sel_cnt, void* out, float* lse, char* ws, const Workspace& w,
+                             bool accumulate, bool append, bool advance, bool new_f32, hipStream_t st,
+                             hipEvent_t ev_start, hipEvent_t ev_stop) {
   if (p.dtype != ADSA_BF16 || p.q_per_kv < 2 || p.q_per_kv > 16) return hipErrorInvalidValue;
+  if (plan.n_chunks < 1 || plan.n_chunks > kMaxChunks) return hipErrorInvalidValue;
   GqaArgs A;
   A.seqs = seqs; A.q = (const char*)q; A.k_new = (const char*)k_new; A.v_new = (const char*)v_new;
   A.sel_idx = sel_idx; A.sel_cnt = sel_cnt; A.out = (char*)out; A.lse = lse;
-  A.n_heads = p.n_heads; A.G = p.q_per_kv; A.sel_cap = p.sel_cap; A.lg_stride = gqa_logit_stride(p);
+  A.logits = reinterpret_cast<float*>(ws + w.logits_off);
+  A.part_ml = reinterpret_cast<float*>(ws + w.part_ml_off);
+  A.part_acc = reinterpret_cast<float*>(ws + w.part_acc_off);
+  A.counters = reinterpret_cast<int32_t*>(ws + w.counters_off);
+  A.lg_global = gqa_global_logit_stride(p);
+  A.n_heads = p.n_heads; A.G = p.q_per_kv; A.sel_cap = p.sel_cap; A.lg_stride = gqa_logit_stride(p, plan.n_chunks);
   A.cap = p.cap; A.stage_b = (int)gqa_stage_bytes(p);
   A.accumulate = accumulate ? 1 : 0; A.append = append ? 1 : 0; A.advance = advance ? 1 : 0;
   A.new_f32 = (new_f32 && append) ? 1 : 0;
@@ -486,10 +613,10 @@ hipError_t launch_attend_gqa(const adsa_params& p, const AttendPlan& plan, adsa_
   A.head_stride_b = (long long)p.kv_head_stride * 2;
   const float scale = p.softmax_scale != 0.0f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
   A.scale_log2 = scale * kLog2e;
-  const size_t lds = gqa_lds_bytes(p, plan.waves);
+  const size_t lds = gqa_lds_bytes(p, plan.waves, plan.n_chunks);
   if (lds > kGqaMaxLds) return hipErrorInvalidValue;
-  if (p.head_dim == 64) return launch_gqa_d<64>(A, plan.waves, p.n_seq, lds, st, ev_start, ev_stop);
-  if (p.head_dim == 128) return launch_gqa_d<128>(A, plan.waves, p.n_seq, lds, st, ev_start, ev_stop);
+  if (p.head_dim == 64) return launch_gqa_d<64>(A, plan, p.n_seq, lds, st, ev_start, ev_stop);
+  if (p.head_dim == 128) return launch_gqa_d<128>(A, plan, p.n_seq, lds, st, ev_start, ev_stop);
   return hipErrorInvalidValue;
 }
 
