@@ -396,6 +396,15 @@ def workload_text(wl, n_layers, args, job_params, replicas):
     return txt
 
 
+def other_algorithmic_bytes(wl, att_bytes, n_launch):
+    e = 2 if wl.dtype == "bf16" else 4
+    tokens = att_bytes / wl.token_bytes / max(1, n_launch)              # attended tokens per launch, all sequences
+    per_token = 4 + (8 * wl.n_heads if wl.score_mode == 0 else 0)
+    hq = wl.n_heads * max(wl.q_per_kv, 1)
+    per_seq = 2 * hq * wl.head_dim * e + 2 * wl.n_heads * wl.head_dim * e + 4 * hq
+    return tokens * per_token + wl.n_seq * per_seq
+
+
 def roofline_block(wl, att_bytes, n_launch, att_ms, flops=None):
     achieved = att_bytes / (att_ms * 1e-3) / 1e9
     ratio = measured_traffic_ratio(wl.name)
@@ -407,6 +416,10 @@ def roofline_block(wl, att_bytes, n_launch, att_ms, flops=None):
         f"profiles/{wl.name}_attend_hbm_traffic.txt: measured HBM bytes / algorithmic bytes = {ratio} x this run's bytes per launch",
         "launches": int(n_launch), "avg_launch_us": 1e3 * att_ms / max(1, n_launch),
         "algorithmic_bytes_per_launch": att_bytes / max(1, n_launch),
+        # what else one launch must move, by the same kind of count: per attended token its slot-list entry (4 B) and,
+        # with attention-mass ranking, one score word read and written per cache head; per sequence q, out, the
+        # appended k/v rows and lse
+        "other_algorithmic_bytes_per_launch": other_algorithmic_bytes(wl, att_bytes, n_launch),
     }
     if flops is not None:        # the contraction runs on the matrix cores: 4 flops per (query head, token, column)
         r["mfma_tflops"] = flops / (att_ms * 1e-3) / 1e12
